@@ -1,0 +1,493 @@
+"""Plain CPU oracle for the MORLAX rollout-and-update step.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, obviously-correct definition that the HIP kernels are
+checked against.  It may be imported only by `tests/`, by
+`__graft_entry__.smoke()` and by the `cpu_baseline` leg of `bench.py`; the
+product path never calls it and shares no code with it.
+
+All arithmetic is numpy float64.  Inputs are whatever the caller passes (the
+tests pass the float32 tensors of the seeded generator); outputs are float64
+arrays which the tests compare with the GPU's float32 results.
+
+Symbols: K objectives (paper: m), P distinct trade-off vectors (paper: K),
+N environments in P contiguous groups of n_g = N / P (Sec. III-C, sampling
+phase), T rollout horizon, O / A observation / action width, F hypernet
+feature width, r factor rank.
+
+Every function names the passage of the paper it follows.  Where the paper
+is silent the reading taken is stated next to the code (and collected in the
+design notes): the hypernet emits rank-r factors added to shared base
+weights; the trunk f is a two-layer tanh MLP; the Gaussian log-std is state
+independent and produced by the actor hypernet; the actor mean is tanh(z);
+GAE is the textbook recursion with `done` as a select; advantages are
+scalarised then normalised over the minibatch with population std + 1e-8;
+losses carry no extra coefficients and no entropy term.
+
+Pinned by tests/test_oracle_*.py: closed forms and brute force for GAE,
+float64 torch.autograd and central finite differences for every gradient,
+library routines (torch linear/tanh/silu, torch Normal.log_prob) for the
+forward pieces, structural invariants for the hypernet.  Not pinned
+("parity unpinned"): which of the readings above the authors' own code uses,
+because that code is not available.
+"""
+from __future__ import annotations
+
+import math
+from collections import OrderedDict
+
+import numpy as np
+
+ACTOR, CRITIC = 0, 1
+ACT_TANH, ACT_SILU = 0, 1
+
+
+# --------------------------------------------------------------------------- shapes
+
+def layer_shapes(d, net):
+    """(d_out, d_in) per dense layer: O -> W, (W -> W) x (L-1), W -> A (actor) or K (critic)."""
+    out = d.act_dim if net == ACTOR else d.K
+    widths = [d.obs_dim] + [d.width] * d.n_hidden + [out]
+    return [(widths[i + 1], widths[i]) for i in range(len(widths) - 1)]
+
+
+def theta_mat_len(d, net):
+    return sum(do * di for do, di in layer_shapes(d, net))
+
+
+def theta_vec_len(d, net):
+    n = sum(do for do, _ in layer_shapes(d, net))
+    return n + (d.act_dim if net == ACTOR else 0)
+
+
+def hparam_layout(d, net):
+    """name -> (offset, shape) of each hypernet parameter block in the flat vector."""
+    K, F, r = d.K, d.hyper_width, d.rank
+    lay, off = OrderedDict(), 0
+
+    def add(name, shape):
+        nonlocal off
+        lay[name] = (off, shape)
+        off += int(np.prod(shape))
+
+    add("Wh1", (F, K)); add("bh1", (F,)); add("Wh2", (F, F)); add("bh2", (F,))
+    for l, (do, di) in enumerate(layer_shapes(d, net)):
+        add(f"W0_{l}", (do, di)); add(f"b0_{l}", (do,))
+        add(f"MA_{l}", (do * r, F)); add(f"cA_{l}", (do * r,))
+        add(f"MB_{l}", (r * di, F)); add(f"cB_{l}", (r * di,))
+        add(f"Mb_{l}", (do, F))
+    if net == ACTOR:
+        add("logsig0", (d.act_dim,)); add("Msig", (d.act_dim, F))
+    lay["_total"] = (off, ())
+    return lay
+
+
+def hparam_count(d, net):
+    return hparam_layout(d, net)["_total"][0]
+
+
+def _unpack(d, net, flat):
+    flat = np.asarray(flat, dtype=np.float64).reshape(-1)
+    lay = hparam_layout(d, net)
+    assert flat.size == lay["_total"][0], "hparams length"
+    return {k: flat[o:o + int(np.prod(s))].reshape(s) for k, (o, s) in lay.items() if k != "_total"}
+
+
+def env_pref_index(N, P):
+    """g(n): index of the trade-off vector environment n rolls out (Sec. III-C, sampling phase:
+    each of the P vectors is repeated N/P times in contiguous blocks).  P > 1 and P | N."""
+    if not (P > 1 and N % P == 0):
+        raise ValueError("need P > 1 and P | N")
+    n_g = N // P
+    return (np.arange(N, dtype=np.int64) // n_g).astype(np.int32)
+
+
+def check_preferences(w, tol=1e-6):
+    """Sec. III-A: every trade-off vector lies on the simplex."""
+    w = np.asarray(w, dtype=np.float64)
+    return bool(np.all(w >= 0.0) and np.all(np.abs(w.sum(axis=1) - 1.0) <= tol))
+
+
+def round_bf16(x):
+    """float -> nearest bfloat16 (ties to even), returned as float64."""
+    f = np.ascontiguousarray(np.asarray(x, dtype=np.float32))
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) & np.uint64(0xFFFF0000)
+    out = u.astype(np.uint32).view(np.float32)
+    out = np.where(np.isnan(f), f, out)
+    return out.astype(np.float64)
+
+
+def _act(z, kind):
+    if kind == ACT_TANH:
+        return np.tanh(z)
+    return z / (1.0 + np.exp(-z))
+
+
+def _dact(z, kind):
+    if kind == ACT_TANH:
+        return 1.0 - np.tanh(z) ** 2
+    s = 1.0 / (1.0 + np.exp(-z))
+    return s * (1.0 + z * (1.0 - s))
+
+
+# --------------------------------------------------------------------------- hypernetwork
+
+def _hyper_cache(d, net, hparams, w):
+    hp = _unpack(d, net, hparams)
+    w = np.asarray(w, dtype=np.float64)
+    h1 = np.tanh(w @ hp["Wh1"].T + hp["bh1"])
+    f = np.tanh(h1 @ hp["Wh2"].T + hp["bh2"])
+    return hp, w, h1, f
+
+
+def hypernet_fwd(d, net, hparams, w):
+    """H(w) = M f(w) + b (Sec. III-B), read as: f a two-layer tanh MLP K -> F -> F; the affine map
+    emits, per target layer l, factors A_l [d_out, r] and B_l [r, d_in] and a bias delta, and the
+    layer's weights are W_l = W0_l + A_l B_l, b_l = b0_l + Mb_l f; the actor also gets
+    log sigma = logsig0 + Msig f.  Returns theta_mat [P, mat_len] (layers concatenated, each
+    [d_out, d_in] row-major) and theta_vec [P, vec_len] (biases, then the actor's log sigma)."""
+    hp, w, h1, f = _hyper_cache(d, net, hparams, w)
+    P, r = w.shape[0], d.rank
+    mats, vecs = [], []
+    for l, (do, di) in enumerate(layer_shapes(d, net)):
+        A = (f @ hp[f"MA_{l}"].T + hp[f"cA_{l}"]).reshape(P, do, r)
+        B = (f @ hp[f"MB_{l}"].T + hp[f"cB_{l}"]).reshape(P, r, di)
+        W = hp[f"W0_{l}"][None] + np.einsum("pok,pki->poi", A, B)
+        mats.append(W.reshape(P, do * di))
+        vecs.append(hp[f"b0_{l}"][None] + f @ hp[f"Mb_{l}"].T)
+    if net == ACTOR:
+        vecs.append(hp["logsig0"][None] + f @ hp["Msig"].T)
+    return np.concatenate(mats, axis=1), np.concatenate(vecs, axis=1)
+
+
+def hypernet_bwd(d, net, hparams, w, dtheta_mat, dtheta_vec):
+    """Reverse mode of `hypernet_fwd`: gradient of a scalar with respect to the flat hypernet
+    parameters, given its gradient with respect to every preference's theta (Sec. III-C update
+    phase: the loss is differentiated back into the hypernetwork)."""
+    hp, w, h1, f = _hyper_cache(d, net, hparams, w)
+    P, r = w.shape[0], d.rank
+    lay = hparam_layout(d, net)
+    g = np.zeros(lay["_total"][0], dtype=np.float64)
+
+    def put(name, val):
+        o, s = lay[name]
+        g[o:o + int(np.prod(s))] = np.asarray(val, dtype=np.float64).reshape(-1)
+
+    dtheta_mat = np.asarray(dtheta_mat, dtype=np.float64)
+    dtheta_vec = np.asarray(dtheta_vec, dtype=np.float64)
+    df = np.zeros_like(f)
+    moff = voff = 0
+    for l, (do, di) in enumerate(layer_shapes(d, net)):
+        A = (f @ hp[f"MA_{l}"].T + hp[f"cA_{l}"]).reshape(P, do, r)
+        B = (f @ hp[f"MB_{l}"].T + hp[f"cB_{l}"]).reshape(P, r, di)
+        dW = dtheta_mat[:, moff:moff + do * di].reshape(P, do, di)
+        db = dtheta_vec[:, voff:voff + do]
+        moff += do * di
+        voff += do
+        put(f"W0_{l}", dW.sum(axis=0))
+        put(f"b0_{l}", db.sum(axis=0))
+        dA = np.einsum("poi,pki->pok", dW, B).reshape(P, do * r)
+        dB = np.einsum("pok,poi->pki", A, dW).reshape(P, r * di)
+        put(f"MA_{l}", dA.T @ f); put(f"cA_{l}", dA.sum(axis=0))
+        put(f"MB_{l}", dB.T @ f); put(f"cB_{l}", dB.sum(axis=0))
+        put(f"Mb_{l}", db.T @ f)
+        df += dA @ hp[f"MA_{l}"] + dB @ hp[f"MB_{l}"] + db @ hp[f"Mb_{l}"]
+    if net == ACTOR:
+        dls = dtheta_vec[:, voff:voff + d.act_dim]
+        put("logsig0", dls.sum(axis=0)); put("Msig", dls.T @ f)
+        df += dls @ hp["Msig"]
+    dz2 = df * (1.0 - f * f)
+    put("Wh2", dz2.T @ h1); put("bh2", dz2.sum(axis=0))
+    dz1 = (dz2 @ hp["Wh2"]) * (1.0 - h1 * h1)
+    put("Wh1", dz1.T @ w); put("bh1", dz1.sum(axis=0))
+    return g
+
+
+# --------------------------------------------------------------------------- grouped target networks
+
+def full_rows(d, t_cnt):
+    return (0, int(t_cnt), 0, d.N // d.P)
+
+
+def row_mask(d, rows, t_total):
+    """Boolean [t_total, N]: the (t, n) cells a row selection covers.  rows = (t0, t_cnt, j0,
+    j_cnt) selects times [t0, t0+t_cnt) and, in every preference group, the environments whose
+    position inside the group lies in [j0, j0+j_cnt)."""
+    t0, tc, j0, jc = rows
+    n_g = d.N // d.P
+    m = np.zeros((t_total, d.N), dtype=bool)
+    j = np.arange(d.N) % n_g
+    m[t0:t0 + tc, :] = ((j >= j0) & (j < j0 + jc))[None, :]
+    return m
+
+
+def _split_theta(d, net, theta_mat, theta_vec, p):
+    Ws, bs, moff, voff = [], [], 0, 0
+    for do, di in layer_shapes(d, net):
+        Ws.append(np.asarray(theta_mat[p, moff:moff + do * di], dtype=np.float64).reshape(do, di))
+        bs.append(np.asarray(theta_vec[p, voff:voff + do], dtype=np.float64))
+        moff += do * di
+        voff += do
+    logsig = np.asarray(theta_vec[p, voff:voff + d.act_dim], dtype=np.float64) if net == ACTOR else None
+    return Ws, bs, logsig
+
+
+def _group_env_index(d, rows, p):
+    _, _, j0, jc = rows
+    n_g = d.N // d.P
+    return p * n_g + j0 + np.arange(jc)
+
+
+def _mlp_forward(d, net, Ws, bs, X, emulate_bf16):
+    """Sec. III-B / III-E: hidden layers h_l = act(W_l h_{l-1} + b_l); actor mean tanh(z) (actuator
+    limits), critic output the K-vector z.  With emulate_bf16 every GEMM input activation is
+    rounded to bfloat16 on entry (the weights arrive already rounded)."""
+    hs, zs = [X], []
+    nl = len(Ws)
+    for l in range(nl):
+        hin = round_bf16(hs[-1]) if emulate_bf16 else hs[-1]
+        z = hin @ Ws[l].T + bs[l]
+        zs.append(z)
+        if l < nl - 1:
+            hs.append(_act(z, d.act))
+    z = zs[-1]
+    out = np.tanh(z) if (net == ACTOR and d.mean_tanh) else z
+    return hs, zs, out
+
+
+def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=False):
+    """Rollout-phase forward of the family {pi_i} or {V_i} (Sec. III-C): environment n is served by
+    the network of preference g(n).  x is [Tx, N, O]; returns `out` [Tx, N, A or K] and, when the
+    Gaussian noise eps [Tx, N, A] is given (actor only), the sampled action a = mu + sigma * eps
+    and its log-density log p = sum_j [ -((a_j - mu_j)/sigma_j)^2 / 2 - log sigma_j ] - (A/2) log 2 pi.
+    Cells outside `rows` stay zero."""
+    x = np.asarray(x, dtype=np.float64)
+    Tx = x.shape[0]
+    t0, tc, j0, jc = rows
+    odim = d.act_dim if net == ACTOR else d.K
+    out = np.zeros((Tx, d.N, odim))
+    act = logp = None
+    if eps is not None:
+        assert net == ACTOR
+        eps = np.asarray(eps, dtype=np.float64)
+        act = np.zeros((Tx, d.N, d.act_dim))
+        logp = np.zeros((Tx, d.N))
+    for p in range(d.P):
+        Ws, bs, logsig = _split_theta(d, net, theta_mat, theta_vec, p)
+        idx = _group_env_index(d, rows, p)
+        X = x[t0:t0 + tc][:, idx, :].reshape(tc * jc, d.obs_dim)
+        _, _, o = _mlp_forward(d, net, Ws, bs, X, emulate_bf16)
+        o = o.reshape(tc, jc, odim)
+        out[t0:t0 + tc, idx[0]:idx[0] + jc, :] = o
+        if eps is not None:
+            sig = np.exp(logsig)
+            e = eps[t0:t0 + tc, idx[0]:idx[0] + jc, :]
+            a = o + sig * e
+            act[t0:t0 + tc, idx[0]:idx[0] + jc, :] = a
+            logp[t0:t0 + tc, idx[0]:idx[0] + jc] = gaussian_logp(a, o, logsig)
+    return out, act, logp
+
+
+def gaussian_logp(a, mu, logsig):
+    """Log-density of a diagonal Gaussian N(mu, diag(exp(logsig))^2) at a, summed over action dims."""
+    sig = np.exp(logsig)
+    q = (a - mu) / sig
+    A = a.shape[-1]
+    return (-0.5 * q * q - logsig).sum(axis=-1) - 0.5 * A * math.log(2.0 * math.pi)
+
+
+def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulate_bf16=False,
+               want_dx=False):
+    """Reverse mode through the grouped target networks: given dL/d(out) on the selected rows,
+    returns dL/dtheta_mat [P, mat_len] and dL/dtheta_vec [P, vec_len] (bias gradients, then for the
+    actor the given dL/dlogsig [P, A] copied through).  dW_l(p) = dZ_l^T H_{l-1} over the rows of
+    preference p, db_l(p) = column sums of dZ_l, dH_{l-1} = dZ_l W_l(p), dZ = dH * act'(z).
+    With emulate_bf16 both operands of every GEMM are rounded to bfloat16 on entry."""
+    x = np.asarray(x, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    t0, tc, j0, jc = rows
+    odim = d.act_dim if net == ACTOR else d.K
+    dmat = np.zeros((d.P, theta_mat_len(d, net)))
+    dvec = np.zeros((d.P, theta_vec_len(d, net)))
+    dx = np.zeros_like(x) if want_dx else None
+    rb = round_bf16 if emulate_bf16 else (lambda a: a)
+    for p in range(d.P):
+        Ws, bs, _ = _split_theta(d, net, theta_mat, theta_vec, p)
+        idx = _group_env_index(d, rows, p)
+        X = x[t0:t0 + tc][:, idx, :].reshape(tc * jc, d.obs_dim)
+        hs, zs, o = _mlp_forward(d, net, Ws, bs, X, emulate_bf16)
+        dz = dout[t0:t0 + tc][:, idx, :].reshape(tc * jc, odim)
+        if net == ACTOR and d.mean_tanh:
+            dz = dz * (1.0 - o * o)
+        gW, gb = [None] * len(Ws), [None] * len(Ws)
+        for l in range(len(Ws) - 1, -1, -1):
+            gW[l] = rb(dz).T @ rb(hs[l])
+            gb[l] = dz.sum(axis=0)
+            if l > 0 or want_dx:
+                dh = rb(dz) @ Ws[l]
+                if l > 0:
+                    dz = dh * _dact(zs[l - 1], d.act)
+                else:
+                    dx[t0:t0 + tc, idx[0]:idx[0] + jc, :] = dh.reshape(tc, jc, d.obs_dim)
+        dmat[p] = np.concatenate([g.reshape(-1) for g in gW])
+        vec = np.concatenate(gb)
+        dvec[p, :vec.size] = vec
+    if net == ACTOR and dlogsig is not None:
+        dvec[:, -d.act_dim:] = np.asarray(dlogsig, dtype=np.float64)
+    if want_dx:
+        return dmat, dvec, dx
+    return dmat, dvec
+
+
+# --------------------------------------------------------------------------- advantage estimation
+
+def vec_gae(r, v, done, w, gamma, lam):
+    """Generalised advantage estimation applied to each objective on its own, then scalarised with
+    the environment's trade-off vector (Sec. III-C, update phase).  r [T,N,K], v [T+1,N,K],
+    done [T,N] (1: the transition at step t ended the episode), w [P,K].  Backward in time,
+    per (n, k): if done: delta = r_t - V_t and the running sum restarts at delta; otherwise
+    delta = r_t + gamma V_{t+1} - V_t and A_t = delta + gamma lam A_{t+1}; A_T = 0.
+    Value target Vhat_t = A_t + V_t.  Scalar advantage A^s[t,n] = sum_k w[g(n),k] A_t[n,k].
+    `done` acts as a select, so nothing after an episode end can reach the steps before it."""
+    r = np.asarray(r, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    done = np.asarray(done)
+    w = np.asarray(w, dtype=np.float64)
+    T, N, K = r.shape
+    P = w.shape[0]
+    g = env_pref_index(N, P)
+    adv = np.zeros((T, N, K))
+    acc = np.zeros((N, K))
+    for t in range(T - 1, -1, -1):
+        dn = (done[t] != 0)[:, None]
+        delta_live = r[t] + gamma * v[t + 1] - v[t]
+        delta_done = r[t] - v[t]
+        acc = np.where(dn, delta_done, delta_live + gamma * lam * acc)
+        adv[t] = acc
+    vtarg = adv + v[:T]
+    wn = w[g]                                  # [N, K]
+    adv_s = np.zeros((T, N))
+    for k in range(K):
+        adv_s += adv[:, :, k] * wn[None, :, k]
+    return adv, vtarg, adv_s
+
+
+def adv_norm_stats(adv_s, mask):
+    """Mean and population standard deviation of the scalarised advantage over the minibatch."""
+    a = np.asarray(adv_s, dtype=np.float64)[mask]
+    m = a.mean()
+    s = math.sqrt(((a - m) ** 2).mean())
+    return m, s
+
+
+# --------------------------------------------------------------------------- losses
+
+def ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv=True):
+    """Clipped PPO surrogate and vector value loss on one minibatch with their gradients
+    (Sec. III-C, update phase).  With B the number of selected (t, n) cells:
+      Ahat = (A^s - mean) / (std + 1e-8) over the minibatch (if norm_adv),
+      rho  = exp(log pi_theta(a|s) - log pi_old(a|s)),
+      L_pi = -(1/B) sum min(rho Ahat, clip(rho, 1-eps, 1+eps) Ahat),
+      L_V  = (1/B) sum_rows sum_k (V_k - Vhat_k)^2.
+    Ahat, Vhat, log pi_old and the actions are constants.  Gradients: the clipped branch is flat,
+    so dL/dlogp = -(1/B) Ahat rho where (Ahat >= 0 and rho <= 1+eps) or (Ahat < 0 and rho >= 1-eps),
+    else 0; dlogp/dmu_j = (a_j - mu_j)/sigma_j^2; dlogp/dlogsig_j = ((a_j-mu_j)/sigma_j)^2 - 1,
+    summed over the rows of each preference; dL_V/dV_k = 2 (V_k - Vhat_k) / B.
+    Returns dmu [Tx,N,A], dlogsig [P,A], dv [Tx,N,K] (zero outside the rows) and
+    stats = [L_pi, L_V, clip fraction, mean(logp_old - logp), adv mean, adv std, mean rho, B]."""
+    mu = np.asarray(mu, dtype=np.float64); act = np.asarray(act, dtype=np.float64)
+    logp_old = np.asarray(logp_old, dtype=np.float64); adv_s = np.asarray(adv_s, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64); vtarg = np.asarray(vtarg, dtype=np.float64)
+    logsig = np.asarray(logsig, dtype=np.float64)
+    Tx = mu.shape[0]
+    mask = row_mask(d, rows, Tx)
+    B = int(mask.sum())
+    g = env_pref_index(d.N, d.P)
+    ls = logsig[g][None, :, :]                                  # [1, N, A]
+    sig = np.exp(ls)
+    if norm_adv:
+        m, s = adv_norm_stats(adv_s[:Tx], mask)
+        ahat = (adv_s[:Tx] - m) / (s + 1e-8)
+    else:
+        m, s = adv_norm_stats(adv_s[:Tx], mask)
+        ahat = adv_s[:Tx].copy()
+    q = (act - mu) / sig
+    logp = (-0.5 * q * q - ls).sum(axis=-1) - 0.5 * d.act_dim * math.log(2.0 * math.pi)
+    rho = np.exp(logp - logp_old[:Tx])
+    surr = np.minimum(rho * ahat, np.clip(rho, 1.0 - clip_eps, 1.0 + clip_eps) * ahat)
+    L_pi = -(surr[mask].sum()) / B
+    dv_all = v[:Tx] - vtarg[:Tx]
+    L_V = (dv_all ** 2).sum(axis=-1)[mask].sum() / B
+    live = np.where(ahat >= 0.0, rho <= 1.0 + clip_eps, rho >= 1.0 - clip_eps)
+    dlogp = np.where(live & mask, -ahat * rho / B, 0.0)       # [Tx, N]
+    dmu = np.where(mask[..., None], dlogp[..., None] * q / sig, 0.0)
+    dls_rows = np.where(mask[..., None], dlogp[..., None] * (q * q - 1.0), 0.0)   # [Tx, N, A]
+    dlogsig = np.zeros((d.P, d.act_dim))
+    for p in range(d.P):
+        sel = (g == p)
+        dlogsig[p] = dls_rows[:, sel, :].sum(axis=(0, 1))
+    dv = np.where(mask[..., None], 2.0 * dv_all / B, 0.0)
+    clipped = (np.abs(rho - 1.0) > clip_eps)
+    stats = np.array([L_pi, L_V, clipped[mask].mean(), (logp_old[:Tx] - logp)[mask].mean(),
+                      m, s, rho[mask].mean(), float(B)])
+    return dmu, dlogsig, dv, stats
+
+
+# --------------------------------------------------------------------------- one update step
+
+def minibatch_rows(d, T, b, MB):
+    """Minibatch b of MB: every time step, and in each preference group the b-th slice of n_g / MB
+    environments, so every minibatch holds every preference."""
+    n_g = d.N // d.P
+    if n_g % MB:
+        raise ValueError("MB must divide n_g")
+    return (0, T, b * (n_g // MB), n_g // MB)
+
+
+def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rewards, dones, eps,
+                gamma, lam, clip_eps, minibatches=1, epochs=1, emulate_bf16=False, keep=False):
+    """One MORLAX iteration after the trade-offs are drawn (Sec. III-C): rollout forward of the
+    actor family (sampling actions and their log-density) and of the critic family at every state,
+    vector GAE, then for every epoch and minibatch the losses and their gradients with respect to
+    both hypernets.  The actor loss reaches only the actor hypernet and the value loss only the
+    critic hypernet (decoupled updates).  No optimiser step is taken, so every minibatch is
+    evaluated at the same update-time parameters.  Returns a dict; with keep=True it also holds
+    the intermediate tensors."""
+    T = rewards.shape[0]
+    wq = (lambda m: round_bf16(m)) if (emulate_bf16 and d.wdtype == 1) else (lambda m: m)
+    emu = bool(emulate_bf16 and d.wdtype == 1)
+    res = {}
+    tm_a0, tv_a0 = hypernet_fwd(d, ACTOR, hp_actor_old, w)
+    tm_c0, tv_c0 = hypernet_fwd(d, CRITIC, hp_critic_old, w)
+    tm_a0, tm_c0 = wq(tm_a0), wq(tm_c0)
+    mu_old, act, logp_old = policy_fwd(d, ACTOR, tm_a0, tv_a0, obs[:T], full_rows(d, T), eps=eps,
+                                       emulate_bf16=emu)
+    v_roll, _, _ = policy_fwd(d, CRITIC, tm_c0, tv_c0, obs, full_rows(d, T + 1), emulate_bf16=emu)
+    adv_vec, vtarg, adv_s = vec_gae(rewards, v_roll, dones, w, gamma, lam)
+    grads = []
+    for e in range(epochs):
+        for b in range(minibatches):
+            rows = minibatch_rows(d, T, b, minibatches)
+            tm_a, tv_a = hypernet_fwd(d, ACTOR, hp_actor, w)
+            tm_c, tv_c = hypernet_fwd(d, CRITIC, hp_critic, w)
+            tm_a, tm_c = wq(tm_a), wq(tm_c)
+            mu, _, _ = policy_fwd(d, ACTOR, tm_a, tv_a, obs[:T], rows, emulate_bf16=emu)
+            vv, _, _ = policy_fwd(d, CRITIC, tm_c, tv_c, obs[:T], rows, emulate_bf16=emu)
+            logsig = tv_a[:, -d.act_dim:]
+            dmu, dlogsig, dv, stats = ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, vv,
+                                                    vtarg, clip_eps, True)
+            dm_a, dvec_a = policy_bwd(d, ACTOR, tm_a, tv_a, obs[:T], rows, dmu, dlogsig, emulate_bf16=emu)
+            dm_c, dvec_c = policy_bwd(d, CRITIC, tm_c, tv_c, obs[:T], rows, dv, None, emulate_bf16=emu)
+            g_a = hypernet_bwd(d, ACTOR, hp_actor, w, dm_a, dvec_a)
+            g_c = hypernet_bwd(d, CRITIC, hp_critic, w, dm_c, dvec_c)
+            grads.append({"rows": rows, "dhp_actor": g_a, "dhp_critic": g_c, "stats": stats})
+            if keep and e == 0 and b == 0:
+                res.update(mu=mu, v=vv, dmu=dmu, dlogsig=dlogsig, dv=dv, dtheta_mat_actor=dm_a,
+                           dtheta_vec_actor=dvec_a, dtheta_mat_critic=dm_c, dtheta_vec_critic=dvec_c,
+                           theta_mat_actor=tm_a, theta_vec_actor=tv_a, theta_mat_critic=tm_c,
+                           theta_vec_critic=tv_c)
+    res["grads"] = grads
+    if keep:
+        res.update(mu_old=mu_old, act=act, logp_old=logp_old, v_roll=v_roll, adv_vec=adv_vec,
+                   vtarg=vtarg, adv_s=adv_s)
+    return res
