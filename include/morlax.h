@@ -1,0 +1,163 @@
+/*
+ * morlax.h -- C ABI of the MI355X (gfx950) hot path of MORLAX: the preference-conditioned
+ * rollout-and-update step over N parallel environments (paper Sec. III-A..III-C, III-E).
+ *
+ * Symbols.  K objectives (the paper's m); P distinct trade-off vectors per iteration (the paper's
+ * K); N environments split into P contiguous groups of n_g = N / P, environment n using trade-off
+ * g(n) = n / n_g (Sec. III-C, sampling phase); T rollout horizon; O / A observation / action
+ * width; target networks with L hidden layers of width W; F hypernet feature width; r factor rank.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller, contiguous, 16-byte aligned.
+ *    The library allocates no device memory and frees none.  `ws` is caller-provided device
+ *    scratch of at least morlax_workspace_bytes(); its contents are undefined between calls.
+ *  - `stream` is a hipStream_t passed as void*.  Every op only enqueues kernels on it and returns;
+ *    nothing synchronises.  Calls that share `ws`, `saved` or outputs must be stream-ordered.
+ *  - Time-major layouts: x [Tx, N, O], out [Tx, N, A|K], r [T, N, K], done [T, N] ...; the row of
+ *    (t, n) is t * N + n.
+ *  - A row selection `morlax_rows` picks times [t0, t0+t_cnt) and, inside every preference group,
+ *    the environments at positions [j0, j0+j_cnt): every selection holds every preference, so the
+ *    per-preference (grouped) structure is kept.  Minibatch b of MB is {0, T, b*n_g/MB, n_g/MB}.
+ *    Outputs are overwritten on the selected cells and not touched elsewhere.
+ *  - Return value: MORLAX_OK or a negative morlax_status.  All argument checks run on the host
+ *    before the first HIP call; a failed check launches nothing.  morlax_last_error() gives the
+ *    message of the last failure on the calling thread.
+ *  - theta layout (per preference): theta_mat = the layers' weight matrices concatenated, layer l
+ *    stored [d_out, d_in] row-major (y = W x), element type fp32 or bf16 (dims.wdtype);
+ *    theta_vec (fp32) = the layers' biases concatenated, then for the actor log sigma [A].
+ *    Layers: O -> W, (W -> W) x (L-1), W -> A (actor) or K (critic).
+ *  - hparams layout (fp32, flat, every block row-major): trunk Wh1 [F,K], bh1 [F], Wh2 [F,F],
+ *    bh2 [F]; per target layer W0 [d_out,d_in], b0 [d_out], MA [d_out*r, F], cA [d_out*r],
+ *    MB [r*d_in, F], cB [r*d_in], Mb [d_out, F]; actor only: logsig0 [A], Msig [A, F].
+ */
+#ifndef MORLAX_H
+#define MORLAX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct morlax_ctx morlax_ctx; /* opaque: dimensions and derived layouts, no device memory */
+
+typedef enum { MORLAX_ACTOR = 0, MORLAX_CRITIC = 1 } morlax_net;
+
+typedef enum {
+    MORLAX_OK = 0,
+    MORLAX_ERR_NULL = -1,        /* a required pointer is NULL */
+    MORLAX_ERR_SHAPE = -2,       /* P < 2, P does not divide N, K < 1, bad row selection, misaligned pointer ... */
+    MORLAX_ERR_UNSUPPORTED = -3, /* a size outside what the kernels are built for */
+    MORLAX_ERR_WORKSPACE = -4,   /* reserved */
+    MORLAX_ERR_HIP = -5          /* a HIP runtime call failed */
+} morlax_status;
+
+typedef struct {
+    int32_t K, P, N, T;
+    int32_t obs_dim, act_dim;
+    int32_t n_hidden, width;
+    int32_t act;         /* hidden activation: 0 tanh, 1 SiLU */
+    int32_t rank;        /* r >= 0 */
+    int32_t hyper_width; /* F */
+    int32_t wdtype;      /* 0: fp32 weights and GEMM inputs; 1: bf16 weights and GEMM inputs, fp32 accumulate */
+    int32_t mean_tanh;   /* 1: actor mean = tanh(z) (Sec. III-E); 0: mean = z */
+} morlax_dims;
+
+typedef struct {
+    int32_t t0, t_cnt;
+    int32_t j0, j_cnt;
+} morlax_rows;
+
+/* Limits: 1 <= K <= 16, 1 <= act_dim <= 16, 1 <= obs_dim <= 1024, 1 <= n_hidden <= 8,
+ * width a multiple of 16 in [16, 2048], 0 <= rank <= 32, 1 <= hyper_width <= 64, P >= 2, P | N. */
+int morlax_create(const morlax_dims* dims, morlax_ctx** out);
+void morlax_destroy(morlax_ctx* ctx);
+const char* morlax_last_error(void); /* thread-local, never NULL */
+
+int64_t morlax_hparam_count(const morlax_ctx* ctx, int net);   /* floats in a hypernet's flat parameter vector */
+int64_t morlax_theta_mat_len(const morlax_ctx* ctx, int net);  /* weight elements per preference */
+int64_t morlax_theta_vec_len(const morlax_ctx* ctx, int net);  /* fp32 elements per preference */
+/* Bytes of the `saved` buffer policy_fwd fills for policy_bwd on this selection (rows NULL: all
+ * n_g environments and T+1 times). */
+int64_t morlax_saved_bytes(const morlax_ctx* ctx, int net, const morlax_rows* rows);
+/* Bytes of scratch sufficient for every op on this selection (rows NULL: as above). */
+int64_t morlax_workspace_bytes(const morlax_ctx* ctx, const morlax_rows* rows);
+
+/* g(n) = n / n_g for n in [0, N): the environment -> trade-off map (Sec. III-C, sampling phase:
+ * each trade-off repeated N/P times in contiguous blocks).  out [N] int32, device. */
+int morlax_env_pref_index(const morlax_ctx* ctx, int32_t* out, void* stream);
+
+/* Hypernetwork forward H(w) = M f(w) + b (Sec. III-B) for all P trade-offs: f is a two-layer tanh
+ * MLP K -> F -> F; the affine map emits per target layer the factors A_l [d_out, r], B_l [r, d_in]
+ * and a bias delta; W_l(p) = W0_l + A_l(p) B_l(p), b_l(p) = b0_l + Mb_l f(p); actor:
+ * log sigma(p) = logsig0 + Msig f(p).  All arithmetic fp32; theta_mat rounded once (nearest even)
+ * when dims.wdtype is bf16.
+ *   hparams [hparam_count] fp32, w [P, K] fp32 (rows on the simplex; not checked on the device)
+ *   -> theta_mat [P, theta_mat_len] (wdtype), theta_vec [P, theta_vec_len] fp32. */
+int morlax_hypernet_fwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
+                        void* theta_mat, float* theta_vec, void* ws, void* stream);
+
+/* Reverse mode of morlax_hypernet_fwd (Sec. III-C, update phase: the losses are differentiated
+ * back into each hypernetwork separately).  dtheta_mat [P, theta_mat_len] fp32 and dtheta_vec
+ * [P, theta_vec_len] fp32 are the loss gradients w.r.t. every preference's parameters;
+ * dhparams [hparam_count] fp32 is overwritten.  Reductions run in a fixed order (no atomics). */
+int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
+                        const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
+                        void* ws, void* stream);
+
+/* Grouped forward of the target-network family {pi_i} or {V_i} (Sec. III-C, rollout phase;
+ * Sec. III-E for the tanh on the actor output): every selected (t, n) row of x goes through the
+ * network of preference g(n).  Hidden layers h = act(W h + b); actor out = tanh(z) (or z when
+ * mean_tanh = 0), critic out = z in R^K.  With dims.wdtype = bf16 every GEMM input is bf16 and
+ * accumulation fp32; bias, activation and outputs are fp32.
+ *   x [Tx, N, O] fp32; out [Tx, N, A] (actor) or [Tx, N, K] (critic) fp32.
+ *   Actor only, all three or none: eps [Tx, N, A] standard normal noise -> act = out + sigma * eps
+ *   and logp [Tx, N] = sum_j [ -((act_j - out_j)/sigma_j)^2 / 2 - log sigma_j ] - (A/2) log(2 pi).
+ *   saved: NULL for inference/rollout, else morlax_saved_bytes() bytes that policy_bwd needs. */
+int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
+                      const float* x, const morlax_rows* rows, float* out, const float* eps,
+                      float* act, float* logp, void* saved, void* ws, void* stream);
+
+/* Grouped backward through the target networks (Sec. III-C, update phase).  dout [Tx, N, A|K] is
+ * dL/d(out) on the selected rows; `saved` comes from the matching policy_fwd call (same ctx, net,
+ * theta, x, rows).  Outputs, overwritten: dtheta_mat [P, theta_mat_len] fp32 with
+ * dW_l(p) = sum over p's rows of dZ_l^T h_{l-1}, and dtheta_vec [P, theta_vec_len] fp32 with the
+ * bias gradients followed (actor) by dlogsig [P, A] copied through (zeros when dlogsig is NULL). */
+int morlax_policy_bwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
+                      const float* x, const morlax_rows* rows, const void* saved, const float* dout,
+                      const float* dlogsig, float* dtheta_mat, float* dtheta_vec, void* ws,
+                      void* stream);
+
+/* Vector generalised advantage estimation, one reverse-time scan per (environment, objective),
+ * then scalarisation with the environment's trade-off (Sec. III-C, update phase).
+ *   r [T, N, K], v [T+1, N, K], done [T, N] u8 (non-zero: the transition at t ended the episode),
+ *   w [P, K].  Backwards from t = T-1 with A_T = 0:
+ *     done:  delta = r_t - V_t,                 A_t = delta
+ *     else:  delta = r_t + gamma V_{t+1} - V_t, A_t = delta + gamma lambda A_{t+1}
+ *   (`done` is a select: nothing after an episode end can influence the steps before it.)
+ *   -> vtarg [T, N, K] = A_t + V_t, adv_s [T, N] = sum_k w[g(n), k] A_t[n, k],
+ *      adv_vec [T, N, K] = A_t (optional, NULL to skip). */
+int morlax_vec_gae(morlax_ctx* ctx, const float* r, const float* v, const uint8_t* done,
+                   const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
+                   float* adv_s, void* stream);
+
+/* Clipped PPO surrogate and vector value loss with their gradients on one minibatch (Sec. III-C,
+ * update phase).  B = selected cells.  Ahat = (adv_s - mean) / (std + 1e-8) over the selection
+ * (population std) when norm_adv != 0, else adv_s.  logp = Gaussian log-density of act under
+ * (mu, sigma = exp(logsig[g(n)])); rho = exp(logp - logp_old);
+ *   L_pi = -(1/B) sum min(rho Ahat, clip(rho, 1-eps, 1+eps) Ahat);  L_V = (1/B) sum ||v - vtarg||^2.
+ *   mu, act [Tx, N, A]; logsig [P, A] with row stride logsig_stride floats (pass the tail of the
+ *   actor theta_vec and its row length); logp_old, adv_s [Tx, N]; v, vtarg [Tx, N, K].
+ *   -> dmu [Tx, N, A], dv [Tx, N, K] on the selected cells; dlogsig [P, A] (summed over each
+ *   preference's selected rows, fixed order); stats [8] fp32 on the device:
+ *   L_pi, L_V, fraction with |rho-1| > eps, mean(logp_old - logp), adv mean, adv std, mean rho, B. */
+int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
+                         const float* logsig, int32_t logsig_stride, const float* act,
+                         const float* logp_old, const float* adv_s, const float* v,
+                         const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
+                         float* dlogsig, float* dv, float* stats, void* ws, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MORLAX_H */

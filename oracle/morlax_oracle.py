@@ -255,12 +255,13 @@ def _mlp_forward(d, net, Ws, bs, X, emulate_bf16):
     return hs, zs, out
 
 
-def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=False):
+def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=False, prefs=None):
     """Rollout-phase forward of the family {pi_i} or {V_i} (Sec. III-C): environment n is served by
     the network of preference g(n).  x is [Tx, N, O]; returns `out` [Tx, N, A or K] and, when the
     Gaussian noise eps [Tx, N, A] is given (actor only), the sampled action a = mu + sigma * eps
     and its log-density log p = sum_j [ -((a_j - mu_j)/sigma_j)^2 / 2 - log sigma_j ] - (A/2) log 2 pi.
-    Cells outside `rows` stay zero."""
+    Cells outside `rows` stay zero.  `prefs` (optional) restricts the work to those preference
+    indices (the others' cells stay zero); preferences do not interact in this step."""
     x = np.asarray(x, dtype=np.float64)
     Tx = x.shape[0]
     t0, tc, j0, jc = rows
@@ -272,7 +273,7 @@ def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=Fal
         eps = np.asarray(eps, dtype=np.float64)
         act = np.zeros((Tx, d.N, d.act_dim))
         logp = np.zeros((Tx, d.N))
-    for p in range(d.P):
+    for p in (range(d.P) if prefs is None else prefs):
         Ws, bs, logsig = _split_theta(d, net, theta_mat, theta_vec, p)
         idx = _group_env_index(d, rows, p)
         X = x[t0:t0 + tc][:, idx, :].reshape(tc * jc, d.obs_dim)
@@ -297,12 +298,13 @@ def gaussian_logp(a, mu, logsig):
 
 
 def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulate_bf16=False,
-               want_dx=False):
+               want_dx=False, prefs=None):
     """Reverse mode through the grouped target networks: given dL/d(out) on the selected rows,
     returns dL/dtheta_mat [P, mat_len] and dL/dtheta_vec [P, vec_len] (bias gradients, then for the
     actor the given dL/dlogsig [P, A] copied through).  dW_l(p) = dZ_l^T H_{l-1} over the rows of
     preference p, db_l(p) = column sums of dZ_l, dH_{l-1} = dZ_l W_l(p), dZ = dH * act'(z).
-    With emulate_bf16 both operands of every GEMM are rounded to bfloat16 on entry."""
+    With emulate_bf16 both operands of every GEMM are rounded to bfloat16 on entry.  `prefs`
+    (optional) restricts the work to those preference indices; the other rows stay zero."""
     x = np.asarray(x, dtype=np.float64)
     dout = np.asarray(dout, dtype=np.float64)
     t0, tc, j0, jc = rows
@@ -311,7 +313,7 @@ def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulat
     dvec = np.zeros((d.P, theta_vec_len(d, net)))
     dx = np.zeros_like(x) if want_dx else None
     rb = round_bf16 if emulate_bf16 else (lambda a: a)
-    for p in range(d.P):
+    for p in (range(d.P) if prefs is None else prefs):
         Ws, bs, _ = _split_theta(d, net, theta_mat, theta_vec, p)
         idx = _group_env_index(d, rows, p)
         X = x[t0:t0 + tc][:, idx, :].reshape(tc * jc, d.obs_dim)

@@ -1,0 +1,186 @@
+"""ctypes binding of libmorlax.so: the same entry points as include/morlax.h.
+
+Argument marshalling only.  Tensors are torch CUDA tensors used as device memory (data_ptr) and the
+current torch stream is passed as the hipStream_t; every computation runs in the library's kernels.
+Loading fails loudly when the library has not been built (`python -m paper_2603_09237_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmorlax.so")
+
+ACTOR, CRITIC = 0, 1
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
+
+
+class Dims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("K", "P", "N", "T", "obs_dim", "act_dim", "n_hidden", "width",
+                                         "act", "rank", "hyper_width", "wdtype", "mean_tanh")]
+
+
+class Rows(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("t0", "t_cnt", "j0", "j_cnt")]
+
+
+class MorlaxError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"morlax error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hparam_count",
+           "morlax_theta_mat_len", "morlax_theta_vec_len", "morlax_saved_bytes", "morlax_workspace_bytes",
+           "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
+           "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad")
+
+
+def load():
+    """dlopen the library (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_09237_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    lib.morlax_create.argtypes = [C.POINTER(Dims), C.POINTER(vp)]
+    lib.morlax_create.restype = C.c_int
+    lib.morlax_destroy.argtypes = [vp]
+    lib.morlax_destroy.restype = None
+    lib.morlax_last_error.argtypes = []
+    lib.morlax_last_error.restype = C.c_char_p
+    for name in ("morlax_hparam_count", "morlax_theta_mat_len", "morlax_theta_vec_len"):
+        getattr(lib, name).argtypes = [vp, C.c_int]
+        getattr(lib, name).restype = i64
+    lib.morlax_saved_bytes.argtypes = [vp, C.c_int, C.POINTER(Rows)]
+    lib.morlax_saved_bytes.restype = i64
+    lib.morlax_workspace_bytes.argtypes = [vp, C.POINTER(Rows)]
+    lib.morlax_workspace_bytes.restype = i64
+    lib.morlax_env_pref_index.argtypes = [vp, vp, vp]
+    lib.morlax_hypernet_fwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp]
+    lib.morlax_hypernet_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
+    lib.morlax_policy_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
+    lib.morlax_policy_bwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
+    lib.morlax_vec_gae.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
+                                         vp, vp, vp, vp, vp, vp]
+    for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
+                 "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _rows(rows):
+    if rows is None:
+        return None
+    if isinstance(rows, Rows):
+        return C.byref(rows)
+    return C.byref(Rows(*[int(v) for v in rows]))
+
+
+class Context:
+    """Owns a morlax_ctx.  Methods mirror the C entry points and raise MorlaxError on failure."""
+
+    def __init__(self, **dims):
+        self.lib = load()
+        self.dims = Dims(**{k: int(v) for k, v in dims.items()})
+        h = C.c_void_p()
+        rc = self.lib.morlax_create(C.byref(self.dims), C.byref(h))
+        if rc != OK:
+            raise MorlaxError(rc, self.lib.morlax_last_error().decode())
+        self.h = h
+
+    @classmethod
+    def from_config(cls, cfg):
+        return cls(**cfg.dims_dict())
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.morlax_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != OK:
+            raise MorlaxError(rc, self.lib.morlax_last_error().decode())
+
+    # ---- queries
+    def hparam_count(self, net):
+        return self.lib.morlax_hparam_count(self.h, net)
+
+    def theta_mat_len(self, net):
+        return self.lib.morlax_theta_mat_len(self.h, net)
+
+    def theta_vec_len(self, net):
+        return self.lib.morlax_theta_vec_len(self.h, net)
+
+    def saved_bytes(self, net, rows=None):
+        return self.lib.morlax_saved_bytes(self.h, net, _rows(rows))
+
+    def workspace_bytes(self, rows=None):
+        return self.lib.morlax_workspace_bytes(self.h, _rows(rows))
+
+    # ---- ops
+    def env_pref_index(self, out, stream=None):
+        self._check(self.lib.morlax_env_pref_index(self.h, _ptr(out), stream if stream is not None else _stream()))
+
+    def hypernet_fwd(self, net, hparams, w, theta_mat, theta_vec, ws, stream=None):
+        self._check(self.lib.morlax_hypernet_fwd(self.h, net, _ptr(hparams), _ptr(w), _ptr(theta_mat),
+                                                 _ptr(theta_vec), _ptr(ws),
+                                                 stream if stream is not None else _stream()))
+
+    def hypernet_bwd(self, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, stream=None):
+        self._check(self.lib.morlax_hypernet_bwd(self.h, net, _ptr(hparams), _ptr(w), _ptr(dtheta_mat),
+                                                 _ptr(dtheta_vec), _ptr(dhparams), _ptr(ws),
+                                                 stream if stream is not None else _stream()))
+
+    def policy_fwd(self, net, theta_mat, theta_vec, x, rows, out, eps=None, act=None, logp=None, saved=None,
+                   ws=None, stream=None):
+        self._check(self.lib.morlax_policy_fwd(self.h, net, _ptr(theta_mat), _ptr(theta_vec), _ptr(x), _rows(rows),
+                                               _ptr(out), _ptr(eps), _ptr(act), _ptr(logp), _ptr(saved), _ptr(ws),
+                                               stream if stream is not None else _stream()))
+
+    def policy_bwd(self, net, theta_mat, theta_vec, x, rows, saved, dout, dlogsig, dtheta_mat, dtheta_vec, ws,
+                   stream=None):
+        self._check(self.lib.morlax_policy_bwd(self.h, net, _ptr(theta_mat), _ptr(theta_vec), _ptr(x), _rows(rows),
+                                               _ptr(saved), _ptr(dout), _ptr(dlogsig), _ptr(dtheta_mat),
+                                               _ptr(dtheta_vec), _ptr(ws),
+                                               stream if stream is not None else _stream()))
+
+    def vec_gae(self, r, v, done, w, gamma, lam, adv_vec, vtarg, adv_s, stream=None):
+        self._check(self.lib.morlax_vec_gae(self.h, _ptr(r), _ptr(v), _ptr(done), _ptr(w), float(gamma), float(lam),
+                                            _ptr(adv_vec), _ptr(vtarg), _ptr(adv_s),
+                                            stream if stream is not None else _stream()))
+
+    def ppo_loss_grad(self, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv,
+                      dmu, dlogsig, dv, stats, ws, stream=None):
+        self._check(self.lib.morlax_ppo_loss_grad(self.h, _rows(rows), _ptr(mu), _ptr(logsig), int(logsig_stride),
+                                                  _ptr(act), _ptr(logp_old), _ptr(adv_s), _ptr(v), _ptr(vtarg),
+                                                  float(clip_eps), int(norm_adv), _ptr(dmu), _ptr(dlogsig),
+                                                  _ptr(dv), _ptr(stats), _ptr(ws),
+                                                  stream if stream is not None else _stream()))

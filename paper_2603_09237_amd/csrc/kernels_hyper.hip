@@ -1,0 +1,538 @@
+// Hypernetwork forward and backward (paper Sec. III-B: H(w) = M f(w) + b, read as rank-r factors on
+// shared base weights).  fp32 arithmetic; theta_mat is rounded to bf16 (nearest even) on store when
+// the target networks run in bf16.  Every reduction is fixed-order.
+#include "morlax_internal.h"
+#include "numeric.h"
+
+#define QC 256  // stacked-affine rows per block of the df partial kernel
+
+struct HyperWs {
+    float *h1, *f, *fac, *dfac, *df_part, *df, *dz2, *dz1, *vecs;
+    int n_chunk;
+};
+
+static HyperWs hyper_ws_layout(const morlax_ctx* c, void* ws, int64_t* total) {
+    const int64_t P = c->d.P, F = c->d.hyper_width;
+    int64_t fac = c->net[0].fac_len > c->net[1].fac_len ? c->net[0].fac_len : c->net[1].fac_len;
+    int64_t q = c->aff[0].q_total > c->aff[1].q_total ? c->aff[0].q_total : c->aff[1].q_total;
+    HyperWs L;
+    float* p = reinterpret_cast<float*>(ws);
+    auto take = [&](int64_t n) { float* r = p; p += align_up(n, 64); return r; };
+    L.h1 = take(P * F);
+    L.f = take(P * F);
+    L.df = take(P * F);
+    L.dz2 = take(P * F);
+    L.dz1 = take(P * F);
+    {
+        int64_t vl = c->net[0].vec_len > c->net[1].vec_len ? c->net[0].vec_len : c->net[1].vec_len;
+        L.vecs = take(P * vl);
+    }
+    L.fac = take(P * fac);
+    L.dfac = take(P * fac);
+    L.n_chunk = (int)((q + QC - 1) / QC);
+    L.df_part = take((int64_t)L.n_chunk * P * F);
+    if (total) *total = (int64_t)((char*)p - (char*)ws);
+    return L;
+}
+
+int64_t hyper_ws_bytes(const morlax_ctx* c) {
+    int64_t t = 0;
+    hyper_ws_layout(c, nullptr, &t);
+    return align_up(t, 256);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Trunk f(w): h1 = tanh(Wh1 w + bh1), f = tanh(Wh2 h1 + bh2).  One block per preference.
+__global__ __launch_bounds__(64) void k_hyper_trunk(const float* __restrict__ hp, const float* __restrict__ w,
+                                                   float* __restrict__ h1, float* __restrict__ f, int K, int F,
+                                                   int64_t o_wh1, int64_t o_bh1, int64_t o_wh2, int64_t o_bh2) {
+    __shared__ float sh[MORLAX_MAX_F];
+    const int p = blockIdx.x, j = threadIdx.x;
+    if (j < F) {
+        float a = hp[o_bh1 + j];
+        for (int k = 0; k < K; ++k) a += hp[o_wh1 + (int64_t)j * K + k] * w[p * K + k];
+        a = tanhf(a);
+        sh[j] = a;
+        h1[p * F + j] = a;
+    }
+    __syncthreads();
+    if (j < F) {
+        float a = hp[o_bh2 + j];
+        for (int i = 0; i < F; ++i) a += hp[o_wh2 + (int64_t)j * F + i] * sh[i];
+        f[p * F + j] = tanhf(a);
+    }
+}
+
+__device__ inline int find_seg(const AffineTable& at, int q) {
+    int s = 0;
+    while (s + 1 < at.n_seg && q >= at.q0[s + 1]) ++s;
+    return s;
+}
+
+// Stacked affine map: row q for every preference.  Thread per row; f staged in LDS in tiles of 64 p.
+__global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const float* __restrict__ hp,
+                                                     const float* __restrict__ f, float* __restrict__ fac,
+                                                     float* __restrict__ theta_vec, int P, int F,
+                                                     int64_t fac_len, int64_t vec_len) {
+    __shared__ float sf[64][MORLAX_MAX_F];
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    const bool ok = q < at.q_total;
+    float m[MORLAX_MAX_F];
+    float c = 0.f;
+    if (ok) {
+        const int s = find_seg(at, q);
+        const int64_t loc = q - at.q0[s];
+        c = hp[at.hp_c[s] + loc];
+        const float* mr = hp + at.hp_m[s] + loc * F;
+#pragma unroll
+        for (int j = 0; j < MORLAX_MAX_F; ++j) m[j] = (j < F) ? mr[j] : 0.f;
+    }
+    for (int p0 = 0; p0 < P; p0 += 64) {
+        const int np = (P - p0 < 64) ? (P - p0) : 64;
+        __syncthreads();
+        for (int i = threadIdx.x; i < np * F; i += 256) sf[i / F][i % F] = f[(int64_t)p0 * F + i];
+        __syncthreads();
+        if (ok) {
+            for (int pp = 0; pp < np; ++pp) {
+                float a = c;
+#pragma unroll
+                for (int j = 0; j < MORLAX_MAX_F; ++j)
+                    if (j < F) a += m[j] * sf[pp][j];
+                const int64_t p = p0 + pp;
+                if (q < fac_len) fac[p * fac_len + q] = a;
+                else theta_vec[p * vec_len + (q - fac_len)] = a;
+            }
+        }
+    }
+}
+
+// W_l(p) = W0_l + A_l(p) B_l(p).  A block makes a 64 (d_out) x 128 (d_in) tile of one layer of one
+// preference; each thread 4 x 8 outputs with the factor tiles in LDS.
+struct MatTiles {
+    int32_t tile0[MORLAX_MAX_LAYERS + 1];  // first tile id of each layer
+    int32_t tiles_i[MORLAX_MAX_LAYERS];    // tiles along d_in
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_hyper_materialize(NetDev nd, MatTiles mt, const float* __restrict__ hp,
+                                                          const float* __restrict__ fac,
+                                                          T* __restrict__ theta_mat, int r) {
+    __shared__ float sA[64][MORLAX_MAX_RANK + 1];
+    __shared__ float sB[MORLAX_MAX_RANK][128];
+    const int p = blockIdx.y;
+    int l = 0;
+    while (l + 1 < nd.n_layers && (int)blockIdx.x >= mt.tile0[l + 1]) ++l;
+    const LayerDev L = nd.layer[l];
+    const int tl = blockIdx.x - mt.tile0[l];
+    const int o0 = (tl / mt.tiles_i[l]) * 64, i0 = (tl % mt.tiles_i[l]) * 128;
+    const float* fp = fac + (int64_t)p * nd.fac_len;
+    for (int idx = threadIdx.x; idx < 64 * r; idx += 256) {
+        const int oo = idx / r, k = idx % r;
+        sA[oo][k] = (o0 + oo < L.d_out) ? fp[L.fac_a + (int64_t)(o0 + oo) * r + k] : 0.f;
+    }
+    for (int idx = threadIdx.x; idx < r * 128; idx += 256) {
+        const int k = idx / 128, ii = idx % 128;
+        sB[k][ii] = (i0 + ii < L.d_in) ? fp[L.fac_b + (int64_t)k * L.d_in + i0 + ii] : 0.f;
+    }
+    __syncthreads();
+    const int to = (threadIdx.x / 16) * 4, ti = (threadIdx.x % 16) * 8;
+    float acc[4][8];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
+    for (int k = 0; k < r; ++k) {
+        float bv[8], av[4];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) bv[b] = sB[k][ti + b];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) av[a] = sA[to + a][k];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 8; ++b) acc[a][b] += av[a] * bv[b];
+    }
+    T* dst = theta_mat + (int64_t)p * nd.mat_len + L.mat_off;
+    const float* w0 = hp + L.hp_w0;
+    const bool vec = (L.d_in % 8 == 0);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int o = o0 + to + a;
+        if (o >= L.d_out) continue;
+        const int64_t base = (int64_t)o * L.d_in + i0 + ti;
+        if (vec && i0 + ti + 8 <= L.d_in) {
+            float v[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) v[b] = w0[base + b] + acc[a][b];
+            store8(dst + base, v);
+        } else {
+#pragma unroll
+            for (int b = 0; b < 8; ++b)
+                if (i0 + ti + b < L.d_in) dst[base + b] = cvt<T>(w0[base + b] + acc[a][b]);
+        }
+    }
+}
+
+static void run_trunk_and_affine(const morlax_ctx* c, int net, const float* hp, const float* w,
+                                 const HyperWs& L, float* theta_vec_or_null, float* vec_scratch, hipStream_t s) {
+    const NetDev& nd = c->net[net];
+    const AffineTable& at = c->aff[net];
+    const int P = c->d.P, F = c->d.hyper_width;
+    k_hyper_trunk<<<P, 64, 0, s>>>(hp, w, L.h1, L.f, c->d.K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
+    float* tv = theta_vec_or_null ? theta_vec_or_null : vec_scratch;
+    k_hyper_affine<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, hp, L.f, L.fac, tv, P, F, nd.fac_len, nd.vec_len);
+}
+
+static MatTiles mat_tiles(const NetDev& nd) {
+    MatTiles mt;
+    int t = 0;
+    for (int l = 0; l < nd.n_layers; ++l) {
+        mt.tile0[l] = t;
+        mt.tiles_i[l] = (nd.layer[l].d_in + 127) / 128;
+        t += mt.tiles_i[l] * ((nd.layer[l].d_out + 63) / 64);
+    }
+    mt.tile0[nd.n_layers] = t;
+    return mt;
+}
+
+void launch_hypernet_fwd(const morlax_ctx* c, int net, const float* hparams, const float* w,
+                         void* theta_mat, float* theta_vec, void* ws, hipStream_t s) {
+    const NetDev& nd = c->net[net];
+    HyperWs L = hyper_ws_layout(c, ws, nullptr);
+    run_trunk_and_affine(c, net, hparams, w, L, theta_vec, nullptr, s);
+    MatTiles mt = mat_tiles(nd);
+    const dim3 grid(mt.tile0[nd.n_layers], c->d.P);
+    if (c->d.wdtype == 1)
+        k_hyper_materialize<bf16_t><<<grid, 256, 0, s>>>(nd, mt, hparams, L.fac, (bf16_t*)theta_mat, c->d.rank);
+    else
+        k_hyper_materialize<float><<<grid, 256, 0, s>>>(nd, mt, hparams, L.fac, (float*)theta_mat, c->d.rank);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Backward.
+
+// dW0_l = sum_p dW_l(p): four consecutive elements per thread, p ascending.
+__global__ __launch_bounds__(256) void k_hyper_dbase(NetDev nd, const float* __restrict__ dmat,
+                                                    float* __restrict__ dhp, int P) {
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= nd.mat_len) return;
+    int l = 0;
+    while (l + 1 < nd.n_layers && e >= nd.layer[l + 1].mat_off) ++l;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < P; ++p) {
+        const float4 v = *reinterpret_cast<const float4*>(dmat + (int64_t)p * nd.mat_len + e);
+        a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    }
+    float* d = dhp + nd.layer[l].hp_w0 + (e - nd.layer[l].mat_off);
+    d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w;
+}
+
+struct RowTiles {
+    int32_t tile0[MORLAX_MAX_LAYERS + 1];
+};
+
+// dA_l(p)[o, k] = sum_i dW_l(p)[o, i] B_l(p)[k, i].  Block: 64 rows o of one layer of one p; a row
+// is handled by 16 lanes (float4 each), B staged in LDS in chunks of 512 columns.
+template <int R_MAX>
+__global__ __launch_bounds__(256) void k_hyper_dA(NetDev nd, RowTiles rt, const float* __restrict__ dmat,
+                                                 const float* __restrict__ fac, float* __restrict__ dfac, int r) {
+    extern __shared__ float sB[];  // [r][512]
+    const int p = blockIdx.y;
+    int l = 0;
+    while (l + 1 < nd.n_layers && (int)blockIdx.x >= rt.tile0[l + 1]) ++l;
+    const LayerDev L = nd.layer[l];
+    const int o0 = (blockIdx.x - rt.tile0[l]) * 64;
+    const float* dW = dmat + (int64_t)p * nd.mat_len + L.mat_off;
+    const float* B = fac + (int64_t)p * nd.fac_len + L.fac_b;
+    const int rl = threadIdx.x / 16, il = threadIdx.x % 16;  // 16 rows per pass
+    float acc[4][R_MAX];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int k = 0; k < R_MAX; ++k) acc[a][k] = 0.f;
+    const bool vec = (L.d_in % 4 == 0);
+    for (int c0 = 0; c0 < L.d_in; c0 += 512) {
+        const int cw = (L.d_in - c0 < 512) ? (L.d_in - c0) : 512;
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < r * 512; idx += 256) {
+            const int k = idx / 512, ii = idx % 512;
+            sB[idx] = (ii < cw) ? B[(int64_t)k * L.d_in + c0 + ii] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int o = o0 + a * 16 + rl;
+            if (o >= L.d_out) continue;
+            for (int ii = il * 4; ii < cw; ii += 64) {
+                float x[4];
+                const float* src = dW + (int64_t)o * L.d_in + c0 + ii;
+                if (vec) {
+                    const float4 v = *reinterpret_cast<const float4*>(src);
+                    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) x[b] = (ii + b < cw) ? src[b] : 0.f;
+                }
+#pragma unroll
+                for (int k = 0; k < R_MAX; ++k) {
+                    if (k < r) {
+                        const float* bk = sB + k * 512 + ii;
+                        acc[a][k] += x[0] * bk[0] + x[1] * bk[1] + x[2] * bk[2] + x[3] * bk[3];
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int o = o0 + a * 16 + rl;
+#pragma unroll
+        for (int k = 0; k < R_MAX; ++k) {
+            if (k < r) {
+                float v = acc[a][k];
+                v += __shfl_xor(v, 8, 64);
+                v += __shfl_xor(v, 4, 64);
+                v += __shfl_xor(v, 2, 64);
+                v += __shfl_xor(v, 1, 64);
+                if (il == 0 && o < L.d_out) dfac[(int64_t)p * nd.fac_len + L.fac_a + (int64_t)o * r + k] = v;
+            }
+        }
+    }
+}
+
+struct ColTiles {
+    int32_t tile0[MORLAX_MAX_LAYERS + 1];
+};
+
+// dB_l(p)[k, i] = sum_o A_l(p)[o, k] dW_l(p)[o, i].  Block: 256 columns i of one layer of one p;
+// thread per column, o ascending, A staged in LDS in chunks of 512 rows.
+template <int R_MAX>
+__global__ __launch_bounds__(256) void k_hyper_dB(NetDev nd, ColTiles ct, const float* __restrict__ dmat,
+                                                 const float* __restrict__ fac, float* __restrict__ dfac, int r) {
+    extern __shared__ float sA[];  // [512][r]
+    const int p = blockIdx.y;
+    int l = 0;
+    while (l + 1 < nd.n_layers && (int)blockIdx.x >= ct.tile0[l + 1]) ++l;
+    const LayerDev L = nd.layer[l];
+    const int i = (blockIdx.x - ct.tile0[l]) * 256 + threadIdx.x;
+    const float* dW = dmat + (int64_t)p * nd.mat_len + L.mat_off;
+    const float* A = fac + (int64_t)p * nd.fac_len + L.fac_a;
+    float acc[R_MAX];
+#pragma unroll
+    for (int k = 0; k < R_MAX; ++k) acc[k] = 0.f;
+    for (int o0 = 0; o0 < L.d_out; o0 += 512) {
+        const int oh = (L.d_out - o0 < 512) ? (L.d_out - o0) : 512;
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < oh * r; idx += 256) sA[idx] = A[(int64_t)o0 * r + idx];
+        __syncthreads();
+        if (i < L.d_in) {
+            int oo = 0;
+            for (; oo + 4 <= oh; oo += 4) {
+                float x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) x[u] = dW[(int64_t)(o0 + oo + u) * L.d_in + i];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int k = 0; k < R_MAX; ++k)
+                        if (k < r) acc[k] += sA[(oo + u) * r + k] * x[u];
+            }
+            for (; oo < oh; ++oo) {
+                const float x = dW[(int64_t)(o0 + oo) * L.d_in + i];
+#pragma unroll
+                for (int k = 0; k < R_MAX; ++k)
+                    if (k < r) acc[k] += sA[oo * r + k] * x;
+            }
+        }
+    }
+    if (i < L.d_in) {
+#pragma unroll
+        for (int k = 0; k < R_MAX; ++k)
+            if (k < r) dfac[(int64_t)p * nd.fac_len + L.fac_b + (int64_t)k * L.d_in + i] = acc[k];
+    }
+}
+
+__device__ inline float grad_row(const float* __restrict__ dfac, const float* __restrict__ dvec, int64_t p, int q,
+                                 int64_t fac_len, int64_t vec_len) {
+    return (q < fac_len) ? dfac[p * fac_len + q] : dvec[p * vec_len + (q - fac_len)];
+}
+
+// dM[q, :] = sum_p g[p, q] f[p, :],  dc[q] = sum_p g[p, q]  (g: gradient of the stacked affine rows)
+__global__ __launch_bounds__(256) void k_hyper_dM(AffineTable at, const float* __restrict__ f,
+                                                 const float* __restrict__ dfac, const float* __restrict__ dvec,
+                                                 float* __restrict__ dhp, int P, int F, int64_t fac_len,
+                                                 int64_t vec_len) {
+    __shared__ float sf[64][MORLAX_MAX_F];
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    const bool ok = q < at.q_total;
+    float acc[MORLAX_MAX_F];
+#pragma unroll
+    for (int j = 0; j < MORLAX_MAX_F; ++j) acc[j] = 0.f;
+    float dc = 0.f;
+    for (int p0 = 0; p0 < P; p0 += 64) {
+        const int np = (P - p0 < 64) ? (P - p0) : 64;
+        __syncthreads();
+        for (int i = threadIdx.x; i < np * F; i += 256) sf[i / F][i % F] = f[(int64_t)p0 * F + i];
+        __syncthreads();
+        if (ok) {
+            for (int pp = 0; pp < np; ++pp) {
+                const float g = grad_row(dfac, dvec, p0 + pp, q, fac_len, vec_len);
+                dc += g;
+#pragma unroll
+                for (int j = 0; j < MORLAX_MAX_F; ++j)
+                    if (j < F) acc[j] += g * sf[pp][j];
+            }
+        }
+    }
+    if (ok) {
+        const int s = find_seg(at, q);
+        const int64_t loc = q - at.q0[s];
+        dhp[at.hp_c[s] + loc] = dc;
+        float* mr = dhp + at.hp_m[s] + loc * F;
+#pragma unroll
+        for (int j = 0; j < MORLAX_MAX_F; ++j)
+            if (j < F) mr[j] = acc[j];
+    }
+}
+
+// df partials: part[chunk, p, j] = sum over the chunk's rows q of g[p, q] M[q, j].
+__global__ __launch_bounds__(256) void k_hyper_df_part(AffineTable at, const float* __restrict__ hp,
+                                                      const float* __restrict__ dfac,
+                                                      const float* __restrict__ dvec, float* __restrict__ part,
+                                                      int P, int F, int64_t fac_len, int64_t vec_len) {
+    __shared__ float sM[64][MORLAX_MAX_F];
+    __shared__ float sd[64][65];
+    const int chunk = blockIdx.x;
+    const int pp = threadIdx.x % 64, jq = threadIdx.x / 64;
+    const int JG = (F + 3) / 4;  // <= 16 features per thread
+    const int qa = chunk * QC;
+    const int qb = (qa + QC < at.q_total) ? (qa + QC) : at.q_total;
+    for (int p0 = 0; p0 < P; p0 += 64) {
+        float acc[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc[u] = 0.f;
+        for (int qs = qa; qs < qb; qs += 64) {
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < 64 * F; idx += 256) {
+                const int qq = idx / F, j = idx % F;
+                const int q = qs + qq;
+                float v = 0.f;
+                if (q < qb) {
+                    const int s = find_seg(at, q);
+                    v = hp[at.hp_m[s] + (int64_t)(q - at.q0[s]) * F + j];
+                }
+                sM[qq][j] = v;
+            }
+            for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+                const int lp = idx / 64, qq = idx % 64;
+                const int q = qs + qq;
+                sd[lp][qq] = (q < qb && p0 + lp < P) ? grad_row(dfac, dvec, p0 + lp, q, fac_len, vec_len) : 0.f;
+            }
+            __syncthreads();
+            for (int qq = 0; qq < 64; ++qq) {
+                const float d = sd[pp][qq];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int j = jq * JG + u;
+                    if (u < JG && j < F) acc[u] += d * sM[qq][j];
+                }
+            }
+        }
+        if (p0 + pp < P) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int j = jq * JG + u;
+                if (u < JG && j < F) part[((int64_t)chunk * P + p0 + pp) * F + j] = acc[u];
+            }
+        }
+    }
+}
+
+// df[p, j] = sum_chunk part; dz2 = df * (1 - f^2)
+__global__ __launch_bounds__(256) void k_hyper_df_final(const float* __restrict__ part, int n_chunk,
+                                                       const float* __restrict__ f, float* __restrict__ dz2,
+                                                       int PF) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= PF) return;
+    float a = 0.f;
+    for (int c = 0; c < n_chunk; ++c) a += part[(int64_t)c * PF + i];
+    const float fv = f[i];
+    dz2[i] = a * (1.f - fv * fv);
+}
+
+// Trunk backward in one block: dWh2, dbh2, dz1, dWh1, dbh1 (sums over p ascending).
+__global__ __launch_bounds__(256) void k_hyper_trunk_bwd(const float* __restrict__ hp, const float* __restrict__ w,
+                                                        const float* __restrict__ h1,
+                                                        const float* __restrict__ dz2, float* __restrict__ dz1,
+                                                        float* __restrict__ dhp, int P, int K, int F,
+                                                        int64_t o_wh1, int64_t o_bh1, int64_t o_wh2,
+                                                        int64_t o_bh2) {
+    for (int idx = threadIdx.x; idx < F * F; idx += 256) {
+        const int j = idx / F, i = idx % F;
+        float a = 0.f;
+        for (int p = 0; p < P; ++p) a += dz2[p * F + j] * h1[p * F + i];
+        dhp[o_wh2 + idx] = a;
+    }
+    for (int j = threadIdx.x; j < F; j += 256) {
+        float a = 0.f;
+        for (int p = 0; p < P; ++p) a += dz2[p * F + j];
+        dhp[o_bh2 + j] = a;
+    }
+    for (int idx = threadIdx.x; idx < P * F; idx += 256) {
+        const int p = idx / F, i = idx % F;
+        float a = 0.f;
+        for (int j = 0; j < F; ++j) a += dz2[p * F + j] * hp[o_wh2 + (int64_t)j * F + i];
+        const float h = h1[idx];
+        dz1[idx] = a * (1.f - h * h);
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < F * K; idx += 256) {
+        const int i = idx / K, k = idx % K;
+        float a = 0.f;
+        for (int p = 0; p < P; ++p) a += dz1[p * F + i] * w[p * K + k];
+        dhp[o_wh1 + idx] = a;
+    }
+    for (int i = threadIdx.x; i < F; i += 256) {
+        float a = 0.f;
+        for (int p = 0; p < P; ++p) a += dz1[p * F + i];
+        dhp[o_bh1 + i] = a;
+    }
+}
+
+void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, const float* w,
+                         const float* dtheta_mat, const float* dtheta_vec, float* dhparams, void* ws,
+                         hipStream_t s) {
+    const NetDev& nd = c->net[net];
+    const AffineTable& at = c->aff[net];
+    const int P = c->d.P, F = c->d.hyper_width, r = c->d.rank, K = c->d.K;
+    HyperWs L = hyper_ws_layout(c, ws, nullptr);
+    // recompute f and the factors; the theta_vec rows of the affine map land in a scratch nobody reads
+    run_trunk_and_affine(c, net, hparams, w, L, nullptr, L.vecs, s);
+    k_hyper_dbase<<<(int)((nd.mat_len / 4 + 255) / 256), 256, 0, s>>>(nd, dtheta_mat, dhparams, P);
+    if (r > 0) {
+        RowTiles rt;
+        ColTiles ct;
+        int ta = 0, tb = 0;
+        for (int l = 0; l < nd.n_layers; ++l) {
+            rt.tile0[l] = ta; ta += (nd.layer[l].d_out + 63) / 64;
+            ct.tile0[l] = tb; tb += (nd.layer[l].d_in + 255) / 256;
+        }
+        rt.tile0[nd.n_layers] = ta;
+        ct.tile0[nd.n_layers] = tb;
+        const size_t lds = (size_t)r * 512 * sizeof(float);
+        if (r <= 16) {
+            k_hyper_dA<16><<<dim3(ta, P), 256, lds, s>>>(nd, rt, dtheta_mat, L.fac, L.dfac, r);
+            k_hyper_dB<16><<<dim3(tb, P), 256, lds, s>>>(nd, ct, dtheta_mat, L.fac, L.dfac, r);
+        } else {
+            k_hyper_dA<32><<<dim3(ta, P), 256, lds, s>>>(nd, rt, dtheta_mat, L.fac, L.dfac, r);
+            k_hyper_dB<32><<<dim3(tb, P), 256, lds, s>>>(nd, ct, dtheta_mat, L.fac, L.dfac, r);
+        }
+    }
+    k_hyper_dM<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.f, L.dfac, dtheta_vec, dhparams, P, F, nd.fac_len,
+                                                       nd.vec_len);
+    k_hyper_df_part<<<L.n_chunk, 256, 0, s>>>(at, hparams, L.dfac, dtheta_vec, L.df_part, P, F, nd.fac_len,
+                                              nd.vec_len);
+    k_hyper_df_final<<<(P * F + 255) / 256, 256, 0, s>>>(L.df_part, L.n_chunk, L.f, L.dz2, P * F);
+    k_hyper_trunk_bwd<<<1, 256, 0, s>>>(hparams, w, L.h1, L.dz2, L.dz1, dhparams, P, K, F, nd.hp_wh1, nd.hp_bh1,
+                                        nd.hp_wh2, nd.hp_bh2);
+}

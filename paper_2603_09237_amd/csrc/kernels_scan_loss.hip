@@ -1,0 +1,293 @@
+// Bandwidth-bound kernels of the update phase (paper Sec. III-C): the environment -> trade-off
+// index map, the reverse-time vector GAE scan with scalarisation, the advantage statistics and the
+// clipped-PPO / value loss with its gradients.  All reductions are two-stage and fixed-order.
+#include "morlax_internal.h"
+
+#define WAVE 64
+
+// ------------------------------------------------------------------------------------------------
+// g(n) = n / n_g  (Sec. III-C, sampling phase: contiguous blocks of N/P repeated trade-offs)
+__global__ void k_env_pref_index(int32_t* __restrict__ out, int N, int n_g) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n < N) out[n] = n / n_g;
+}
+
+void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s) {
+    int N = c->d.N;
+    k_env_pref_index<<<(N + 255) / 256, 256, 0, s>>>(out, N, c->n_g);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Vector GAE.  One lane per (environment, objective): a wave holds G = 64 / K environments with
+// their K objectives in adjacent lanes, so every load of r[t] and v[t] is one contiguous run of
+// G*K floats and the scalarisation sum_k w_k A_k is a K-lane shuffle reduction.  The scan over t
+// is sequential per lane; loads of U steps are issued before the U dependent updates.
+template <int U>
+__global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
+                                                const uint8_t* __restrict__ done, const float* __restrict__ w,
+                                                float gamma, float gl, float* __restrict__ adv_vec,
+                                                float* __restrict__ vtarg, float* __restrict__ adv_s,
+                                                int T, int N, int K, int n_g) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const int G = WAVE / K;
+    const int e = lane / K, k = lane - e * K;
+    const int n = wave * G + e;
+    const bool live = (e < G) && (n < N);
+    const int64_t NK = (int64_t)N * K;
+    const int64_t idx = (int64_t)n * K + k;
+    const float wk = live ? w[(n / n_g) * K + k] : 0.f;
+    float vn = live ? v[(int64_t)T * NK + idx] : 0.f;
+    float acc = 0.f;
+    int t = T - 1;
+    while (t >= 0) {
+        float rt[U], vt[U];
+        uint8_t dn[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tt = t - u;
+            const bool ok = live && tt >= 0;
+            rt[u] = ok ? r[(int64_t)tt * NK + idx] : 0.f;
+            vt[u] = ok ? v[(int64_t)tt * NK + idx] : 0.f;
+            dn[u] = ok ? done[(int64_t)tt * N + n] : (uint8_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tt = t - u;
+            if (tt < 0) break;  // uniform across the wave
+            const float d_done = rt[u] - vt[u];
+            const float d_live = rt[u] + gamma * vn - vt[u];
+            acc = dn[u] ? d_done : (d_live + gl * acc);
+            float s = wk * acc;
+            float tot = s;
+            for (int j = 1; j < K; ++j) tot += __shfl_down(s, j, WAVE);
+            if (live) {
+                const int64_t o = (int64_t)tt * NK + idx;
+                if (adv_vec) adv_vec[o] = acc;
+                vtarg[o] = acc + vt[u];
+                if (k == 0) adv_s[(int64_t)tt * N + n] = tot;
+            }
+            vn = vt[u];
+        }
+        t -= U;
+    }
+}
+
+void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const uint8_t* done,
+                    const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
+                    float* adv_s, hipStream_t s) {
+    const int K = c->d.K, N = c->d.N, T = c->d.T;
+    const int G = WAVE / K;
+    const int waves = (N + G - 1) / G;
+    const int blocks = (waves + 3) / 4;
+    k_vec_gae<8><<<blocks, 256, 0, s>>>(r, v, done, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s, T, N, K,
+                                        c->n_g);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Loss.  Selected cells are enumerated per preference: cell m of preference p is time
+// t0 + m / j_cnt, environment p * n_g + j0 + m % j_cnt.  A block handles 256 cells of one p.
+
+__device__ inline double block_sum(double v, double* sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) sh[wv] = v;
+    __syncthreads();
+    double tot = sh[0] + sh[1] + sh[2] + sh[3];
+    __syncthreads();
+    return tot;
+}
+
+struct LossWs {
+    double* adv_part;   // [nblk][2]
+    double* adv_stat;   // [2]: mean, std
+    double* stat_part;  // [nblk][5]
+    double* dls_part;   // [nblk][A]
+};
+
+static LossWs loss_ws_layout(const morlax_ctx* c, const RowSel& rs, void* ws, int64_t* total) {
+    const int64_t nbm = (rs.M + 255) / 256, nblk = nbm * c->d.P;
+    LossWs L;
+    double* p = reinterpret_cast<double*>(ws);
+    L.adv_part = p; p += nblk * 2;
+    L.adv_stat = p; p += 2;
+    L.stat_part = p; p += nblk * 5;
+    L.dls_part = p; p += nblk * c->d.act_dim;
+    if (total) *total = (int64_t)((char*)p - (char*)ws);
+    return L;
+}
+
+int64_t loss_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
+    int64_t tot = 0;
+    loss_ws_layout(c, rs, nullptr, &tot);
+    return align_up(tot, 256);
+}
+
+__device__ inline int64_t cell_row(const RowSel& rs, int p, int m, int N, int n_g) {
+    const int t = rs.t0 + m / rs.j_cnt;
+    const int j = rs.j0 + m % rs.j_cnt;
+    return (int64_t)t * N + (int64_t)p * n_g + j;
+}
+
+__global__ __launch_bounds__(256) void k_adv_partial(RowSel rs, const float* __restrict__ adv_s,
+                                                    double* __restrict__ part, int N, int n_g) {
+    __shared__ double sh[4];
+    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
+    double a = 0.0;
+    if (m < rs.M) a = (double)adv_s[cell_row(rs, p, m, N, n_g)];
+    const double s1 = block_sum(a, sh);
+    const double s2 = block_sum(a * a, sh);
+    if (threadIdx.x == 0) {
+        const int64_t b = (int64_t)p * gridDim.x + blockIdx.x;
+        part[b * 2] = s1;
+        part[b * 2 + 1] = s2;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_adv_final(const double* __restrict__ part, int64_t nblk, double cnt,
+                                                  double* __restrict__ stat) {
+    __shared__ double sh[4];
+    double s1 = 0.0, s2 = 0.0;
+    for (int64_t b = threadIdx.x; b < nblk; b += 256) {
+        s1 += part[b * 2];
+        s2 += part[b * 2 + 1];
+    }
+    s1 = block_sum(s1, sh);
+    s2 = block_sum(s2, sh);
+    if (threadIdx.x == 0) {
+        const double mean = s1 / cnt;
+        double var = s2 / cnt - mean * mean;
+        if (var < 0.0) var = 0.0;
+        stat[0] = mean;
+        stat[1] = sqrt(var);
+    }
+}
+
+template <int A_MAX>
+__global__ __launch_bounds__(256) void k_ppo_loss_grad(
+    RowSel rs, const float* __restrict__ mu, const float* __restrict__ logsig, int ls_stride,
+    const float* __restrict__ act, const float* __restrict__ logp_old, const float* __restrict__ adv_s,
+    const float* __restrict__ v, const float* __restrict__ vtarg, const double* __restrict__ adv_stat,
+    float clip_eps, int norm_adv, float inv_B, float* __restrict__ dmu, float* __restrict__ dv,
+    double* __restrict__ stat_part, double* __restrict__ dls_part, int N, int n_g, int A, int K) {
+    __shared__ double sh[4];
+    __shared__ float s_ls[A_MAX], s_isig[A_MAX];
+    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
+    if (threadIdx.x < A) {
+        const float ls = logsig[(int64_t)p * ls_stride + threadIdx.x];
+        s_ls[threadIdx.x] = ls;
+        s_isig[threadIdx.x] = expf(-ls);
+    }
+    __syncthreads();
+    const bool ok = m < rs.M;
+    float l_pi = 0.f, l_v = 0.f, clipped = 0.f, kl = 0.f, rho_s = 0.f;
+    float dls[A_MAX];
+#pragma unroll
+    for (int a = 0; a < A_MAX; ++a) dls[a] = 0.f;
+    if (ok) {
+        const int64_t row = cell_row(rs, p, m, N, n_g);
+        float ahat = adv_s[row];
+        if (norm_adv) ahat = (float)(((double)ahat - adv_stat[0]) / (adv_stat[1] + 1e-8));
+        float q[A_MAX];
+        float logp = -0.918938533204672742f * (float)A;  // -(A/2) log(2 pi)
+#pragma unroll
+        for (int a = 0; a < A_MAX; ++a) {
+            if (a < A) {
+                q[a] = (act[row * A + a] - mu[row * A + a]) * s_isig[a];
+                logp += -0.5f * q[a] * q[a] - s_ls[a];
+            }
+        }
+        const float lpo = logp_old[row];
+        const float rho = expf(logp - lpo);
+        const float rc = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
+        l_pi = -fminf(rho * ahat, rc * ahat);
+        const bool pass = (ahat >= 0.f) ? (rho <= 1.f + clip_eps) : (rho >= 1.f - clip_eps);
+        const float dlogp = pass ? (-ahat * rho * inv_B) : 0.f;
+        clipped = (fabsf(rho - 1.f) > clip_eps) ? 1.f : 0.f;
+        kl = lpo - logp;
+        rho_s = rho;
+#pragma unroll
+        for (int a = 0; a < A_MAX; ++a) {
+            if (a < A) {
+                dmu[row * A + a] = dlogp * q[a] * s_isig[a];
+                dls[a] = dlogp * (q[a] * q[a] - 1.f);
+            }
+        }
+        for (int k = 0; k < K; ++k) {
+            const float dd = v[row * K + k] - vtarg[row * K + k];
+            l_v += dd * dd;
+            dv[row * K + k] = 2.f * dd * inv_B;
+        }
+    }
+    const int64_t b = (int64_t)p * gridDim.x + blockIdx.x;
+    const double r0 = block_sum((double)l_pi, sh), r1 = block_sum((double)l_v, sh),
+                 r2 = block_sum((double)clipped, sh), r3 = block_sum((double)kl, sh),
+                 r4 = block_sum((double)rho_s, sh);
+    if (threadIdx.x == 0) {
+        stat_part[b * 5 + 0] = r0; stat_part[b * 5 + 1] = r1; stat_part[b * 5 + 2] = r2;
+        stat_part[b * 5 + 3] = r3; stat_part[b * 5 + 4] = r4;
+    }
+#pragma unroll
+    for (int a = 0; a < A_MAX; ++a) {
+        if (a < A) {
+            const double t = block_sum((double)dls[a], sh);
+            if (threadIdx.x == 0) dls_part[b * A + a] = t;
+        }
+    }
+}
+
+// blocks 0..P-1: dlogsig[p][:]; block P: stats
+__global__ __launch_bounds__(256) void k_loss_final(const double* __restrict__ stat_part,
+                                                   const double* __restrict__ dls_part,
+                                                   const double* __restrict__ adv_stat, int nbm, int P, int A,
+                                                   double cnt, float* __restrict__ dlogsig,
+                                                   float* __restrict__ stats) {
+    __shared__ double sh[4];
+    const int p = blockIdx.x;
+    if (p < P) {
+        for (int a = 0; a < A; ++a) {
+            double s = 0.0;
+            for (int b = threadIdx.x; b < nbm; b += 256) s += dls_part[((int64_t)p * nbm + b) * A + a];
+            s = block_sum(s, sh);
+            if (threadIdx.x == 0) dlogsig[p * A + a] = (float)s;
+        }
+    } else {
+        const int64_t nblk = (int64_t)nbm * P;
+        double acc[5];
+        for (int i = 0; i < 5; ++i) {
+            double s = 0.0;
+            for (int64_t b = threadIdx.x; b < nblk; b += 256) s += stat_part[b * 5 + i];
+            acc[i] = block_sum(s, sh);
+        }
+        if (threadIdx.x == 0) {
+            stats[0] = (float)(acc[0] / cnt);
+            stats[1] = (float)(acc[1] / cnt);
+            stats[2] = (float)(acc[2] / cnt);
+            stats[3] = (float)(acc[3] / cnt);
+            stats[4] = (float)adv_stat[0];
+            stats[5] = (float)adv_stat[1];
+            stats[6] = (float)(acc[4] / cnt);
+            stats[7] = (float)cnt;
+        }
+    }
+}
+
+void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu, const float* logsig,
+                          int logsig_stride, const float* act, const float* logp_old,
+                          const float* adv_s, const float* v, const float* vtarg, float clip_eps,
+                          int norm_adv, float* dmu, float* dlogsig, float* dv, float* stats, void* ws,
+                          hipStream_t s) {
+    const int P = c->d.P, N = c->d.N, A = c->d.act_dim, K = c->d.K;
+    LossWs L = loss_ws_layout(c, rs, ws, nullptr);
+    const int nbm = (rs.M + 255) / 256;
+    const dim3 grid(nbm, P);
+    const double cnt = (double)rs.M * P;
+    k_adv_partial<<<grid, 256, 0, s>>>(rs, adv_s, L.adv_part, N, c->n_g);
+    k_adv_final<<<1, 256, 0, s>>>(L.adv_part, (int64_t)nbm * P, cnt, L.adv_stat);
+    k_ppo_loss_grad<MORLAX_MAX_OUT><<<grid, 256, 0, s>>>(rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v,
+                                                        vtarg, L.adv_stat, clip_eps, norm_adv,
+                                                        (float)(1.0 / cnt), dmu, dv, L.stat_part, L.dls_part,
+                                                        N, c->n_g, A, K);
+    k_loss_final<<<P + 1, 256, 0, s>>>(L.stat_part, L.dls_part, L.adv_stat, nbm, P, A, cnt, dlogsig, stats);
+}

@@ -1,0 +1,290 @@
+// Host side of the C ABI declared in include/morlax.h: context construction (layouts of the
+// hypernet parameter vector and of theta), argument validation (all of it before the first HIP
+// call) and dispatch to the kernel launchers.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "morlax_internal.h"
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+extern "C" const char* morlax_last_error(void) { return g_err; }
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at) {
+    const int64_t F = d.hyper_width, r = d.rank, K = d.K;
+    const int out = (net == MORLAX_ACTOR) ? d.act_dim : d.K;
+    nd.n_layers = d.n_hidden + 1;
+    nd.out_dim = out;
+    int64_t hp = 0, mat = 0, vec = 0, fac = 0;
+    nd.hp_wh1 = hp; hp += F * K;
+    nd.hp_bh1 = hp; hp += F;
+    nd.hp_wh2 = hp; hp += F * F;
+    nd.hp_bh2 = hp; hp += F;
+    for (int l = 0; l < nd.n_layers; ++l) {
+        LayerDev& L = nd.layer[l];
+        L.d_in = (l == 0) ? d.obs_dim : d.width;
+        L.d_out = (l == nd.n_layers - 1) ? out : d.width;
+        L.mat_off = mat; mat += (int64_t)L.d_out * L.d_in;
+        L.vec_off = vec; vec += L.d_out;
+        L.fac_a = fac; fac += (int64_t)L.d_out * r;
+        L.fac_b = fac; fac += r * (int64_t)L.d_in;
+        L.hp_w0 = hp; hp += (int64_t)L.d_out * L.d_in;
+        L.hp_b0 = hp; hp += L.d_out;
+        L.hp_ma = hp; hp += (int64_t)L.d_out * r * F;
+        L.hp_ca = hp; hp += (int64_t)L.d_out * r;
+        L.hp_mb = hp; hp += r * (int64_t)L.d_in * F;
+        L.hp_cb = hp; hp += r * (int64_t)L.d_in;
+        L.hp_mbias = hp; hp += (int64_t)L.d_out * F;
+    }
+    nd.hp_logsig0 = nd.hp_msig = -1;
+    if (net == MORLAX_ACTOR) {
+        nd.hp_logsig0 = hp; hp += d.act_dim;
+        nd.hp_msig = hp; hp += (int64_t)d.act_dim * F;
+        vec += d.act_dim;
+    }
+    // stacked affine rows: factor rows first (in factor-vector order), then theta_vec rows
+    at.n_seg = 0;
+    int32_t q = 0;
+    auto seg = [&](int64_t hp_m, int64_t hp_c, int32_t rows) {
+        int s = at.n_seg++;
+        at.q0[s] = q;
+        at.hp_m[s] = hp_m;
+        at.hp_c[s] = hp_c;
+        q += rows;
+        at.q0[s + 1] = q;
+    };
+    if (r > 0)
+        for (int l = 0; l < nd.n_layers; ++l) {
+            const LayerDev& L = nd.layer[l];
+            seg(L.hp_ma, L.hp_ca, (int32_t)(L.d_out * r));
+            seg(L.hp_mb, L.hp_cb, (int32_t)(r * L.d_in));
+        }
+    for (int l = 0; l < nd.n_layers; ++l) seg(nd.layer[l].hp_mbias, nd.layer[l].hp_b0, nd.layer[l].d_out);
+    if (net == MORLAX_ACTOR) seg(nd.hp_msig, nd.hp_logsig0, d.act_dim);
+    at.q_total = q;
+    nd.mat_len = mat;
+    nd.vec_len = vec;
+    nd.fac_len = fac;
+    nd.hp_count = hp;
+}
+
+extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
+    if (!dims || !out) return fail(MORLAX_ERR_NULL, "morlax_create: NULL argument");
+    *out = nullptr;
+    const morlax_dims& d = *dims;
+    if (d.K < 1 || d.T < 1 || d.N < 1 || d.obs_dim < 1 || d.act_dim < 1 || d.n_hidden < 1 ||
+        d.width < 1 || d.rank < 0 || d.hyper_width < 1)
+        return fail(MORLAX_ERR_SHAPE, "morlax_create: K, T, N, obs_dim, act_dim, n_hidden, width, hyper_width must be >= 1 and rank >= 0");
+    if (d.P < 2) return fail(MORLAX_ERR_SHAPE, "morlax_create: need P > 1 trade-off vectors (got %d)", d.P);
+    if (d.N % d.P != 0)
+        return fail(MORLAX_ERR_SHAPE, "morlax_create: P = %d must divide N = %d", d.P, d.N);
+    if (d.K > MORLAX_MAX_OUT || d.act_dim > MORLAX_MAX_OUT)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: K and act_dim must be <= %d", MORLAX_MAX_OUT);
+    if (d.obs_dim > 1024) return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: obs_dim must be <= 1024");
+    if (d.n_hidden > MORLAX_MAX_LAYERS - 1)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: n_hidden must be <= %d", MORLAX_MAX_LAYERS - 1);
+    if (d.width % 16 != 0 || d.width < 16 || d.width > 2048)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: width must be a multiple of 16 in [16, 2048]");
+    if (d.rank > MORLAX_MAX_RANK)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: rank must be <= %d", MORLAX_MAX_RANK);
+    if (d.hyper_width > MORLAX_MAX_F)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: hyper_width must be <= %d", MORLAX_MAX_F);
+    if (d.act != 0 && d.act != 1) return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: act must be 0 (tanh) or 1 (SiLU)");
+    if (d.wdtype != 0 && d.wdtype != 1)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: wdtype must be 0 (fp32) or 1 (bf16)");
+    if (d.mean_tanh != 0 && d.mean_tanh != 1)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: mean_tanh must be 0 or 1");
+    if ((int64_t)(d.T + 1) * d.N >= (int64_t)1 << 31)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: (T+1) * N must stay below 2^31");
+    morlax_ctx* c = new (std::nothrow) morlax_ctx;
+    if (!c) return fail(MORLAX_ERR_HIP, "morlax_create: out of host memory");
+    memset(c, 0, sizeof(*c));
+    c->d = d;
+    c->n_g = d.N / d.P;
+    build_net(d, MORLAX_ACTOR, c->net[0], c->aff[0]);
+    build_net(d, MORLAX_CRITIC, c->net[1], c->aff[1]);
+    *out = c;
+    return MORLAX_OK;
+}
+
+extern "C" void morlax_destroy(morlax_ctx* ctx) { delete ctx; }
+
+static bool bad_net(int net) { return net != MORLAX_ACTOR && net != MORLAX_CRITIC; }
+
+extern "C" int64_t morlax_hparam_count(const morlax_ctx* c, int net) {
+    return (!c || bad_net(net)) ? -1 : c->net[net].hp_count;
+}
+extern "C" int64_t morlax_theta_mat_len(const morlax_ctx* c, int net) {
+    return (!c || bad_net(net)) ? -1 : c->net[net].mat_len;
+}
+extern "C" int64_t morlax_theta_vec_len(const morlax_ctx* c, int net) {
+    return (!c || bad_net(net)) ? -1 : c->net[net].vec_len;
+}
+
+// rows == NULL: the largest selection (all environments of a group, T+1 times).
+static int resolve_rows(const morlax_ctx* c, const morlax_rows* rows, int t_max, RowSel& rs, const char* who) {
+    if (!rows) {
+        rs.t0 = 0; rs.t_cnt = t_max; rs.j0 = 0; rs.j_cnt = c->n_g;
+    } else {
+        rs.t0 = rows->t0; rs.t_cnt = rows->t_cnt; rs.j0 = rows->j0; rs.j_cnt = rows->j_cnt;
+    }
+    if (rs.t0 < 0 || rs.t_cnt < 1 || rs.t0 + (int64_t)rs.t_cnt > t_max)
+        return fail(MORLAX_ERR_SHAPE, "%s: time slice [%d, %d+%d) outside [0, %d)", who, rs.t0, rs.t0, rs.t_cnt, t_max);
+    if (rs.j0 < 0 || rs.j_cnt < 1 || rs.j0 + (int64_t)rs.j_cnt > c->n_g)
+        return fail(MORLAX_ERR_SHAPE, "%s: group slice [%d, %d+%d) outside [0, n_g = %d)", who, rs.j0, rs.j0, rs.j_cnt, c->n_g);
+    rs.M = rs.t_cnt * rs.j_cnt;
+    return MORLAX_OK;
+}
+
+extern "C" int64_t morlax_saved_bytes(const morlax_ctx* c, int net, const morlax_rows* rows) {
+    if (!c || bad_net(net)) return -1;
+    RowSel rs;
+    if (resolve_rows(c, rows, c->d.T + 1, rs, "morlax_saved_bytes") != MORLAX_OK) return -1;
+    return mlp_saved_bytes(c, net, rs);
+}
+
+extern "C" int64_t morlax_workspace_bytes(const morlax_ctx* c, const morlax_rows* rows) {
+    if (!c) return -1;
+    RowSel rs;
+    if (resolve_rows(c, rows, c->d.T + 1, rs, "morlax_workspace_bytes") != MORLAX_OK) return -1;
+    int64_t b = hyper_ws_bytes(c);
+    int64_t m = mlp_ws_bytes(c, rs);
+    int64_t l = loss_ws_bytes(c, rs);
+    if (m > b) b = m;
+    if (l > b) b = l;
+    return b;
+}
+
+static int finish(const char* who) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(MORLAX_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
+    return MORLAX_OK;
+}
+
+#define REQ(ptr, who)                                                                   \
+    do {                                                                                \
+        if (!(ptr)) return fail(MORLAX_ERR_NULL, "%s: %s is NULL", who, #ptr);          \
+        if (!aligned16(ptr)) return fail(MORLAX_ERR_SHAPE, "%s: %s is not 16-byte aligned", who, #ptr); \
+    } while (0)
+#define OPT(ptr, who)                                                                   \
+    do {                                                                                \
+        if ((ptr) && !aligned16(ptr)) return fail(MORLAX_ERR_SHAPE, "%s: %s is not 16-byte aligned", who, #ptr); \
+    } while (0)
+
+extern "C" int morlax_env_pref_index(const morlax_ctx* ctx, int32_t* out, void* stream) {
+    const char* who = "morlax_env_pref_index";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    REQ(out, who);
+    launch_env_pref_index(ctx, out, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_hypernet_fwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
+                                   void* theta_mat, float* theta_vec, void* ws, void* stream) {
+    const char* who = "morlax_hypernet_fwd";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
+    REQ(hparams, who); REQ(w, who); REQ(theta_mat, who); REQ(theta_vec, who); REQ(ws, who);
+    launch_hypernet_fwd(ctx, net, hparams, w, theta_mat, theta_vec, ws, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
+                                   const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
+                                   void* ws, void* stream) {
+    const char* who = "morlax_hypernet_bwd";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
+    REQ(hparams, who); REQ(w, who); REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(dhparams, who);
+    REQ(ws, who);
+    launch_hypernet_bwd(ctx, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
+                                 const float* x, const morlax_rows* rows, float* out, const float* eps,
+                                 float* act, float* logp, void* saved, void* ws, void* stream) {
+    const char* who = "morlax_policy_fwd";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
+    REQ(theta_mat, who); REQ(theta_vec, who); REQ(x, who); REQ(out, who); REQ(ws, who);
+    OPT(eps, who); OPT(act, who); OPT(logp, who); OPT(saved, who);
+    if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
+    const bool any = eps || act || logp, all = eps && act && logp;
+    if (any && !all) return fail(MORLAX_ERR_NULL, "%s: eps, act and logp must be given together", who);
+    if (any && net != MORLAX_ACTOR) return fail(MORLAX_ERR_SHAPE, "%s: sampling outputs are actor-only", who);
+    RowSel rs;
+    int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
+    if (rc != MORLAX_OK) return rc;
+    launch_policy_fwd(ctx, net, theta_mat, theta_vec, x, rs, out, eps, act, logp, saved, ws, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_policy_bwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
+                                 const float* x, const morlax_rows* rows, const void* saved,
+                                 const float* dout, const float* dlogsig, float* dtheta_mat,
+                                 float* dtheta_vec, void* ws, void* stream) {
+    const char* who = "morlax_policy_bwd";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
+    REQ(theta_mat, who); REQ(theta_vec, who); REQ(x, who); REQ(saved, who); REQ(dout, who);
+    REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(ws, who);
+    OPT(dlogsig, who);
+    if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
+    if (dlogsig && net != MORLAX_ACTOR) return fail(MORLAX_ERR_SHAPE, "%s: dlogsig is actor-only", who);
+    RowSel rs;
+    int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
+    if (rc != MORLAX_OK) return rc;
+    launch_policy_bwd(ctx, net, theta_mat, theta_vec, x, rs, saved, dout, dlogsig, dtheta_mat, dtheta_vec,
+                      ws, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_vec_gae(morlax_ctx* ctx, const float* r, const float* v, const uint8_t* done,
+                              const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
+                              float* adv_s, void* stream) {
+    const char* who = "morlax_vec_gae";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    REQ(r, who); REQ(v, who); REQ(done, who); REQ(w, who); REQ(vtarg, who); REQ(adv_s, who);
+    OPT(adv_vec, who);
+    if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f))
+        return fail(MORLAX_ERR_SHAPE, "%s: gamma and lambda must lie in [0, 1]", who);
+    launch_vec_gae(ctx, r, v, done, w, gamma, lambda, adv_vec, vtarg, adv_s, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
+                                    const float* logsig, int32_t logsig_stride, const float* act,
+                                    const float* logp_old, const float* adv_s, const float* v,
+                                    const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
+                                    float* dlogsig, float* dv, float* stats, void* ws, void* stream) {
+    const char* who = "morlax_ppo_loss_grad";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
+    REQ(mu, who); REQ(act, who); REQ(logp_old, who); REQ(adv_s, who); REQ(v, who);
+    REQ(vtarg, who); REQ(dmu, who); REQ(dlogsig, who); REQ(dv, who); REQ(stats, who); REQ(ws, who);
+    if (!logsig) return fail(MORLAX_ERR_NULL, "%s: logsig is NULL", who);
+    if ((reinterpret_cast<uintptr_t>(logsig) & 3u) != 0)
+        return fail(MORLAX_ERR_SHAPE, "%s: logsig is not 4-byte aligned", who);
+    if (logsig_stride < ctx->d.act_dim)
+        return fail(MORLAX_ERR_SHAPE, "%s: logsig_stride %d < act_dim %d", who, logsig_stride, ctx->d.act_dim);
+    if (!(clip_eps >= 0.f)) return fail(MORLAX_ERR_SHAPE, "%s: clip_eps must be >= 0", who);
+    RowSel rs;
+    int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
+    if (rc != MORLAX_OK) return rc;
+    launch_ppo_loss_grad(ctx, rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps,
+                         norm_adv, dmu, dlogsig, dv, stats, ws, (hipStream_t)stream);
+    return finish(who);
+}

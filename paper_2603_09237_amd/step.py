@@ -1,0 +1,116 @@
+"""Buffers and call sequence of one MORLAX update step on one GPU.
+
+`UpdateStep` owns the device tensors (torch is used for memory and the stream only) and issues the
+C-ABI calls in the order of the method (paper Sec. III-C): rollout forward of the actor and critic
+families with the rollout-time hypernet parameters, vector GAE, then for every epoch and minibatch
+hypernet forward, grouped forward, loss, grouped backward and hypernet backward for both nets.
+No arithmetic happens here.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding
+from .binding import ACTOR, CRITIC
+from .configs import Config, WDTYPE_BF16
+
+
+class UpdateStep:
+    def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.dev = torch.device(device)
+        self.ctx = binding.Context.from_config(cfg)
+        c, ctx = cfg, self.ctx
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        wdt = torch.bfloat16 if cfg.wdtype == WDTYPE_BF16 else torch.float32
+        T, N, K, A, O, P = c.T, c.N, c.K, c.act_dim, c.obs_dim, c.P
+        self.w = torch.empty(P, K, **f32)
+        self.obs = torch.empty(T + 1, N, O, **f32)
+        self.rewards = torch.empty(T, N, K, **f32)
+        self.dones = torch.empty(T, N, dtype=torch.uint8, device=self.dev)
+        self.eps = torch.empty(T, N, A, **f32)
+        self.hp = {}
+        self.hp_old = {}
+        self.theta_mat, self.theta_vec, self.dtheta_mat, self.dtheta_vec, self.dhp = {}, {}, {}, {}, {}
+        for net in (ACTOR, CRITIC):
+            n = ctx.hparam_count(net)
+            self.hp[net] = torch.empty(n, **f32)
+            self.hp_old[net] = torch.empty(n, **f32)
+            self.dhp[net] = torch.zeros(n, **f32)
+            self.theta_mat[net] = torch.empty(P, ctx.theta_mat_len(net), dtype=wdt, device=self.dev)
+            self.theta_vec[net] = torch.empty(P, ctx.theta_vec_len(net), **f32)
+            self.dtheta_mat[net] = torch.empty(P, ctx.theta_mat_len(net), **f32)
+            self.dtheta_vec[net] = torch.empty(P, ctx.theta_vec_len(net), **f32)
+        self.mu_old = torch.empty(T, N, A, **f32)
+        self.act = torch.empty(T, N, A, **f32)
+        self.logp_old = torch.empty(T, N, **f32)
+        self.v_roll = torch.empty(T + 1, N, K, **f32)
+        self.vtarg = torch.empty(T, N, K, **f32)
+        self.adv_s = torch.empty(T, N, **f32)
+        self.adv_vec = torch.empty(T, N, K, **f32) if keep_adv_vec else None
+        self.mu = torch.zeros(T, N, A, **f32)
+        self.v = torch.zeros(T, N, K, **f32)
+        self.dmu = torch.zeros(T, N, A, **f32)
+        self.dv = torch.zeros(T, N, K, **f32)
+        self.dlogsig = torch.zeros(P, A, **f32)
+        self.stats = torch.zeros(8, **f32)
+        if c.n_g % c.minibatches:
+            raise ValueError("minibatches must divide n_g")
+        self.mb_rows = [(0, T, b * (c.n_g // c.minibatches), c.n_g // c.minibatches)
+                        for b in range(c.minibatches)]
+        self.saved = {net: torch.empty(ctx.saved_bytes(net, self.mb_rows[0]), dtype=torch.uint8, device=self.dev)
+                      for net in (ACTOR, CRITIC)}
+        self.ws = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device=self.dev)
+        self.full_T = (0, T, 0, c.n_g)
+        self.full_T1 = (0, T + 1, 0, c.n_g)
+        self.logsig_off = ctx.theta_vec_len(ACTOR) - A
+
+    def load_inputs(self, d: dict):
+        t = self.torch
+        put = lambda dst, src: dst.copy_(t.from_numpy(np.ascontiguousarray(src)))
+        put(self.w, d["w"]); put(self.obs, d["obs"]); put(self.rewards, d["rewards"])
+        put(self.dones, d["dones"]); put(self.eps, d["eps"])
+        put(self.hp_old[ACTOR], d["hparams_actor_old"]); put(self.hp_old[CRITIC], d["hparams_critic_old"])
+        put(self.hp[ACTOR], d["hparams_actor"]); put(self.hp[CRITIC], d["hparams_critic"])
+        t.cuda.synchronize()
+
+    def rollout(self):
+        c, ctx = self.cfg, self.ctx
+        for net in (ACTOR, CRITIC):
+            ctx.hypernet_fwd(net, self.hp_old[net], self.w, self.theta_mat[net], self.theta_vec[net], self.ws)
+        ctx.policy_fwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, self.full_T, self.mu_old,
+                       eps=self.eps, act=self.act, logp=self.logp_old, saved=None, ws=self.ws)
+        ctx.policy_fwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, self.full_T1, self.v_roll,
+                       saved=None, ws=self.ws)
+        ctx.vec_gae(self.rewards, self.v_roll, self.dones, self.w, c.gamma, c.lam, self.adv_vec, self.vtarg,
+                    self.adv_s)
+
+    def minibatch(self, rows):
+        c, ctx = self.cfg, self.ctx
+        for net in (ACTOR, CRITIC):
+            ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], self.ws)
+        ctx.policy_fwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, rows, self.mu,
+                       saved=self.saved[ACTOR], ws=self.ws)
+        ctx.policy_fwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, rows, self.v,
+                       saved=self.saved[CRITIC], ws=self.ws)
+        logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
+        ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, self.adv_s,
+                          self.v, self.vtarg, c.clip_eps, 1, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
+        ctx.policy_bwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, rows, self.saved[ACTOR],
+                       self.dmu, self.dlogsig, self.dtheta_mat[ACTOR], self.dtheta_vec[ACTOR], self.ws)
+        ctx.policy_bwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, rows, self.saved[CRITIC],
+                       self.dv, None, self.dtheta_mat[CRITIC], self.dtheta_vec[CRITIC], self.ws)
+        for net in (ACTOR, CRITIC):
+            ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net], self.dhp[net],
+                             self.ws)
+
+    def run(self, on_minibatch=None):
+        """One whole update step.  `on_minibatch(e, b)` (optional) is called after each minibatch."""
+        self.rollout()
+        for e in range(self.cfg.epochs):
+            for b, rows in enumerate(self.mb_rows):
+                self.minibatch(rows)
+                if on_minibatch is not None:
+                    on_minibatch(e, b)

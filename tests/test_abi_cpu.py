@@ -1,0 +1,103 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, computes the layouts the oracle and the generator agree on, and rejects bad arguments
+before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import morlax_oracle as orc
+from paper_2603_09237_amd import binding, configs, inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_09237_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "morlax.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(morlax_[a-z0-9_]+)\s*\(", hdr)))
+    assert len(names) >= 15
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_layout_queries_match_oracle_and_generator(lib):
+    for cid, cfg in configs.CONFIGS.items():
+        ctx = binding.Context.from_config(cfg)
+        for net in (0, 1):
+            assert ctx.hparam_count(net) == orc.hparam_count(cfg, net) == inputs.hparam_count(cfg, net)
+            assert ctx.theta_mat_len(net) == orc.theta_mat_len(cfg, net)
+            assert ctx.theta_vec_len(net) == orc.theta_vec_len(cfg, net)
+            assert ctx.saved_bytes(net, (0, cfg.T, 0, cfg.n_g // cfg.minibatches)) > 0
+        assert ctx.workspace_bytes() >= ctx.workspace_bytes((0, 1, 0, 1)) > 0
+        ctx.close()
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(P=1), binding.ERR_SHAPE), (dict(P=3), binding.ERR_SHAPE), (dict(K=0), binding.ERR_SHAPE),
+    (dict(T=0), binding.ERR_SHAPE), (dict(rank=-1), binding.ERR_SHAPE), (dict(K=17), binding.ERR_UNSUPPORTED),
+    (dict(width=40), binding.ERR_UNSUPPORTED), (dict(act=2), binding.ERR_UNSUPPORTED),
+    (dict(wdtype=3), binding.ERR_UNSUPPORTED), (dict(rank=64), binding.ERR_UNSUPPORTED),
+    (dict(hyper_width=128), binding.ERR_UNSUPPORTED), (dict(n_hidden=9), binding.ERR_UNSUPPORTED),
+])
+def test_create_rejects_bad_dims(lib, over, code):
+    d = configs.CONFIGS[1].dims_dict()
+    d.update(over)
+    with pytest.raises(binding.MorlaxError) as e:
+        binding.Context(**d)
+    assert e.value.code == code
+    assert lib.morlax_last_error().decode() != ""
+
+
+def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
+    cfg = configs.CONFIGS[1]
+    ctx = binding.Context.from_config(cfg)
+    good = 0x10000  # aligned fake device address; never dereferenced because validation fails first
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.vec_gae(None, good, good, good, 0.99, 0.95, None, good, good, stream=0)
+    assert e.value.code == binding.ERR_NULL
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.vec_gae(good + 4, good, good, good, 0.99, 0.95, None, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.vec_gae(good, good, good, good, 1.5, 0.95, None, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.hypernet_fwd(2, good, good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.hypernet_bwd(0, good, good, None, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_NULL
+    bad_rows = [(0, cfg.T + 2, 0, cfg.n_g), (0, 0, 0, 1), (0, 1, 0, cfg.n_g + 1), (-1, 1, 0, 1), (0, 1, cfg.n_g, 1)]
+    for rows in bad_rows:
+        with pytest.raises(binding.MorlaxError) as e:
+            ctx.policy_fwd(0, good, good, good, rows, good, ws=good, stream=0)
+        assert e.value.code == binding.ERR_SHAPE, rows
+        with pytest.raises(binding.MorlaxError) as e:
+            ctx.ppo_loss_grad(rows, good, good, 4, good, good, good, good, good, 0.2, 1, good, good, good, good,
+                              good, stream=0)
+        assert e.value.code == binding.ERR_SHAPE, rows
+    with pytest.raises(binding.MorlaxError) as e:      # sampling outputs must come together
+        ctx.policy_fwd(0, good, good, good, (0, 1, 0, 1), good, eps=good, ws=good, stream=0)
+    assert e.value.code == binding.ERR_NULL
+    with pytest.raises(binding.MorlaxError) as e:      # ... and only for the actor
+        ctx.policy_fwd(1, good, good, good, (0, 1, 0, 1), good, eps=good, act=good, logp=good, ws=good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.policy_bwd(1, good, good, good, (0, 1, 0, 1), good, good, good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE           # dlogsig is actor-only
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.ppo_loss_grad((0, 1, 0, 1), good, good, 1, good, good, good, good, good, 0.2, 1, good, good, good,
+                          good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE           # logsig_stride < act_dim
+    ctx.close()
