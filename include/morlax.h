@@ -157,6 +157,17 @@ int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* 
                          const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
                          float* dlogsig, float* dv, float* stats, void* ws, void* stream);
 
+/* Timing aid for benchmarks (not part of the method).  Between morlax_profile_begin() and
+ * morlax_profile_end() every grouped-GEMM launch of policy_fwd / policy_bwd on this ctx is bracketed
+ * by a pair of HIP events recorded on the launch stream.  morlax_profile_end() waits for the last
+ * event (it synchronises with the stream) and returns, per GEMM kind k in
+ * {0 forward first layer, 1 forward hidden layer, 2 dX hidden layer, 3 dW hidden layer, 4 dW first
+ * layer}: ms[k] total kernel time, launches[k], flops[k] total algorithmic flops (2 * rows * cols *
+ * depth summed over preferences; tile padding not counted).  The three arrays are HOST pointers of
+ * length 5.  Profiling stops at morlax_profile_end(). */
+int morlax_profile_begin(morlax_ctx* ctx);
+int morlax_profile_end(morlax_ctx* ctx, double* ms, int64_t* launches, double* flops);
+
 #ifdef __cplusplus
 }
 #endif

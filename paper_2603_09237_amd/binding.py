@@ -36,7 +36,10 @@ _lib = None
 EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hparam_count",
            "morlax_theta_mat_len", "morlax_theta_vec_len", "morlax_saved_bytes", "morlax_workspace_bytes",
            "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
-           "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad")
+           "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad", "morlax_profile_begin",
+           "morlax_profile_end")
+
+GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first")
 
 
 def load():
@@ -47,6 +50,9 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_09237_amd.build` "
                           "(there is no CPU fallback)")
+    # torch provides the device memory and the streams, so the library must bind to the HIP runtime
+    # torch has loaded (two runtimes in one process do not share devices): import torch first.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     lib.morlax_create.argtypes = [C.POINTER(Dims), C.POINTER(vp)]
@@ -70,6 +76,10 @@ def load():
     lib.morlax_vec_gae.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
                                          vp, vp, vp, vp, vp, vp]
+    lib.morlax_profile_begin.argtypes = [vp]
+    lib.morlax_profile_begin.restype = C.c_int
+    lib.morlax_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double)]
+    lib.morlax_profile_end.restype = C.c_int
     for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
                  "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad"):
         getattr(lib, name).restype = C.c_int
@@ -144,6 +154,16 @@ class Context:
 
     def workspace_bytes(self, rows=None):
         return self.lib.morlax_workspace_bytes(self.h, _rows(rows))
+
+    def profile_begin(self):
+        self._check(self.lib.morlax_profile_begin(self.h))
+
+    def profile_end(self):
+        """-> {kind: (total_ms, launches, total_flops)} for the grouped-GEMM launches since profile_begin."""
+        n = len(GEMM_KINDS)
+        ms, cnt, fl = (C.c_double * n)(), (C.c_int64 * n)(), (C.c_double * n)()
+        self._check(self.lib.morlax_profile_end(self.h, ms, cnt, fl))
+        return {k: (ms[i], cnt[i], fl[i]) for i, k in enumerate(GEMM_KINDS)}
 
     # ---- ops
     def env_pref_index(self, out, stream=None):

@@ -338,12 +338,69 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi> g
     }
 }
 
+// ---- optional event timing of the GEMM launches ------------------------------------------------
+#include <vector>
+struct GemmProf {
+    struct Rec { hipEvent_t a, b; int kind; double flops; };
+    std::vector<Rec> recs;
+    size_t used = 0;
+    bool on = false;
+};
+
+int prof_begin(morlax_ctx* c) {
+    if (!c->prof) c->prof = new GemmProf;
+    c->prof->used = 0;
+    c->prof->on = true;
+    return 0;
+}
+
+void prof_free(morlax_ctx* c) {
+    if (!c->prof) return;
+    for (auto& r : c->prof->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    delete c->prof;
+    c->prof = nullptr;
+}
+
+int prof_end(morlax_ctx* c, double* ms, int64_t* launches, double* flops) {
+    GemmProf* pr = c->prof;
+    pr->on = false;
+    for (int k = 0; k < MORLAX_GEMM_KINDS; ++k) { ms[k] = 0.0; launches[k] = 0; flops[k] = 0.0; }
+    if (pr->used == 0) return 0;
+    if (hipEventSynchronize(pr->recs[pr->used - 1].b) != hipSuccess) return -1;
+    for (size_t i = 0; i < pr->used; ++i) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, pr->recs[i].a, pr->recs[i].b) != hipSuccess) return -1;
+        ms[pr->recs[i].kind] += t;
+        launches[pr->recs[i].kind] += 1;
+        flops[pr->recs[i].kind] += pr->recs[i].flops;
+    }
+    pr->used = 0;
+    return 0;
+}
+
+static GemmProf::Rec* prof_take(const morlax_ctx* c, int kind, double flops) {
+    GemmProf* pr = c->prof;
+    if (!pr || !pr->on) return nullptr;
+    if (pr->used == pr->recs.size()) {
+        GemmProf::Rec r;
+        if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return nullptr;
+        pr->recs.push_back(r);
+    }
+    GemmProf::Rec* r = &pr->recs[pr->used++];
+    r->kind = kind;
+    r->flops = flops;
+    return r;
+}
+
 template <typename T, int KA, int KB, class Epi>
-static void run_gemm(GemmArgs<T, KA, KB, Epi>& g, int P, hipStream_t s) {
+static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi>& g, int P, hipStream_t s) {
     g.tiles_m = (g.a.rows + BM - 1) / BM;
     g.tiles_n = (g.b.rows + BN - 1) / BN;
     const int nb = g.tiles_m * g.tiles_n * P;
+    GemmProf::Rec* r = prof_take(c, kind, 2.0 * g.a.rows * (double)g.b.rows * g.a.kdim * P);
+    if (r) (void)hipEventRecord(r->a, s);
     k_grouped_gemm<T, KA, KB, Epi><<<nb, 256, 0, s>>>(g);
+    if (r) (void)hipEventRecord(r->b, s);
 }
 
 // ---- output layer ------------------------------------------------------------------------------
@@ -646,14 +703,14 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             g.b.vec_ok = (O % VE == 0);
             g.a_pstride = 0; g.b_pstride = nd.mat_len;
             g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
-            run_gemm(g, P, s);
+            run_gemm(c, 0, g, P, s);
         } else {
             GemmArgs<T, SRC_KCONTIG, SRC_KCONTIG, EpiFwd<T>> g;
             g.a.base = Hbuf(l - 1); g.a.ld = W; g.a.rows = M; g.a.kdim = W; g.a.rm = rm; g.a.vec_ok = true;
             g.b.base = theta_mat + Ld.mat_off; g.b.ld = W; g.b.rows = W; g.b.kdim = W; g.b.rm = rm; g.b.vec_ok = true;
             g.a_pstride = (int64_t)M * W; g.b_pstride = nd.mat_len;
             g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
-            run_gemm(g, P, s);
+            run_gemm(c, 1, g, P, s);
         }
     }
     const LayerDev& Lh = nd.layer[L];
@@ -704,14 +761,14 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             g.b.base = Hbuf(l - 1); g.b.ld = W; g.b.rows = W; g.b.kdim = M; g.b.rm = rm; g.b.vec_ok = true;
             g.a_pstride = (int64_t)M * W; g.b_pstride = (int64_t)M * W;
             g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
-            run_gemm(g, P, s);
+            run_gemm(c, 3, g, P, s);
             GemmArgs<T, SRC_KCONTIG, SRC_KSTRIDED, EpiDx<T>> h;
             h.a.base = dZbuf(l); h.a.ld = W; h.a.rows = M; h.a.kdim = W; h.a.rm = rm; h.a.vec_ok = true;
             h.b.base = theta_mat + Ld.mat_off; h.b.ld = W; h.b.rows = W; h.b.kdim = W; h.b.rm = rm; h.b.vec_ok = true;
             h.a_pstride = (int64_t)M * W; h.b_pstride = nd.mat_len;
             h.epi.G = Gbuf(l - 1); h.epi.dZ = dZbuf(l - 1); h.epi.ld = W; h.epi.part = part;
             h.e0_pstride = (int64_t)M * W; h.e1_pstride = 0; h.e2_pstride = 0;
-            run_gemm(h, P, s);
+            run_gemm(c, 2, h, P, s);
             n_part = (M + BM - 1) / BM;
         } else {
             GemmArgs<T, SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw> g;
@@ -719,7 +776,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             g.b.base = x; g.b.ld = O; g.b.rows = O; g.b.kdim = M; g.b.rm = rm; g.b.vec_ok = false;
             g.a_pstride = (int64_t)M * W; g.b_pstride = 0;
             g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
-            run_gemm(g, P, s);
+            run_gemm(c, 4, g, P, s);
         }
     }
     (void)VE;

@@ -119,7 +119,24 @@ extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
     return MORLAX_OK;
 }
 
-extern "C" void morlax_destroy(morlax_ctx* ctx) { delete ctx; }
+extern "C" void morlax_destroy(morlax_ctx* ctx) {
+    if (!ctx) return;
+    prof_free(ctx);
+    delete ctx;
+}
+
+extern "C" int morlax_profile_begin(morlax_ctx* ctx) {
+    if (!ctx) return fail(MORLAX_ERR_NULL, "morlax_profile_begin: ctx is NULL");
+    if (prof_begin(ctx) != 0) return fail(MORLAX_ERR_HIP, "morlax_profile_begin: event creation failed");
+    return MORLAX_OK;
+}
+
+extern "C" int morlax_profile_end(morlax_ctx* ctx, double* ms, int64_t* launches, double* flops) {
+    if (!ctx || !ms || !launches || !flops) return fail(MORLAX_ERR_NULL, "morlax_profile_end: NULL argument");
+    if (!ctx->prof) return fail(MORLAX_ERR_SHAPE, "morlax_profile_end: profiling was not started");
+    if (prof_end(ctx, ms, launches, flops) != 0) return fail(MORLAX_ERR_HIP, "morlax_profile_end: event query failed");
+    return MORLAX_OK;
+}
 
 static bool bad_net(int net) { return net != MORLAX_ACTOR && net != MORLAX_CRITIC; }
 

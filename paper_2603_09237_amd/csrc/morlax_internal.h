@@ -42,12 +42,20 @@ struct NetDev {
     LayerDev layer[MORLAX_MAX_LAYERS];
 };
 
+struct GemmProf;  // event pairs around grouped-GEMM launches (kernels_mlp.hip)
+
 struct morlax_ctx {
     morlax_dims d;
     int32_t n_g;
     NetDev net[2];
     AffineTable aff[2];
+    GemmProf* prof;  // NULL unless morlax_profile_begin() was called
 };
+
+#define MORLAX_GEMM_KINDS 5  // fwd first layer, fwd hidden, dX hidden, dW hidden, dW first layer
+int prof_begin(morlax_ctx* c);
+int prof_end(morlax_ctx* c, double* ms, int64_t* launches, double* flops);
+void prof_free(morlax_ctx* c);
 
 struct RowSel {  // a validated morlax_rows plus derived sizes
     int32_t t0, t_cnt, j0, j_cnt;
