@@ -69,39 +69,39 @@ __device__ inline int find_seg(const AffineTable& at, int q) {
     return s;
 }
 
-// Stacked affine map: row q for every preference.  Thread per row; f staged in LDS in tiles of 64 p.
+// Stacked affine map: row q for every preference.  Thread per row with its M row in registers; f[p, :]
+// is read through wave-uniform addresses (scalar loads), so the inner product costs no LDS traffic.
 __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const float* __restrict__ hp,
                                                      const float* __restrict__ f, float* __restrict__ fac,
                                                      float* __restrict__ theta_vec, int P, int F,
                                                      int64_t fac_len, int64_t vec_len) {
-    __shared__ float sf[64][MORLAX_MAX_F];
     const int q = blockIdx.x * 256 + threadIdx.x;
-    const bool ok = q < at.q_total;
+    if (q >= at.q_total) return;
     float m[MORLAX_MAX_F];
-    float c = 0.f;
-    if (ok) {
-        const int s = find_seg(at, q);
-        const int64_t loc = q - at.q0[s];
-        c = hp[at.hp_c[s] + loc];
-        const float* mr = hp + at.hp_m[s] + loc * F;
+    const int s = find_seg(at, q);
+    const int64_t loc = q - at.q0[s];
+    const float c = hp[at.hp_c[s] + loc];
+    const float* mr = hp + at.hp_m[s] + loc * F;
 #pragma unroll
-        for (int j = 0; j < MORLAX_MAX_F; ++j) m[j] = (j < F) ? mr[j] : 0.f;
-    }
-    for (int p0 = 0; p0 < P; p0 += 64) {
-        const int np = (P - p0 < 64) ? (P - p0) : 64;
-        __syncthreads();
-        for (int i = threadIdx.x; i < np * F; i += 256) sf[i / F][i % F] = f[(int64_t)p0 * F + i];
-        __syncthreads();
-        if (ok) {
-            for (int pp = 0; pp < np; ++pp) {
-                float a = c;
+    for (int j = 0; j < MORLAX_MAX_F; ++j) m[j] = (j < F) ? mr[j] : 0.f;
+    float* dst = (q < fac_len) ? (fac + q) : (theta_vec + (q - fac_len));
+    const int64_t stride = (q < fac_len) ? fac_len : vec_len;
+    if (F == 32) {
+        for (int p = 0; p < P; ++p) {
+            const float* fp = f + (int64_t)p * 32;
+            float a = c;
 #pragma unroll
-                for (int j = 0; j < MORLAX_MAX_F; ++j)
-                    if (j < F) a += m[j] * sf[pp][j];
-                const int64_t p = p0 + pp;
-                if (q < fac_len) fac[p * fac_len + q] = a;
-                else theta_vec[p * vec_len + (q - fac_len)] = a;
-            }
+            for (int j = 0; j < 32; ++j) a += m[j] * fp[j];
+            dst[(int64_t)p * stride] = a;
+        }
+    } else {
+        for (int p = 0; p < P; ++p) {
+            const float* fp = f + (int64_t)p * F;
+            float a = c;
+#pragma unroll
+            for (int j = 0; j < MORLAX_MAX_F; ++j)
+                if (j < F) a += m[j] * fp[j];
+            dst[(int64_t)p * stride] = a;
         }
     }
 }
@@ -357,42 +357,45 @@ __device__ inline float grad_row(const float* __restrict__ dfac, const float* __
     return (q < fac_len) ? dfac[p * fac_len + q] : dvec[p * vec_len + (q - fac_len)];
 }
 
-// dM[q, :] = sum_p g[p, q] f[p, :],  dc[q] = sum_p g[p, q]  (g: gradient of the stacked affine rows)
+// dM[q, :] = sum_p g[p, q] f[p, :],  dc[q] = sum_p g[p, q]  (g: gradient of the stacked affine rows).
+// Thread per row, p ascending, f[p, :] through wave-uniform (scalar) loads.
 __global__ __launch_bounds__(256) void k_hyper_dM(AffineTable at, const float* __restrict__ f,
                                                  const float* __restrict__ dfac, const float* __restrict__ dvec,
                                                  float* __restrict__ dhp, int P, int F, int64_t fac_len,
                                                  int64_t vec_len) {
-    __shared__ float sf[64][MORLAX_MAX_F];
     const int q = blockIdx.x * 256 + threadIdx.x;
-    const bool ok = q < at.q_total;
+    if (q >= at.q_total) return;
     float acc[MORLAX_MAX_F];
 #pragma unroll
     for (int j = 0; j < MORLAX_MAX_F; ++j) acc[j] = 0.f;
     float dc = 0.f;
-    for (int p0 = 0; p0 < P; p0 += 64) {
-        const int np = (P - p0 < 64) ? (P - p0) : 64;
-        __syncthreads();
-        for (int i = threadIdx.x; i < np * F; i += 256) sf[i / F][i % F] = f[(int64_t)p0 * F + i];
-        __syncthreads();
-        if (ok) {
-            for (int pp = 0; pp < np; ++pp) {
-                const float g = grad_row(dfac, dvec, p0 + pp, q, fac_len, vec_len);
-                dc += g;
+    const float* src = (q < fac_len) ? (dfac + q) : (dvec + (q - fac_len));
+    const int64_t stride = (q < fac_len) ? fac_len : vec_len;
+    if (F == 32) {
+        for (int p = 0; p < P; ++p) {
+            const float g = src[(int64_t)p * stride];
+            const float* fp = f + (int64_t)p * 32;
+            dc += g;
 #pragma unroll
-                for (int j = 0; j < MORLAX_MAX_F; ++j)
-                    if (j < F) acc[j] += g * sf[pp][j];
-            }
+            for (int j = 0; j < 32; ++j) acc[j] += g * fp[j];
+        }
+    } else {
+        for (int p = 0; p < P; ++p) {
+            const float g = src[(int64_t)p * stride];
+            const float* fp = f + (int64_t)p * F;
+            dc += g;
+#pragma unroll
+            for (int j = 0; j < MORLAX_MAX_F; ++j)
+                if (j < F) acc[j] += g * fp[j];
         }
     }
-    if (ok) {
-        const int s = find_seg(at, q);
-        const int64_t loc = q - at.q0[s];
-        dhp[at.hp_c[s] + loc] = dc;
-        float* mr = dhp + at.hp_m[s] + loc * F;
+    const int s = find_seg(at, q);
+    const int64_t loc = q - at.q0[s];
+    dhp[at.hp_c[s] + loc] = dc;
+    float* mr = dhp + at.hp_m[s] + loc * F;
 #pragma unroll
-        for (int j = 0; j < MORLAX_MAX_F; ++j)
-            if (j < F) mr[j] = acc[j];
-    }
+    for (int j = 0; j < MORLAX_MAX_F; ++j)
+        if (j < F) mr[j] = acc[j];
 }
 
 // df partials: part[chunk, p, j] = sum over the chunk's rows q of g[p, q] M[q, j].

@@ -12,13 +12,14 @@
 // axis in memory (W in the dX product, both operands of the dW product) are transposed on the way
 // into LDS.  The skinny output layer (<= 16 columns) uses 16x16 MFMA tiles straight from global
 // memory in the forward pass and plain vector code in the backward pass.
+#include <type_traits>
+
 #include "morlax_internal.h"
 #include "numeric.h"
 
 #define BM 128
 #define BN 128
-#define PITCH 80           // bytes per LDS tile row: four 16-byte chunks + 16 bytes of padding
-#define TILE_BYTES (128 * PITCH)
+#define GEMM_NCH 4         // 16-byte chunks of the contraction axis staged per step and operand row
 #define OUT_PITCH 16       // floats per row of the saved head output
 
 enum { SRC_KCONTIG = 0, SRC_KSTRIDED = 1, SRC_X_KCONTIG = 2, SRC_X_KSTRIDED = 3 };
@@ -45,19 +46,26 @@ template <> __device__ inline uint4 pack_chunk<bf16_t>(const float* v) {
                       pack2((bf16_t)v[4], (bf16_t)v[5]), pack2((bf16_t)v[6], (bf16_t)v[7]));
 }
 
-// One GEMM operand: a [rows x Kdim] matrix of which a workgroup stages 128 rows x (4 chunks) per step.
-template <typename T, int KIND>
+// One GEMM operand: a [rows x kdim] matrix of which a workgroup stages 128 rows x NCH 16-byte chunks of
+// the contraction axis per step.  FAST = every access is a full, aligned vector (the launcher checks
+// the shapes): loads are branch-free, out-of-range rows are clamped to a valid row (their results are
+// never stored) and out-of-range contraction indices are masked to zero.  !FAST = element-wise loads
+// with bounds checks, used only where a dimension is odd (first layer with an odd observation width).
+template <typename T, int KIND, bool FAST, int NCH>
 struct Operand {
     const void* base;  // T* (compact kinds) or float* (x kinds), already offset to preference p
     int64_t ld;        // compact: elements between consecutive slow-axis indices; x: obs_dim
     int rows, kdim;    // valid extent
     RowMap rm;
     int p;
-    bool vec_ok;       // 16-byte loads allowed (alignment)
 
     static constexpr int VE = Elems<T>::VE;
+    static constexpr int PITCH = NCH * 16 + 16;
+    static constexpr int CPT = NCH / 2;  // chunks per thread (128 * NCH / 256)
+    static constexpr bool PAIR = (KIND == SRC_KSTRIDED && sizeof(T) == 2 && FAST);
 
-    // element (row r of the operand, contraction index k), zero outside the valid extent
+    const char* ptr[CPT];  // per-thread source pointers, set by init()
+
     __device__ inline float elem(int r, int k) const {
         if (r >= rows || k >= kdim) return 0.f;
         if (KIND == SRC_KCONTIG) return to_f(reinterpret_cast<const T*>(base)[(int64_t)r * ld + k]);
@@ -66,75 +74,169 @@ struct Operand {
         return reinterpret_cast<const float*>(base)[rm.row(p, k) * ld + r];
     }
 
-    // Stage the tile rows [r0, r0+128) x contraction [k0, k0 + 4*VE) into registers (two chunks).
-    __device__ inline void load(int r0, int k0, uint4 regs[2]) const {
+    // thread -> (tile row, chunk) of its i-th chunk
+    __device__ static inline int trow(int i) {
         const int tid = threadIdx.x;
-        if (KIND == SRC_KCONTIG || KIND == SRC_X_KCONTIG) {
+        if (KIND == SRC_KCONTIG || KIND == SRC_X_KCONTIG) return (tid + 256 * i) / NCH;
+        if (PAIR) return 2 * (tid % 64);
+        return tid % 128;
+    }
+    __device__ static inline int tchunk(int i) {
+        const int tid = threadIdx.x;
+        if (KIND == SRC_KCONTIG || KIND == SRC_X_KCONTIG) return (tid + 256 * i) % NCH;
+        if (PAIR) return tid / 64 + 4 * (i / 2);  // chunks 2i and 2i+1 of a pair thread share the k range
+        return tid / 128 + 2 * i;
+    }
+
+    __device__ inline void init(int r0) {
+        if (!FAST) return;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int c = tid + 256 * i, r = r0 + c / 4, k = k0 + (c % 4) * VE;
-                if (KIND == SRC_KCONTIG && vec_ok && r < rows && k + VE <= kdim) {
-                    regs[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(base) + (int64_t)r * ld + k);
-                } else if (KIND == SRC_X_KCONTIG && vec_ok && r < rows && k + VE <= kdim) {
-                    const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) +
-                                                                        rm.row(p, r) * ld + k);
-                    float v[8];
-#pragma unroll
-                    for (int q = 0; q < VE / 4; ++q) {
-                        const float4 f = src[q];
-                        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
-                    }
-                    regs[i] = pack_chunk<T>(v);
-                } else {
-                    float v[8];
-#pragma unroll
-                    for (int e = 0; e < VE; ++e) v[e] = elem(r, k + e);
-                    regs[i] = pack_chunk<T>(v);
-                }
-            }
-        } else if (KIND == SRC_KSTRIDED && sizeof(T) == 2 && vec_ok) {
-            // bf16: a thread reads a pair of adjacent rows for 8 consecutive k and splits it into two chunks
-            const int r = r0 + 2 * (tid % 64), k = k0 + (tid / 64) * 8;
-            uint32_t d[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                d[e] = 0u;
-                if (r < rows && k + e < kdim)
-                    d[e] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(base) + (int64_t)(k + e) * ld + r);
-            }
-            regs[0] = make_uint4((d[0] & 0xffffu) | (d[1] << 16), (d[2] & 0xffffu) | (d[3] << 16),
-                                 (d[4] & 0xffffu) | (d[5] << 16), (d[6] & 0xffffu) | (d[7] << 16));
-            regs[1] = make_uint4((d[0] >> 16) | (d[1] & 0xffff0000u), (d[2] >> 16) | (d[3] & 0xffff0000u),
-                                 (d[4] >> 16) | (d[5] & 0xffff0000u), (d[6] >> 16) | (d[7] & 0xffff0000u));
-        } else {
-            // a thread builds chunk (row r, 16 bytes of k) from VE strided loads; adjacent lanes -> adjacent rows
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int r = r0 + tid % 128, k = k0 + (tid / 128 + 2 * i) * VE;
-                float v[8];
-#pragma unroll
-                for (int e = 0; e < VE; ++e) v[e] = elem(r, k + e);
-                regs[i] = pack_chunk<T>(v);
+        for (int i = 0; i < CPT; ++i) {
+            int r = r0 + trow(i);
+            if (KIND == SRC_KCONTIG) {
+                r = r < rows ? r : rows - 1;
+                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const T*>(base) + (int64_t)r * ld + tchunk(i) * VE);
+            } else if (KIND == SRC_X_KCONTIG) {
+                r = r < rows ? r : rows - 1;
+                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const float*>(base) + rm.row(p, r) * ld +
+                                                       tchunk(i) * VE);
+            } else if (KIND == SRC_KSTRIDED) {
+                const int lim = PAIR ? rows - 2 : rows - 1;
+                r = r < lim ? r : lim;
+                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const T*>(base) + r);
+            } else {
+                r = r < rows ? r : rows - 1;
+                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const float*>(base) + r);
             }
         }
     }
 
-    __device__ inline void store(unsigned char* tile, const uint4 regs[2]) const {
-        const int tid = threadIdx.x;
-        if (KIND == SRC_KCONTIG || KIND == SRC_X_KCONTIG) {
+    // Raw staging registers per thread: the loads of step k+1 are issued before the products of step k
+    // and nothing touches the loaded values until store(), so the load latency overlaps the MFMAs.
+    static constexpr bool XSRC = (KIND == SRC_X_KCONTIG || KIND == SRC_X_KSTRIDED);
+    static constexpr int RPC = (XSRC && sizeof(T) == 2) ? 2 : 1;  // uint4 registers per chunk (fp32 source of bf16)
+    static constexpr int NRAW = FAST ? CPT * RPC : CPT;
+
+    // Issue the loads of contraction range [k0, k0 + NCH * VE).
+    __device__ inline void load(int r0, int k0, uint4 raw[NRAW]) const {
+        if (!FAST) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int c = tid + 256 * i;
-                *reinterpret_cast<uint4*>(tile + (c / 4) * PITCH + (c % 4) * 16) = regs[i];
+            for (int i = 0; i < CPT; ++i) {
+                const int r = r0 + trow(i), k = k0 + tchunk(i) * VE;
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < VE; ++e) v[e] = elem(r, k + e);
+                raw[i] = pack_chunk<T>(v);
             }
-        } else if (KIND == SRC_KSTRIDED && sizeof(T) == 2 && vec_ok) {
-            const int r = 2 * (tid % 64), kc = tid / 64;
-            *reinterpret_cast<uint4*>(tile + r * PITCH + kc * 16) = regs[0];
-            *reinterpret_cast<uint4*>(tile + (r + 1) * PITCH + kc * 16) = regs[1];
-        } else {
+            return;
+        }
+        if (KIND == SRC_KCONTIG) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                *reinterpret_cast<uint4*>(tile + (tid % 128) * PITCH + (tid / 128 + 2 * i) * 16) = regs[i];
+            for (int i = 0; i < CPT; ++i) {
+                const bool ok = k0 + tchunk(i) * VE < kdim;  // kdim is a multiple of VE
+                raw[i] = *reinterpret_cast<const uint4*>(ptr[i] + (ok ? (int64_t)k0 * sizeof(T) : 0));
+            }
+        } else if (KIND == SRC_X_KCONTIG) {
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const bool ok = k0 + tchunk(i) * VE < kdim;
+                const uint4* src = reinterpret_cast<const uint4*>(ptr[i] + (ok ? (int64_t)k0 * 4 : 0));
+#pragma unroll
+                for (int q = 0; q < RPC; ++q) raw[i * RPC + q] = src[q];
+            }
+        } else if (PAIR) {
+            // bf16: a thread reads a pair of adjacent rows for 8 consecutive k (split into two chunks later)
+#pragma unroll
+            for (int i = 0; i < CPT; i += 2) {
+                const int k = k0 + tchunk(i) * 8;
+                uint32_t d[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int kk = k + e;
+                    const int kc = kk < kdim ? kk : kdim - 1;
+                    d[e] = *reinterpret_cast<const uint32_t*>(ptr[i] + (int64_t)kc * ld * 2);
+                }
+                raw[i] = make_uint4(d[0], d[1], d[2], d[3]);
+                raw[i + 1] = make_uint4(d[4], d[5], d[6], d[7]);
+            }
+        } else if (KIND == SRC_KSTRIDED) {
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const int k = k0 + tchunk(i) * VE;
+                uint32_t d[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int kk = k + e;
+                    const int kc = kk < kdim ? kk : kdim - 1;
+                    d[e] = *reinterpret_cast<const uint32_t*>(ptr[i] + (int64_t)kc * ld * 4);
+                }
+                raw[i] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        } else {
+            // x, contraction over rows of the selection: VE consecutive selected rows share one time step
+            // (the launcher checks j_cnt % VE == 0), so one row lookup serves the chunk
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const int k = k0 + tchunk(i) * VE;
+                const int64_t rb = rm.row(p, k < kdim ? k : 0);
+                uint32_t d[8];
+#pragma unroll
+                for (int e = 0; e < VE; ++e)
+                    d[e] = *reinterpret_cast<const uint32_t*>(ptr[i] + (rb + e) * ld * 4);
+                raw[i * RPC] = make_uint4(d[0], d[1], d[2], d[3]);
+                if (RPC == 2) raw[i * RPC + 1] = make_uint4(d[4], d[5], d[6], d[7]);
+            }
+        }
+    }
+
+    __device__ static inline uint4 mask4(const uint4& u, bool ok) {
+        const uint32_t m = ok ? 0xffffffffu : 0u;
+        return make_uint4(u.x & m, u.y & m, u.z & m, u.w & m);
+    }
+
+    // Convert / transpose / mask the staged values of range k0 and write them to the LDS tile.
+    __device__ inline void store(unsigned char* tile, const uint4 raw[NRAW], int k0) const {
+        if (!FAST || KIND == SRC_KCONTIG) {
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const bool ok = !FAST || (k0 + tchunk(i) * VE < kdim);
+                *reinterpret_cast<uint4*>(tile + trow(i) * PITCH + tchunk(i) * 16) = mask4(raw[i], ok);
+            }
+        } else if (PAIR) {
+#pragma unroll
+            for (int i = 0; i < CPT; i += 2) {
+                const int k = k0 + tchunk(i) * 8;
+                uint32_t d[8] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w, raw[i + 1].x, raw[i + 1].y, raw[i + 1].z, raw[i + 1].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d[e] = (k + e < kdim) ? d[e] : 0u;
+                const uint4 lo = make_uint4((d[0] & 0xffffu) | (d[1] << 16), (d[2] & 0xffffu) | (d[3] << 16),
+                                            (d[4] & 0xffffu) | (d[5] << 16), (d[6] & 0xffffu) | (d[7] << 16));
+                const uint4 hi = make_uint4((d[0] >> 16) | (d[1] & 0xffff0000u), (d[2] >> 16) | (d[3] & 0xffff0000u),
+                                            (d[4] >> 16) | (d[5] & 0xffff0000u), (d[6] >> 16) | (d[7] & 0xffff0000u));
+                *reinterpret_cast<uint4*>(tile + trow(i) * PITCH + tchunk(i) * 16) = lo;
+                *reinterpret_cast<uint4*>(tile + (trow(i) + 1) * PITCH + tchunk(i) * 16) = hi;
+            }
+        } else if (KIND == SRC_KSTRIDED) {  // fp32, element-wise mask of the contraction tail
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const int k = k0 + tchunk(i) * 4;
+                const uint4 u = make_uint4(k < kdim ? raw[i].x : 0u, k + 1 < kdim ? raw[i].y : 0u,
+                                           k + 2 < kdim ? raw[i].z : 0u, k + 3 < kdim ? raw[i].w : 0u);
+                *reinterpret_cast<uint4*>(tile + trow(i) * PITCH + tchunk(i) * 16) = u;
+            }
+        } else {  // x sources: fp32 -> T, whole chunks in or out of the contraction range
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const bool ok = k0 + tchunk(i) * VE < kdim;
+                float v[8];
+#pragma unroll
+                for (int q = 0; q < RPC; ++q) {
+                    const uint4 u = raw[i * RPC + q];
+                    v[4 * q] = __uint_as_float(u.x); v[4 * q + 1] = __uint_as_float(u.y);
+                    v[4 * q + 2] = __uint_as_float(u.z); v[4 * q + 3] = __uint_as_float(u.w);
+                }
+                *reinterpret_cast<uint4*>(tile + trow(i) * PITCH + tchunk(i) * 16) = mask4(pack_chunk<T>(v), ok);
+            }
         }
     }
 };
@@ -155,34 +257,91 @@ template <> struct Mma32<float> {
     }
 };
 
-__device__ inline float act_fn(float z, int kind) {
-    if (kind == 0) return tanhf(z);
-    return z / (1.f + expf(-z));
-}
-__device__ inline float act_grad(float z, int kind) {
-    if (kind == 0) {
-        const float t = tanhf(z);
-        return 1.f - t * t;
+// h = act(z) and g = act'(z).  SiLU uses the hardware exp2 / reciprocal approximations (about 1 ulp
+// each): s = 1 / (1 + e^-z), h = z s, g = s (1 + z - h).  tanh keeps the library routine.
+template <int ACT>
+__device__ inline void act_pair(float z, float& h, float& g) {
+    if (ACT == 0) {
+        h = tanhf(z);
+        g = 1.f - h * h;
+    } else {
+        const float e = __expf(-z);
+        const float s = __builtin_amdgcn_rcpf(1.f + e);
+        h = z * s;
+        g = s * (1.f + z - h);
     }
-    const float s = 1.f / (1.f + expf(-z));
-    return s * (1.f + z * (1.f - s));
 }
 
-// ---- epilogues: called once per accumulator element with its tile-global (row, col) ------------
-template <typename T>
-struct EpiFwd {  // h = act(z + b), optionally also act'(z); compact [M][n_cols] stores
-    const float* bias;  // [n_cols] of preference p
+// eight consecutive elements of type T / of the saved-derivative type: packing and 16-byte accesses
+struct Pack8 { uint4 lo, hi; };  // bf16 / fixed point use lo only; fp32 uses both
+__device__ inline Pack8 pack8(const float v[8], const float*) {
+    Pack8 r;
+    r.lo = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    r.hi = make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7]));
+    return r;
+}
+__device__ inline Pack8 pack8(const float v[8], const bf16_t*) {
+    Pack8 r;
+    r.lo = pack_chunk<bf16_t>(v);
+    r.hi = make_uint4(0, 0, 0, 0);
+    return r;
+}
+__device__ inline Pack8 pack8(const float v[8], const gfix16_t*) {
+    // round(v / step + 1/8 / step); values are in (-0.125, 1.125) so the conversion cannot overflow
+    uint32_t q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = (uint32_t)(v[i] * (1.0f / GFIX_STEP) + (0.125f / GFIX_STEP + 0.5f));
+    Pack8 r;
+    r.lo = make_uint4(q[0] | (q[1] << 16), q[2] | (q[3] << 16), q[4] | (q[5] << 16), q[6] | (q[7] << 16));
+    r.hi = make_uint4(0, 0, 0, 0);
+    return r;
+}
+__device__ inline void put8(float* dst, const Pack8& pk) {
+    reinterpret_cast<uint4*>(dst)[0] = pk.lo;
+    reinterpret_cast<uint4*>(dst)[1] = pk.hi;
+}
+__device__ inline void put8(bf16_t* dst, const Pack8& pk) { *reinterpret_cast<uint4*>(dst) = pk.lo; }
+__device__ inline void put8(gfix16_t* dst, const Pack8& pk) { *reinterpret_cast<uint4*>(dst) = pk.lo; }
+__device__ inline void get8(const float* src, float v[8]) {
+    const float4 a = reinterpret_cast<const float4*>(src)[0], b = reinterpret_cast<const float4*>(src)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ inline void get8(const gfix16_t* src, float v[8]) {
+    const uint4 u = *reinterpret_cast<const uint4*>(src);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = (float)(w[i] & 0xffffu) * GFIX_STEP - 0.125f;
+        v[2 * i + 1] = (float)(w[i] >> 16) * GFIX_STEP - 0.125f;
+    }
+}
+
+// ---- epilogues.  A lane owns, for each of its 8 "octets", row r and the eight consecutive columns
+// c .. c+7 (c a multiple of 8).  compute() turns the accumulators into results (left in v[], used for
+// the column sums) and packs what will be stored; flush() issues the stores.  The kernel calls
+// compute() for all octets first and then all flush()es back to back, so that the pieces of a cache
+// line leave the wave together. ---------------------------------------------------------------------
+template <typename T, int ACT, bool SAVE>
+struct EpiFwd {  // h = act(z + b) and, when SAVE, act'(z); compact [M][ld] stores
+    const float* bias;  // [ld] of preference p
     T* H;               // compact, offset to p
-    typename GradT<T>::type* G;  // nullable
-    int ld, act;
+    typename GradT<T>::type* G;  // used when SAVE
+    int ld;
     static constexpr bool kColSum = false;
     float* part;  // unused
-    __device__ inline float operator()(int r, int c, float v) const {
-        const float z = v + bias[c];
-        const float h = act_fn(z, act);
-        H[(int64_t)r * ld + c] = cvt<T>(h);
-        if (G) G[(int64_t)r * ld + c] = cvt<typename GradT<T>::type>(act_grad(z, act));
-        return h;
+    struct Out { Pack8 h, g; };
+    __device__ inline void compute(int r, int c, int n, float v[8], Out& o) const {
+        (void)r; (void)n;  // ld is a multiple of 16, so an octet is never cut
+        float g[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) act_pair<ACT>(v[i] + bias[c + i], v[i], g[i]);
+        o.h = pack8(v, (const T*)nullptr);
+        if (SAVE) o.g = pack8(g, (const typename GradT<T>::type*)nullptr);
+    }
+    __device__ inline void flush(int r, int c, int n, const Out& o) const {
+        (void)n;
+        put8(H + (int64_t)r * ld + c, o.h);
+        if (SAVE) put8(G + (int64_t)r * ld + c, o.g);
     }
 };
 template <typename T>
@@ -192,10 +351,18 @@ struct EpiDx {  // dZ_{l-1} = (dZ_l W_l) * act'(z_{l-1})
     int ld;
     static constexpr bool kColSum = true;  // column sums of the unrounded dZ feed the bias gradient
     float* part;                           // [P][tiles_m][ld] partial column sums
-    __device__ inline float operator()(int r, int c, float v) const {
-        const float d = v * to_f(G[(int64_t)r * ld + c]);
-        dZ[(int64_t)r * ld + c] = cvt<T>(d);
-        return d;
+    struct Out { Pack8 d; };
+    __device__ inline void compute(int r, int c, int n, float v[8], Out& o) const {
+        (void)n;
+        float g[8];
+        get8(G + (int64_t)r * ld + c, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] *= g[i];
+        o.d = pack8(v, (const T*)nullptr);
+    }
+    __device__ inline void flush(int r, int c, int n, const Out& o) const {
+        (void)n;
+        put8(dZ + (int64_t)r * ld + c, o.d);
     }
 };
 struct EpiDw {  // dW_l(p)[o, i]
@@ -203,16 +370,29 @@ struct EpiDw {  // dW_l(p)[o, i]
     int ld;
     static constexpr bool kColSum = false;
     float* part;  // unused
-    __device__ inline float operator()(int r, int c, float v) const {
-        dW[(int64_t)r * ld + c] = v;
-        return v;
+    struct Out { Pack8 w; };
+    __device__ inline void compute(int r, int c, int n, float v[8], Out& o) const {
+        (void)r; (void)c; (void)n;
+        o.w = pack8(v, (const float*)nullptr);
+    }
+    __device__ inline void flush(int r, int c, int n, const Out& o) const {
+        float* d = dW + (int64_t)r * ld + c;
+        if (n == 8 && (ld & 3) == 0) {
+            put8(d, o.w);
+        } else {
+            const uint32_t w[8] = {o.w.lo.x, o.w.lo.y, o.w.lo.z, o.w.lo.w, o.w.hi.x, o.w.hi.y, o.w.hi.z, o.w.hi.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (i < n) d[i] = __uint_as_float(w[i]);
+        }
     }
 };
 
-template <typename T> __device__ inline void shift_epi(EpiFwd<T>& e, int p, int64_t s0, int64_t s1, int64_t) {
+template <typename T, int ACT, bool SAVE>
+__device__ inline void shift_epi(EpiFwd<T, ACT, SAVE>& e, int p, int64_t s0, int64_t s1, int64_t) {
     e.bias += (int64_t)p * s0;
     e.H += (int64_t)p * s1;
-    if (e.G) e.G += (int64_t)p * s1;
+    if (SAVE) e.G += (int64_t)p * s1;
 }
 template <typename T> __device__ inline void shift_epi(EpiDx<T>& e, int p, int64_t s0, int64_t, int64_t) {
     e.G += (int64_t)p * s0;
@@ -227,10 +407,10 @@ __device__ inline int xcd_remap(int bid, int nb) {
     return x * q + (x < rem ? x : rem) + pos;
 }
 
-template <typename T, int KA, int KB, class Epi>
+template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
 struct GemmArgs {
-    Operand<T, KA> a;
-    Operand<T, KB> b;
+    Operand<T, KA, FAST, NCH> a;
+    Operand<T, KB, FAST, NCH> b;
     Epi epi;
     int64_t a_pstride, b_pstride;  // per-preference strides (elements of the operand's storage type)
     int64_t e0_pstride, e1_pstride, e2_pstride;
@@ -238,30 +418,37 @@ struct GemmArgs {
 };
 
 // C[rows_a x rows_b] = A[rows_a x K] * B[rows_b x K]^T for every preference.
-template <typename T, int KA, int KB, class Epi>
-__global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi> g) {
-    __shared__ __align__(16) unsigned char lds[2][2][TILE_BYTES];
+template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
+__global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, FAST, NCH> g) {
+    constexpr int PITCH = NCH * 16 + 16;
+    constexpr int TILE = 128 * PITCH;
+    constexpr int CPT = NCH / 2;
+    __shared__ __align__(16) unsigned char lds[2][2][TILE];
     constexpr int VE = Elems<T>::VE;
-    constexpr int BK = 4 * VE;
+    constexpr int BK = NCH * VE;
     const int id = xcd_remap(blockIdx.x, gridDim.x);
     const int per_p = g.tiles_m * g.tiles_n;
     const int p = id / per_p, tm = (id % per_p) / g.tiles_n, tn = id % g.tiles_n;
 
-    Operand<T, KA> A = g.a;
-    Operand<T, KB> B = g.b;
+    Operand<T, KA, FAST, NCH> A = g.a;
+    Operand<T, KB, FAST, NCH> B = g.b;
     A.p = p; B.p = p;
     if (KA == SRC_KCONTIG || KA == SRC_KSTRIDED)
         A.base = reinterpret_cast<const T*>(A.base) + (int64_t)p * g.a_pstride;
     if (KB == SRC_KCONTIG || KB == SRC_KSTRIDED)
         B.base = reinterpret_cast<const T*>(B.base) + (int64_t)p * g.b_pstride;
     Epi epi = g.epi;
-    // epilogue pointers are shifted by the caller-provided strides through the specialisations below
     shift_epi(epi, p, g.e0_pstride, g.e1_pstride, g.e2_pstride);
 
     const int r0 = tm * BM, c0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int lr = lane & 31, lg = lane >> 5;
+    // B rows are fed to the MFMA with bits 2 and 3 of the row index swapped, which makes every lane's
+    // accumulators cover two runs of eight consecutive output columns (see the epilogue)
+    const int lrp = (lr & 0x13) | ((lr & 4) << 1) | ((lr & 8) >> 1);
+    A.init(r0);
+    B.init(c0);
 
     float16_t acc[2][2];
 #pragma unroll
@@ -273,11 +460,14 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi> g
 
     const int kdim = A.kdim;
     const int nk = (kdim + BK - 1) / BK;
-    uint4 ra[2], rb[2];
+    // Register stage + two LDS stages: the loads of step kt+1 are in flight while step kt is multiplied
+    // out of LDS; they are converted and written to the other LDS stage after the products.
+    constexpr int NRA = Operand<T, KA, FAST, NCH>::NRAW, NRB = Operand<T, KB, FAST, NCH>::NRAW;
+    uint4 ra[NRA], rb[NRB];
     A.load(r0, 0, ra);
     B.load(c0, 0, rb);
-    A.store(lds[0][0], ra);
-    B.store(lds[0][1], rb);
+    A.store(lds[0][0], ra, 0);
+    B.store(lds[0][1], rb, 0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
@@ -285,48 +475,87 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi> g
             A.load(r0, (kt + 1) * BK, ra);
             B.load(c0, (kt + 1) * BK, rb);
         }
-        const unsigned char* ta = lds[cur][0];
-        const unsigned char* tb = lds[cur][1];
+        const unsigned char* ta = lds[cur][0] + (wm + lr) * PITCH + lg * 16;
+        const unsigned char* tb = lds[cur][1] + (wn + lrp) * PITCH + lg * 16;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const int ch = (2 * ks + lg) * 16;
+        for (int ks = 0; ks < NCH / 2; ++ks) {
             uint4 fa[2], fb[2];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const uint4*>(ta + (wm + 32 * i + lr) * PITCH + ch);
+            for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const uint4*>(ta + 32 * i * PITCH + ks * 32);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const uint4*>(tb + (wn + 32 * j + lr) * PITCH + ch);
+            for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const uint4*>(tb + 32 * j * PITCH + ks * 32);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) Mma32<T>::run(fa[i], fb[j], acc[i][j]);
+                for (int j = 0; j < 2; ++j) Mma32<T>::run(fb[j], fa[i], acc[i][j]);  // transposed tile
         }
         if (kt + 1 < nk) {
-            A.store(lds[cur ^ 1][0], ra);
-            B.store(lds[cur ^ 1][1], rb);
+            A.store(lds[cur ^ 1][0], ra, (kt + 1) * BK);
+            B.store(lds[cur ^ 1][1], rb, (kt + 1) * BK);
         }
         __syncthreads();
     }
-    // accumulator element e of lane: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 tile
+    // The products were issued with the operands swapped, so each 32x32 accumulator holds the transposed
+    // tile: lane (lr, lg) owns output row lr; with the row permutation of the B fragments its 16 values
+    // are the columns 16 h + 8 lg + 0..7 for h = 0, 1 (accumulator elements 8 h .. 8 h + 7) -- one 16-byte
+    // bf16 access per octet, and the two lane groups of a row together fill 32 contiguous bytes.
     const int rows = A.rows, cols = B.rows;
-    float cs[2] = {0.f, 0.f};
+    float cs[Epi::kColSum ? 32 : 1];
+    typename Epi::Out outs[8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+        const int r = r0 + wm + 32 * i + lr;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int c = c0 + wn + 32 * j + lr;
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int r = r0 + wm + 32 * i + 8 * (e / 4) + 4 * lg + (e % 4);
-                if (r < rows && c < cols) cs[j] += epi(r, c, acc[i][j][e]);
+            for (int h = 0; h < 2; ++h) {
+                const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = acc[i][j][8 * h + u];
+                const bool ok = (r < rows) && (c < cols);
+                // out-of-range octets are computed on a clamped, valid position and not stored
+                const int rc = r < rows ? r : rows - 1;
+                const int cc = c < cols ? c : 0;
+                epi.compute(rc, cc, 8, v, outs[(i * 2 + j) * 2 + h]);
+                if (Epi::kColSum) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int t = Epi::kColSum ? (16 * j + 8 * h + u) : 0;
+                        cs[t] = (i == 0 ? 0.f : cs[t]) + (ok ? v[u] : 0.f);
+                    }
+                }
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = r0 + wm + 32 * i + lr;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
+                if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[(i * 2 + j) * 2 + h]);
+            }
+    }
+    if (Epi::kColSum) {
+        // Column sums over the tile's 128 rows, fixed order.  Slot t = 16 j + 8 h + u of a lane is column
+        // wn + 32 j + 16 h + 8 lg + u; the 32 lanes of a half-wave (same lg) fold their 32 slots pairwise so
+        // that lane lr ends up with the half-wave total of slot lr.
+#pragma unroll
+        for (int hh = 16; hh >= 1; hh >>= 1) {
+            const bool up = (lr & hh) != 0;
+#pragma unroll
+            for (int t = 0; t < hh; ++t) {
+                const float send = up ? cs[t] : cs[t + hh];
+                const float keep = up ? cs[t + hh] : cs[t];
+                cs[t] = keep + __shfl_xor(send, hh, 64);
             }
         }
-    if (Epi::kColSum) {
-        // column sums over this tile's 128 rows in a fixed order: lane pair, then the two row waves
         float* red = reinterpret_cast<float*>(&lds[0][0][0]);  // the staging tiles are no longer read
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            cs[j] += __shfl_xor(cs[j], 32, 64);
-            if (lg == 0) red[wave * 64 + 32 * j + lr] = cs[j];
+        {
+            const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
+            red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
         }
         __syncthreads();
         if (threadIdx.x < 128) {
@@ -392,14 +621,14 @@ static GemmProf::Rec* prof_take(const morlax_ctx* c, int kind, double flops) {
     return r;
 }
 
-template <typename T, int KA, int KB, class Epi>
-static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi>& g, int P, hipStream_t s) {
+template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
+static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, hipStream_t s) {
     g.tiles_m = (g.a.rows + BM - 1) / BM;
     g.tiles_n = (g.b.rows + BN - 1) / BN;
     const int nb = g.tiles_m * g.tiles_n * P;
     GemmProf::Rec* r = prof_take(c, kind, 2.0 * g.a.rows * (double)g.b.rows * g.a.kdim * P);
     if (r) (void)hipEventRecord(r->a, s);
-    k_grouped_gemm<T, KA, KB, Epi><<<nb, 256, 0, s>>>(g);
+    k_grouped_gemm<T, KA, KB, Epi, FAST, NCH><<<nb, 256, 0, s>>>(g);
     if (r) (void)hipEventRecord(r->b, s);
 }
 
@@ -556,77 +785,136 @@ __global__ __launch_bounds__(256) void k_head_bwd_dz(const float* __restrict__ d
     }
 }
 
-// dW_L(p)[j, i] = sum_m dz_L[m, j] h_{L-1}[m, i] and db_L(p)[j] = sum_m dz_L[m, j].
-// Block: 64 columns i of one preference, 4 waves taking rows m = wave, wave + 4, ...; fixed-order merge.
+// dW_L(p)[j, i] = sum_m dz_L[m, j] h_{L-1}[m, i] and db_L(p)[j] = sum_m dz_L[m, j], in two stages.
+// Stage 1: a block takes 256 rows x 128 columns of one preference; thread (cg, rs) owns 8 columns and the
+// rows rs, rs + 16, ...; the 16 row groups are merged in a fixed order.  Partials go to
+// pw[p][chunk][j][i] and pb[p][chunk][j].  Stage 2 (k_head_bwd_dw_final) adds the chunks in order.
+#define HB_ROWS 256
 template <typename T>
 __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ dout,
                                                     const float* __restrict__ saved_out,
-                                                    const T* __restrict__ Hin, float* __restrict__ dtheta_mat,
-                                                    float* __restrict__ dtheta_vec, int64_t mat_len,
-                                                    int64_t vec_len, int64_t mat_off, int64_t vec_off, int W,
-                                                    int out_dim, int M, RowMap rm, int tanh_head) {
-    __shared__ float sdr[256][MORLAX_MAX_OUT];  // rounded dz (GEMM input)
-    __shared__ float sdu[256][MORLAX_MAX_OUT];  // unrounded dz (bias gradient)
-    __shared__ float red[4][MORLAX_MAX_OUT][64];
-    const int p = blockIdx.y;
-    const int col = threadIdx.x & 63, sub = threadIdx.x >> 6;
-    const int i = blockIdx.x * 64 + col;
-    float acc[MORLAX_MAX_OUT];
+                                                    const T* __restrict__ Hin, float* __restrict__ pw,
+                                                    float* __restrict__ pb, int W, int out_dim, int M, RowMap rm,
+                                                    int tanh_head) {
+    __shared__ float sdr[HB_ROWS][MORLAX_MAX_OUT];          // rounded dz (GEMM input)
+    __shared__ float red[4][MORLAX_MAX_OUT][128];           // also holds the unrounded dz at the start
+    __shared__ float bpart[16][MORLAX_MAX_OUT];
+    constexpr int VE = Elems<T>::VE;
+    const int p = blockIdx.z, chunk = blockIdx.y, m0 = chunk * HB_ROWS, i0 = blockIdx.x * 128;
+    const int n_chunk = gridDim.y;
+    float(*sdu)[MORLAX_MAX_OUT] = reinterpret_cast<float(*)[MORLAX_MAX_OUT]>(&red[0][0][0]);
+    {
+        const int mm = threadIdx.x;
+        const bool ok = m0 + mm < M;
+        int64_t row = 0;
+        if (ok) row = rm.row(p, m0 + mm);
 #pragma unroll
-    for (int j = 0; j < MORLAX_MAX_OUT; ++j) acc[j] = 0.f;
-    float bsum = 0.f;  // thread (j = tid % 16, part = tid / 16) of block x = 0
-    for (int m0 = 0; m0 < M; m0 += 256) {
-        __syncthreads();
-        {
-            const int mm = threadIdx.x;
+        for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
+            float d = 0.f;
+            if (ok && j < out_dim) {
+                d = dout[row * out_dim + j];
+                if (tanh_head) {
+                    const float mu = saved_out[((int64_t)p * M + m0 + mm) * OUT_PITCH + j];
+                    d *= (1.f - mu * mu);
+                }
+            }
+            sdu[mm][j] = d;
+            sdr[mm][j] = to_f(cvt<T>(d));
+        }
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        const int j = threadIdx.x & 15, part = threadIdx.x >> 4;
+        float b = 0.f;
+        for (int mm = part * 16; mm < part * 16 + 16; ++mm) b += sdu[mm][j];
+        bpart[part][j] = b;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x < out_dim) {
+        float v = 0.f;
+        for (int part = 0; part < 16; ++part) v += bpart[part][threadIdx.x];
+        pb[((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + threadIdx.x] = v;
+    }
+    const int cg = threadIdx.x & 15, rs = threadIdx.x >> 4;
+    const int col = i0 + cg * 8;
+    float acc[MORLAX_MAX_OUT][8];
+#pragma unroll
+    for (int j = 0; j < MORLAX_MAX_OUT; ++j)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[j][b] = 0.f;
+    if (col < W) {
+        for (int mm = rs; mm < HB_ROWS && m0 + mm < M; mm += 16) {
+            const T* src = Hin + ((int64_t)p * M + m0 + mm) * W + col;
+            float h[8];
+#pragma unroll
+            for (int qd = 0; qd < 8 / VE; ++qd) {
+                const uint4 u = *reinterpret_cast<const uint4*>(src + qd * VE);
+                if (sizeof(T) == 2) {
+                    const uint32_t w4[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        h[2 * e] = __uint_as_float(w4[e] << 16);
+                        h[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
+                    }
+                } else {
+                    h[4 * qd] = __uint_as_float(u.x); h[4 * qd + 1] = __uint_as_float(u.y);
+                    h[4 * qd + 2] = __uint_as_float(u.z); h[4 * qd + 3] = __uint_as_float(u.w);
+                }
+            }
 #pragma unroll
             for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
-                float d = 0.f;
-                if (m0 + mm < M && j < out_dim) {
-                    d = dout[rm.row(p, m0 + mm) * out_dim + j];
-                    if (tanh_head) {
-                        const float mu = saved_out[((int64_t)p * M + m0 + mm) * OUT_PITCH + j];
-                        d *= (1.f - mu * mu);
-                    }
+                if (j < out_dim) {
+                    const float d = sdr[mm][j];
+#pragma unroll
+                    for (int b = 0; b < 8; ++b) acc[j][b] += d * h[b];
                 }
-                sdu[mm][j] = d;
-                sdr[mm][j] = to_f(cvt<T>(d));
             }
         }
-        __syncthreads();
-        if (i < W) {
-            for (int mm = sub; mm < 256 && m0 + mm < M; mm += 4) {
-                const float h = to_f(Hin[((int64_t)p * M + m0 + mm) * W + i]);
+    }
+    // merge the four row groups of a wave (lanes 16 apart), then the four waves through LDS
 #pragma unroll
-                for (int j = 0; j < MORLAX_MAX_OUT; ++j)
-                    if (j < out_dim) acc[j] += sdr[mm][j] * h;
-            }
+    for (int j = 0; j < MORLAX_MAX_OUT; ++j)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            float v = acc[j][b];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            acc[j][b] = v;
         }
-        if (blockIdx.x == 0) {
-            const int j = threadIdx.x & 15, part = threadIdx.x >> 4;
-            for (int mm = part * 16; mm < part * 16 + 16; ++mm) bsum += sdu[mm][j];
-        }
+    __syncthreads();  // sdu (aliased with red) is no longer needed
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) < 16) {
+#pragma unroll
+        for (int j = 0; j < MORLAX_MAX_OUT; ++j)
+#pragma unroll
+            for (int b = 0; b < 8; ++b) red[wave][j][cg * 8 + b] = acc[j][b];
     }
     __syncthreads();
-#pragma unroll
-    for (int j = 0; j < MORLAX_MAX_OUT; ++j) red[sub][j][col] = acc[j];
-    __syncthreads();
-    if (sub == 0 && i < W) {
-        for (int j = 0; j < out_dim; ++j) {
-            const float v = red[0][j][col] + red[1][j][col] + red[2][j][col] + red[3][j][col];
-            dtheta_mat[(int64_t)p * mat_len + mat_off + (int64_t)j * W + i] = v;
+    for (int idx = threadIdx.x; idx < out_dim * 128; idx += 256) {
+        const int j = idx / 128, c = idx % 128;
+        if (i0 + c < W) {
+            const float v = red[0][j][c] + red[1][j][c] + red[2][j][c] + red[3][j][c];
+            pw[(((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + j) * W + i0 + c] = v;
         }
     }
-    if (blockIdx.x == 0) {
-        __syncthreads();
-        float* r2 = &red[0][0][0];
-        r2[threadIdx.x] = bsum;
-        __syncthreads();
-        if (threadIdx.x < out_dim) {
-            float v = 0.f;
-            for (int part = 0; part < 16; ++part) v += r2[part * 16 + threadIdx.x];
-            dtheta_vec[(int64_t)p * vec_len + vec_off + threadIdx.x] = v;
-        }
+}
+
+__global__ __launch_bounds__(256) void k_head_bwd_dw_final(const float* __restrict__ pw, const float* __restrict__ pb,
+                                                          int n_chunk, float* __restrict__ dtheta_mat,
+                                                          float* __restrict__ dtheta_vec, int64_t mat_len,
+                                                          int64_t vec_len, int64_t mat_off, int64_t vec_off, int W,
+                                                          int out_dim) {
+    const int p = blockIdx.y, idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < out_dim * W) {
+        const int j = idx / W, i = idx % W;
+        float v = 0.f;
+        for (int c = 0; c < n_chunk; ++c) v += pw[(((int64_t)p * n_chunk + c) * MORLAX_MAX_OUT + j) * W + i];
+        dtheta_mat[(int64_t)p * mat_len + mat_off + idx] = v;
+    }
+    if (idx < out_dim) {
+        float v = 0.f;
+        for (int c = 0; c < n_chunk; ++c) v += pb[((int64_t)p * n_chunk + c) * MORLAX_MAX_OUT + idx];
+        dtheta_vec[(int64_t)p * vec_len + vec_off + idx] = v;
     }
 }
 
@@ -661,7 +949,9 @@ int64_t mlp_saved_bytes(const morlax_ctx* c, int net, const RowSel& rs) {
            align_up((int64_t)c->d.P * rs.M * OUT_PITCH * 4, 256);
 }
 static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
-    return align_up((int64_t)c->d.P * ((rs.M + 63) / 64) * c->d.width, 64);
+    const int64_t colsum = (int64_t)c->d.P * ((rs.M + 63) / 64) * c->d.width;
+    const int64_t head = (int64_t)c->d.P * ((rs.M + HB_ROWS - 1) / HB_ROWS) * MORLAX_MAX_OUT * (c->d.width + 1);
+    return align_up(colsum > head ? colsum : head, 64);
 }
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
     return 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4;
@@ -688,29 +978,44 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     auto Gbuf = [&](int l) { return sv ? reinterpret_cast<GT*>(sv + (int64_t)(2 * l + 1) * ae) : (GT*)nullptr; };
     float* saved_out = sv ? reinterpret_cast<float*>(sv + (int64_t)2 * L * ae) : nullptr;
     constexpr int VE = Elems<T>::VE;
-    for (int l = 0; l < L; ++l) {
+    auto layer = [&](int l, auto act_tag, auto save_tag) {
+        constexpr int ACT = decltype(act_tag)::value;
+        constexpr bool SAVE = decltype(save_tag)::value;
         const LayerDev& Ld = nd.layer[l];
-        EpiFwd<T> ep;
+        EpiFwd<T, ACT, SAVE> ep;
         ep.bias = theta_vec + Ld.vec_off;
         ep.H = Hbuf(l);
         ep.G = Gbuf(l);
         ep.ld = W;
-        ep.act = c->d.act;
+        ep.part = nullptr;
         if (l == 0) {
-            GemmArgs<T, SRC_X_KCONTIG, SRC_KCONTIG, EpiFwd<T>> g;
-            g.a.base = x; g.a.ld = O; g.a.rows = M; g.a.kdim = O; g.a.rm = rm; g.a.vec_ok = (O % 4 == 0);
-            g.b.base = theta_mat + Ld.mat_off; g.b.ld = O; g.b.rows = W; g.b.kdim = O; g.b.rm = rm;
-            g.b.vec_ok = (O % VE == 0);
-            g.a_pstride = 0; g.b_pstride = nd.mat_len;
-            g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
-            run_gemm(c, 0, g, P, s);
+            auto launch = [&](auto fast) {
+                constexpr bool F = decltype(fast)::value;
+                GemmArgs<T, SRC_X_KCONTIG, SRC_KCONTIG, EpiFwd<T, ACT, SAVE>, F, GEMM_NCH> g;
+                g.a.base = x; g.a.ld = O; g.a.rows = M; g.a.kdim = O; g.a.rm = rm;
+                g.b.base = theta_mat + Ld.mat_off; g.b.ld = O; g.b.rows = W; g.b.kdim = O; g.b.rm = rm;
+                g.a_pstride = 0; g.b_pstride = nd.mat_len;
+                g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
+                run_gemm(c, 0, g, P, s);
+            };
+            if (O % VE == 0) launch(std::true_type{}); else launch(std::false_type{});
         } else {
-            GemmArgs<T, SRC_KCONTIG, SRC_KCONTIG, EpiFwd<T>> g;
-            g.a.base = Hbuf(l - 1); g.a.ld = W; g.a.rows = M; g.a.kdim = W; g.a.rm = rm; g.a.vec_ok = true;
-            g.b.base = theta_mat + Ld.mat_off; g.b.ld = W; g.b.rows = W; g.b.kdim = W; g.b.rm = rm; g.b.vec_ok = true;
+            GemmArgs<T, SRC_KCONTIG, SRC_KCONTIG, EpiFwd<T, ACT, SAVE>, true, GEMM_NCH> g;
+            g.a.base = Hbuf(l - 1); g.a.ld = W; g.a.rows = M; g.a.kdim = W; g.a.rm = rm;
+            g.b.base = theta_mat + Ld.mat_off; g.b.ld = W; g.b.rows = W; g.b.kdim = W; g.b.rm = rm;
             g.a_pstride = (int64_t)M * W; g.b_pstride = nd.mat_len;
             g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
             run_gemm(c, 1, g, P, s);
+        }
+    };
+    for (int l = 0; l < L; ++l) {
+        const bool save = sv != nullptr;
+        if (c->d.act == 0) {
+            if (save) layer(l, std::integral_constant<int, 0>{}, std::true_type{});
+            else layer(l, std::integral_constant<int, 0>{}, std::false_type{});
+        } else {
+            if (save) layer(l, std::integral_constant<int, 1>{}, std::true_type{});
+            else layer(l, std::integral_constant<int, 1>{}, std::false_type{});
         }
     }
     const LayerDev& Lh = nd.layer[L];
@@ -743,9 +1048,15 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     constexpr int VE = Elems<T>::VE;
     const LayerDev& Lh = nd.layer[L];
     // output layer
-    k_head_bwd_dw<T><<<dim3((W + 63) / 64, P), 256, 0, s>>>(dout, saved_out, Hbuf(L - 1), dtheta_mat, dtheta_vec,
-                                                           nd.mat_len, nd.vec_len, Lh.mat_off, Lh.vec_off, W,
-                                                           nd.out_dim, M, rm, tanh_head);
+    {
+        const int n_chunk = (M + HB_ROWS - 1) / HB_ROWS;
+        float* pw = part;
+        float* pb = part + (int64_t)P * n_chunk * MORLAX_MAX_OUT * W;
+        k_head_bwd_dw<T><<<dim3((W + 127) / 128, n_chunk, P), 256, 0, s>>>(dout, saved_out, Hbuf(L - 1), pw, pb, W,
+                                                                          nd.out_dim, M, rm, tanh_head);
+        k_head_bwd_dw_final<<<dim3((nd.out_dim * W + 255) / 256, P), 256, 0, s>>>(
+            pw, pb, n_chunk, dtheta_mat, dtheta_vec, nd.mat_len, nd.vec_len, Lh.mat_off, Lh.vec_off, W, nd.out_dim);
+    }
     k_head_bwd_dz<T><<<dim3((W + 127) / 128, (M + 63) / 64, P), 256, 0, s>>>(
         dout, saved_out, theta_mat, nd.mat_len, Lh.mat_off, Gbuf(L - 1), dZbuf(L - 1), part, W, nd.out_dim, M, rm,
         tanh_head);
@@ -756,27 +1067,31 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         ew.dW = dtheta_mat + Ld.mat_off;
         ew.ld = Ld.d_in;
         if (l > 0) {
-            GemmArgs<T, SRC_KSTRIDED, SRC_KSTRIDED, EpiDw> g;
-            g.a.base = dZbuf(l); g.a.ld = W; g.a.rows = W; g.a.kdim = M; g.a.rm = rm; g.a.vec_ok = true;
-            g.b.base = Hbuf(l - 1); g.b.ld = W; g.b.rows = W; g.b.kdim = M; g.b.rm = rm; g.b.vec_ok = true;
+            GemmArgs<T, SRC_KSTRIDED, SRC_KSTRIDED, EpiDw, true, GEMM_NCH> g;
+            g.a.base = dZbuf(l); g.a.ld = W; g.a.rows = W; g.a.kdim = M; g.a.rm = rm;
+            g.b.base = Hbuf(l - 1); g.b.ld = W; g.b.rows = W; g.b.kdim = M; g.b.rm = rm;
             g.a_pstride = (int64_t)M * W; g.b_pstride = (int64_t)M * W;
             g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
             run_gemm(c, 3, g, P, s);
-            GemmArgs<T, SRC_KCONTIG, SRC_KSTRIDED, EpiDx<T>> h;
-            h.a.base = dZbuf(l); h.a.ld = W; h.a.rows = M; h.a.kdim = W; h.a.rm = rm; h.a.vec_ok = true;
-            h.b.base = theta_mat + Ld.mat_off; h.b.ld = W; h.b.rows = W; h.b.kdim = W; h.b.rm = rm; h.b.vec_ok = true;
+            GemmArgs<T, SRC_KCONTIG, SRC_KSTRIDED, EpiDx<T>, true, GEMM_NCH> h;
+            h.a.base = dZbuf(l); h.a.ld = W; h.a.rows = M; h.a.kdim = W; h.a.rm = rm;
+            h.b.base = theta_mat + Ld.mat_off; h.b.ld = W; h.b.rows = W; h.b.kdim = W; h.b.rm = rm;
             h.a_pstride = (int64_t)M * W; h.b_pstride = nd.mat_len;
             h.epi.G = Gbuf(l - 1); h.epi.dZ = dZbuf(l - 1); h.epi.ld = W; h.epi.part = part;
             h.e0_pstride = (int64_t)M * W; h.e1_pstride = 0; h.e2_pstride = 0;
             run_gemm(c, 2, h, P, s);
             n_part = (M + BM - 1) / BM;
         } else {
-            GemmArgs<T, SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw> g;
-            g.a.base = dZbuf(0); g.a.ld = W; g.a.rows = W; g.a.kdim = M; g.a.rm = rm; g.a.vec_ok = true;
-            g.b.base = x; g.b.ld = O; g.b.rows = O; g.b.kdim = M; g.b.rm = rm; g.b.vec_ok = false;
-            g.a_pstride = (int64_t)M * W; g.b_pstride = 0;
-            g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
-            run_gemm(c, 4, g, P, s);
+            auto launch = [&](auto fast) {
+                constexpr bool F = decltype(fast)::value;
+                GemmArgs<T, SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw, F, GEMM_NCH> g;
+                g.a.base = dZbuf(0); g.a.ld = W; g.a.rows = W; g.a.kdim = M; g.a.rm = rm;
+                g.b.base = x; g.b.ld = O; g.b.rows = O; g.b.kdim = M; g.b.rm = rm;
+                g.a_pstride = (int64_t)M * W; g.b_pstride = 0;
+                g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
+                run_gemm(c, 4, g, P, s);
+            };
+            if (rs.j_cnt % VE == 0) launch(std::true_type{}); else launch(std::false_type{});
         }
     }
     (void)VE;
