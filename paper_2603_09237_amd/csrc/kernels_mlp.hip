@@ -64,7 +64,9 @@ struct Operand {
     static constexpr int CPT = NCH / 2;  // chunks per thread (128 * NCH / 256)
     static constexpr bool PAIR = (KIND == SRC_KSTRIDED && sizeof(T) == 2 && FAST);
 
-    const char* ptr[CPT];  // per-thread source pointers, set by init()
+    // FAST: byte offset of the thread's chunk i at contraction index 0, relative to `base`.  Per-preference
+    // tensors stay far below 4 GiB (checked by the launcher), so 32-bit offsets on a wave-uniform base do.
+    uint32_t voff[CPT];
 
     __device__ inline float elem(int r, int k) const {
         if (r >= rows || k >= kdim) return 0.f;
@@ -93,21 +95,12 @@ struct Operand {
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             int r = r0 + trow(i);
-            if (KIND == SRC_KCONTIG) {
-                r = r < rows ? r : rows - 1;
-                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const T*>(base) + (int64_t)r * ld + tchunk(i) * VE);
-            } else if (KIND == SRC_X_KCONTIG) {
-                r = r < rows ? r : rows - 1;
-                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const float*>(base) + rm.row(p, r) * ld +
-                                                       tchunk(i) * VE);
-            } else if (KIND == SRC_KSTRIDED) {
-                const int lim = PAIR ? rows - 2 : rows - 1;
-                r = r < lim ? r : lim;
-                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const T*>(base) + r);
-            } else {
-                r = r < rows ? r : rows - 1;
-                ptr[i] = reinterpret_cast<const char*>(reinterpret_cast<const float*>(base) + r);
-            }
+            const int lim = PAIR ? rows - 2 : rows - 1;
+            r = r < lim ? r : lim;
+            if (KIND == SRC_KCONTIG) voff[i] = (uint32_t)((r * (int)ld + tchunk(i) * VE) * (int)sizeof(T));
+            else if (KIND == SRC_X_KCONTIG) voff[i] = (uint32_t)((rm.row(p, r) * ld + tchunk(i) * VE) * 4);
+            else if (KIND == SRC_KSTRIDED) voff[i] = (uint32_t)((tchunk(i) * VE * (int)ld + r) * (int)sizeof(T));
+            else voff[i] = (uint32_t)(r * 4);
         }
     }
 
@@ -117,7 +110,9 @@ struct Operand {
     static constexpr int RPC = (XSRC && sizeof(T) == 2) ? 2 : 1;  // uint4 registers per chunk (fp32 source of bf16)
     static constexpr int NRAW = FAST ? CPT * RPC : CPT;
 
-    // Issue the loads of contraction range [k0, k0 + NCH * VE).
+    // Issue the loads of contraction range [k0, k0 + NCH * VE).  TAIL = the range may cross kdim: indices
+    // are clamped (and the values masked in store()); otherwise addresses are base + uniform + voff.
+    template <bool TAIL>
     __device__ inline void load(int r0, int k0, uint4 raw[NRAW]) const {
         if (!FAST) {
 #pragma unroll
@@ -130,47 +125,34 @@ struct Operand {
             }
             return;
         }
-        if (KIND == SRC_KCONTIG) {
+        const char* b = reinterpret_cast<const char*>(base);
+        if (KIND == SRC_KCONTIG || KIND == SRC_X_KCONTIG) {
+            constexpr int ES = (KIND == SRC_KCONTIG) ? (int)sizeof(T) : 4;
+            const char* bk = b + (int64_t)k0 * ES;
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
-                const bool ok = k0 + tchunk(i) * VE < kdim;  // kdim is a multiple of VE
-                raw[i] = *reinterpret_cast<const uint4*>(ptr[i] + (ok ? (int64_t)k0 * sizeof(T) : 0));
-            }
-        } else if (KIND == SRC_X_KCONTIG) {
+                const char* src = bk + voff[i];
+                if (TAIL && !(k0 + tchunk(i) * VE < kdim)) src = b + voff[i];  // any valid address; masked later
 #pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                const bool ok = k0 + tchunk(i) * VE < kdim;
-                const uint4* src = reinterpret_cast<const uint4*>(ptr[i] + (ok ? (int64_t)k0 * 4 : 0));
-#pragma unroll
-                for (int q = 0; q < RPC; ++q) raw[i * RPC + q] = src[q];
-            }
-        } else if (PAIR) {
-            // bf16: a thread reads a pair of adjacent rows for 8 consecutive k (split into two chunks later)
-#pragma unroll
-            for (int i = 0; i < CPT; i += 2) {
-                const int k = k0 + tchunk(i) * 8;
-                uint32_t d[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int kk = k + e;
-                    const int kc = kk < kdim ? kk : kdim - 1;
-                    d[e] = *reinterpret_cast<const uint32_t*>(ptr[i] + (int64_t)kc * ld * 2);
-                }
-                raw[i] = make_uint4(d[0], d[1], d[2], d[3]);
-                raw[i + 1] = make_uint4(d[4], d[5], d[6], d[7]);
+                for (int q = 0; q < RPC; ++q) raw[i * RPC + q] = reinterpret_cast<const uint4*>(src)[q];
             }
         } else if (KIND == SRC_KSTRIDED) {
+            const int64_t rstep = ld * (int64_t)sizeof(T);  // bytes between consecutive k
+            const char* bk = b + (int64_t)k0 * rstep;
 #pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                const int k = k0 + tchunk(i) * VE;
-                uint32_t d[4];
+            for (int i = 0; i < CPT; i += (PAIR ? 2 : 1)) {
+                uint32_t d[8];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int kk = k + e;
-                    const int kc = kk < kdim ? kk : kdim - 1;
-                    d[e] = *reinterpret_cast<const uint32_t*>(ptr[i] + (int64_t)kc * ld * 4);
+                for (int e = 0; e < (PAIR ? 8 : 4); ++e) {
+                    const char* src = bk + e * rstep + voff[i];
+                    if (TAIL) {
+                        const int kk = k0 + tchunk(i) * VE + e;
+                        if (kk >= kdim) src = b + (int64_t)(kdim - 1) * rstep + (voff[i] - (uint32_t)(tchunk(i) * VE) * (uint32_t)rstep);
+                    }
+                    d[e] = *reinterpret_cast<const uint32_t*>(src);
                 }
                 raw[i] = make_uint4(d[0], d[1], d[2], d[3]);
+                if (PAIR) raw[i + 1] = make_uint4(d[4], d[5], d[6], d[7]);
             }
         } else {
             // x, contraction over rows of the selection: VE consecutive selected rows share one time step
@@ -182,7 +164,7 @@ struct Operand {
                 uint32_t d[8];
 #pragma unroll
                 for (int e = 0; e < VE; ++e)
-                    d[e] = *reinterpret_cast<const uint32_t*>(ptr[i] + (rb + e) * ld * 4);
+                    d[e] = *reinterpret_cast<const uint32_t*>(b + (rb + e) * ld * 4 + voff[i]);
                 raw[i * RPC] = make_uint4(d[0], d[1], d[2], d[3]);
                 if (RPC == 2) raw[i * RPC + 1] = make_uint4(d[4], d[5], d[6], d[7]);
             }
@@ -194,12 +176,13 @@ struct Operand {
         return make_uint4(u.x & m, u.y & m, u.z & m, u.w & m);
     }
 
-    // Convert / transpose / mask the staged values of range k0 and write them to the LDS tile.
+    // Convert / transpose (and with TAIL mask) the staged values of range k0 and write them to the LDS tile.
+    template <bool TAIL>
     __device__ inline void store(unsigned char* tile, const uint4 raw[NRAW], int k0) const {
         if (!FAST || KIND == SRC_KCONTIG) {
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
-                const bool ok = !FAST || (k0 + tchunk(i) * VE < kdim);
+                const bool ok = !FAST || !TAIL || (k0 + tchunk(i) * VE < kdim);
                 *reinterpret_cast<uint4*>(tile + trow(i) * PITCH + tchunk(i) * 16) = mask4(raw[i], ok);
             }
         } else if (PAIR) {
@@ -207,8 +190,10 @@ struct Operand {
             for (int i = 0; i < CPT; i += 2) {
                 const int k = k0 + tchunk(i) * 8;
                 uint32_t d[8] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w, raw[i + 1].x, raw[i + 1].y, raw[i + 1].z, raw[i + 1].w};
+                if (TAIL) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) d[e] = (k + e < kdim) ? d[e] : 0u;
+                    for (int e = 0; e < 8; ++e) d[e] = (k + e < kdim) ? d[e] : 0u;
+                }
                 const uint4 lo = make_uint4((d[0] & 0xffffu) | (d[1] << 16), (d[2] & 0xffffu) | (d[3] << 16),
                                             (d[4] & 0xffffu) | (d[5] << 16), (d[6] & 0xffffu) | (d[7] << 16));
                 const uint4 hi = make_uint4((d[0] >> 16) | (d[1] & 0xffff0000u), (d[2] >> 16) | (d[3] & 0xffff0000u),
@@ -220,14 +205,16 @@ struct Operand {
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int k = k0 + tchunk(i) * 4;
-                const uint4 u = make_uint4(k < kdim ? raw[i].x : 0u, k + 1 < kdim ? raw[i].y : 0u,
-                                           k + 2 < kdim ? raw[i].z : 0u, k + 3 < kdim ? raw[i].w : 0u);
+                uint4 u = raw[i];
+                if (TAIL)
+                    u = make_uint4(k < kdim ? u.x : 0u, k + 1 < kdim ? u.y : 0u, k + 2 < kdim ? u.z : 0u,
+                                   k + 3 < kdim ? u.w : 0u);
                 *reinterpret_cast<uint4*>(tile + trow(i) * PITCH + tchunk(i) * 16) = u;
             }
         } else {  // x sources: fp32 -> T, whole chunks in or out of the contraction range
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
-                const bool ok = k0 + tchunk(i) * VE < kdim;
+                const bool ok = !TAIL || (k0 + tchunk(i) * VE < kdim);
                 float v[8];
 #pragma unroll
                 for (int q = 0; q < RPC; ++q) {
@@ -407,6 +394,19 @@ __device__ inline int xcd_remap(int bid, int nb) {
     return x * q + (x < rem ? x : rem) + pos;
 }
 
+// One step of the pairwise fold of per-lane slot arrays: lanes whose bit H of lr is set keep the upper H
+// slots, the others the lower H, and each adds what its partner (lr ^ H) held for the kept slots.
+template <int H>
+__device__ inline void fold_slots(float* cs, int lr) {
+    const bool up = (lr & H) != 0;
+#pragma unroll
+    for (int t = 0; t < H; ++t) {
+        const float send = up ? cs[t] : cs[t + H];
+        const float keep = up ? cs[t + H] : cs[t];
+        cs[t] = keep + __shfl_xor(send, H, 64);
+    }
+}
+
 template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
 struct GemmArgs {
     Operand<T, KA, FAST, NCH> a;
@@ -461,19 +461,32 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
     const int kdim = A.kdim;
     const int nk = (kdim + BK - 1) / BK;
     // Register stage + two LDS stages: the loads of step kt+1 are in flight while step kt is multiplied
-    // out of LDS; they are converted and written to the other LDS stage after the products.
+    // out of LDS; they are converted and written to the other LDS stage after the products.  Only the last
+    // step can cross the end of the contraction range; it alone runs the clamped / masked loader.
     constexpr int NRA = Operand<T, KA, FAST, NCH>::NRAW, NRB = Operand<T, KB, FAST, NCH>::NRAW;
     uint4 ra[NRA], rb[NRB];
-    A.load(r0, 0, ra);
-    B.load(c0, 0, rb);
-    A.store(lds[0][0], ra, 0);
-    B.store(lds[0][1], rb, 0);
+    const int nfull = kdim / BK;  // steps [0, nfull) are entirely inside the contraction range
+    if (nfull > 0) {
+        A.template load<false>(r0, 0, ra);
+        B.template load<false>(c0, 0, rb);
+        A.template store<false>(lds[0][0], ra, 0);
+        B.template store<false>(lds[0][1], rb, 0);
+    } else {
+        A.template load<true>(r0, 0, ra);
+        B.template load<true>(c0, 0, rb);
+        A.template store<true>(lds[0][0], ra, 0);
+        B.template store<true>(lds[0][1], rb, 0);
+    }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            A.load(r0, (kt + 1) * BK, ra);
-            B.load(c0, (kt + 1) * BK, rb);
+        const bool more = kt + 1 < nk, full = kt + 1 < nfull;
+        if (full) {
+            A.template load<false>(r0, (kt + 1) * BK, ra);
+            B.template load<false>(c0, (kt + 1) * BK, rb);
+        } else if (more) {
+            A.template load<true>(r0, (kt + 1) * BK, ra);
+            B.template load<true>(c0, (kt + 1) * BK, rb);
         }
         const unsigned char* ta = lds[cur][0] + (wm + lr) * PITCH + lg * 16;
         const unsigned char* tb = lds[cur][1] + (wn + lrp) * PITCH + lg * 16;
@@ -489,9 +502,12 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
 #pragma unroll
                 for (int j = 0; j < 2; ++j) Mma32<T>::run(fb[j], fa[i], acc[i][j]);  // transposed tile
         }
-        if (kt + 1 < nk) {
-            A.store(lds[cur ^ 1][0], ra, (kt + 1) * BK);
-            B.store(lds[cur ^ 1][1], rb, (kt + 1) * BK);
+        if (full) {
+            A.template store<false>(lds[cur ^ 1][0], ra, (kt + 1) * BK);
+            B.template store<false>(lds[cur ^ 1][1], rb, (kt + 1) * BK);
+        } else if (more) {
+            A.template store<true>(lds[cur ^ 1][0], ra, (kt + 1) * BK);
+            B.template store<true>(lds[cur ^ 1][1], rb, (kt + 1) * BK);
         }
         __syncthreads();
     }
@@ -501,12 +517,12 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
     // bf16 access per octet, and the two lane groups of a row together fill 32 contiguous bytes.
     const int rows = A.rows, cols = B.rows;
     float cs[Epi::kColSum ? 32 : 1];
-    typename Epi::Out outs[8];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = r0 + wm + 32 * i + lr;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2; ++j) {
+            typename Epi::Out outs[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
@@ -517,7 +533,7 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
                 // out-of-range octets are computed on a clamped, valid position and not stored
                 const int rc = r < rows ? r : rows - 1;
                 const int cc = c < cols ? c : 0;
-                epi.compute(rc, cc, 8, v, outs[(i * 2 + j) * 2 + h]);
+                epi.compute(rc, cc, 8, v, outs[h]);
                 if (Epi::kColSum) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -526,32 +542,22 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
                     }
                 }
             }
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = r0 + wm + 32 * i + lr;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
-                if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[(i * 2 + j) * 2 + h]);
+                if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[h]);
             }
+        }
     }
     if (Epi::kColSum) {
         // Column sums over the tile's 128 rows, fixed order.  Slot t = 16 j + 8 h + u of a lane is column
         // wn + 32 j + 16 h + 8 lg + u; the 32 lanes of a half-wave (same lg) fold their 32 slots pairwise so
         // that lane lr ends up with the half-wave total of slot lr.
-#pragma unroll
-        for (int hh = 16; hh >= 1; hh >>= 1) {
-            const bool up = (lr & hh) != 0;
-#pragma unroll
-            for (int t = 0; t < hh; ++t) {
-                const float send = up ? cs[t] : cs[t + hh];
-                const float keep = up ? cs[t + hh] : cs[t];
-                cs[t] = keep + __shfl_xor(send, hh, 64);
-            }
-        }
+        fold_slots<16>(cs, lr);
+        fold_slots<8>(cs, lr);
+        fold_slots<4>(cs, lr);
+        fold_slots<2>(cs, lr);
+        fold_slots<1>(cs, lr);
         float* red = reinterpret_cast<float*>(&lds[0][0][0]);  // the staging tiles are no longer read
         {
             const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
@@ -786,24 +792,35 @@ __global__ __launch_bounds__(256) void k_head_bwd_dz(const float* __restrict__ d
 }
 
 // dW_L(p)[j, i] = sum_m dz_L[m, j] h_{L-1}[m, i] and db_L(p)[j] = sum_m dz_L[m, j], in two stages.
-// Stage 1: a block takes 256 rows x 128 columns of one preference; thread (cg, rs) owns 8 columns and the
-// rows rs, rs + 16, ...; the 16 row groups are merged in a fixed order.  Partials go to
-// pw[p][chunk][j][i] and pb[p][chunk][j].  Stage 2 (k_head_bwd_dw_final) adds the chunks in order.
-#define HB_ROWS 256
+// Stage 1: a block takes HB_ROWS rows x 64 columns of one preference.  The dz rows (<= 16 columns,
+// rounded to the GEMM input type) and the h tile sit in LDS; wave w multiplies dz^T [16 x rows] by
+// h [rows x 16 columns 16 w ..] with fp32 16x16x4 MFMAs (bf16 h is widened on the way out of LDS, which
+// is exact).  Partials go to pw[p][chunk][j][i] and pb[p][chunk][j]; stage 2 (k_head_bwd_dw_final) adds
+// the chunks in order.
+#define HB_ROWS 128
 template <typename T>
 __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ dout,
                                                     const float* __restrict__ saved_out,
                                                     const T* __restrict__ Hin, float* __restrict__ pw,
                                                     float* __restrict__ pb, int W, int out_dim, int M, RowMap rm,
                                                     int tanh_head) {
-    __shared__ float sdr[HB_ROWS][MORLAX_MAX_OUT];          // rounded dz (GEMM input)
-    __shared__ float red[4][MORLAX_MAX_OUT][128];           // also holds the unrounded dz at the start
-    __shared__ float bpart[16][MORLAX_MAX_OUT];
     constexpr int VE = Elems<T>::VE;
-    const int p = blockIdx.z, chunk = blockIdx.y, m0 = chunk * HB_ROWS, i0 = blockIdx.x * 128;
+    constexpr int HP = 64 + VE;                            // h tile pitch in elements (16 bytes of padding)
+    __shared__ float sdr[HB_ROWS][MORLAX_MAX_OUT];         // rounded dz (GEMM input)
+    __shared__ float sdu[HB_ROWS][MORLAX_MAX_OUT];         // unrounded dz (bias gradient)
+    __shared__ __align__(16) T sh[HB_ROWS][HP];
+    __shared__ float bpart[16][MORLAX_MAX_OUT];
+    const int p = blockIdx.z, chunk = blockIdx.y, m0 = chunk * HB_ROWS, i0 = blockIdx.x * 64;
     const int n_chunk = gridDim.y;
-    float(*sdu)[MORLAX_MAX_OUT] = reinterpret_cast<float(*)[MORLAX_MAX_OUT]>(&red[0][0][0]);
-    {
+    // stage h: 16-byte pieces, rows beyond M and columns beyond W as zeros
+    for (int idx = threadIdx.x; idx < HB_ROWS * (64 / VE); idx += 256) {
+        const int mm = idx / (64 / VE), cc = (idx % (64 / VE)) * VE;
+        uint4 u = make_uint4(0, 0, 0, 0);
+        if (m0 + mm < M && i0 + cc < W)
+            u = *reinterpret_cast<const uint4*>(Hin + ((int64_t)p * M + m0 + mm) * W + i0 + cc);
+        *reinterpret_cast<uint4*>(&sh[mm][cc]) = u;
+    }
+    if (threadIdx.x < HB_ROWS) {
         const int mm = threadIdx.x;
         const bool ok = m0 + mm < M;
         int64_t row = 0;
@@ -826,76 +843,33 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ d
     if (blockIdx.x == 0) {
         const int j = threadIdx.x & 15, part = threadIdx.x >> 4;
         float b = 0.f;
-        for (int mm = part * 16; mm < part * 16 + 16; ++mm) b += sdu[mm][j];
+        for (int mm = part * (HB_ROWS / 16); mm < (part + 1) * (HB_ROWS / 16); ++mm) b += sdu[mm][j];
         bpart[part][j] = b;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ln = lane & 15, kg = lane >> 4;
+    float4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
+        const int m = 4 * kk + kg;
+        const float a = sdr[m][ln];                 // dz^T[j = ln][m]
+        const float b = to_f(sh[m][16 * wave + ln]);  // h[m][column 16 wave + ln]
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
+    }
+    // lane holds column ln of rows j = 4 kg + e
+    const int col = i0 + 16 * wave + ln;
+    if (col < W) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = 4 * kg + e;
+            if (j < out_dim) pw[(((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + j) * W + col] = acc[e];
+        }
     }
     __syncthreads();
     if (blockIdx.x == 0 && threadIdx.x < out_dim) {
         float v = 0.f;
         for (int part = 0; part < 16; ++part) v += bpart[part][threadIdx.x];
         pb[((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + threadIdx.x] = v;
-    }
-    const int cg = threadIdx.x & 15, rs = threadIdx.x >> 4;
-    const int col = i0 + cg * 8;
-    float acc[MORLAX_MAX_OUT][8];
-#pragma unroll
-    for (int j = 0; j < MORLAX_MAX_OUT; ++j)
-#pragma unroll
-        for (int b = 0; b < 8; ++b) acc[j][b] = 0.f;
-    if (col < W) {
-        for (int mm = rs; mm < HB_ROWS && m0 + mm < M; mm += 16) {
-            const T* src = Hin + ((int64_t)p * M + m0 + mm) * W + col;
-            float h[8];
-#pragma unroll
-            for (int qd = 0; qd < 8 / VE; ++qd) {
-                const uint4 u = *reinterpret_cast<const uint4*>(src + qd * VE);
-                if (sizeof(T) == 2) {
-                    const uint32_t w4[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        h[2 * e] = __uint_as_float(w4[e] << 16);
-                        h[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
-                    }
-                } else {
-                    h[4 * qd] = __uint_as_float(u.x); h[4 * qd + 1] = __uint_as_float(u.y);
-                    h[4 * qd + 2] = __uint_as_float(u.z); h[4 * qd + 3] = __uint_as_float(u.w);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
-                if (j < out_dim) {
-                    const float d = sdr[mm][j];
-#pragma unroll
-                    for (int b = 0; b < 8; ++b) acc[j][b] += d * h[b];
-                }
-            }
-        }
-    }
-    // merge the four row groups of a wave (lanes 16 apart), then the four waves through LDS
-#pragma unroll
-    for (int j = 0; j < MORLAX_MAX_OUT; ++j)
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            float v = acc[j][b];
-            v += __shfl_xor(v, 16, 64);
-            v += __shfl_xor(v, 32, 64);
-            acc[j][b] = v;
-        }
-    __syncthreads();  // sdu (aliased with red) is no longer needed
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) < 16) {
-#pragma unroll
-        for (int j = 0; j < MORLAX_MAX_OUT; ++j)
-#pragma unroll
-            for (int b = 0; b < 8; ++b) red[wave][j][cg * 8 + b] = acc[j][b];
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < out_dim * 128; idx += 256) {
-        const int j = idx / 128, c = idx % 128;
-        if (i0 + c < W) {
-            const float v = red[0][j][c] + red[1][j][c] + red[2][j][c] + red[3][j][c];
-            pw[(((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + j) * W + i0 + c] = v;
-        }
     }
 }
 
@@ -1052,7 +1026,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         const int n_chunk = (M + HB_ROWS - 1) / HB_ROWS;
         float* pw = part;
         float* pb = part + (int64_t)P * n_chunk * MORLAX_MAX_OUT * W;
-        k_head_bwd_dw<T><<<dim3((W + 127) / 128, n_chunk, P), 256, 0, s>>>(dout, saved_out, Hbuf(L - 1), pw, pb, W,
+        k_head_bwd_dw<T><<<dim3((W + 63) / 64, n_chunk, P), 256, 0, s>>>(dout, saved_out, Hbuf(L - 1), pw, pb, W,
                                                                           nd.out_dim, M, rm, tanh_head);
         k_head_bwd_dw_final<<<dim3((nd.out_dim * W + 255) / 256, P), 256, 0, s>>>(
             pw, pb, n_chunk, dtheta_mat, dtheta_vec, nd.mat_len, nd.vec_len, Lh.mat_off, Lh.vec_off, W, nd.out_dim);
