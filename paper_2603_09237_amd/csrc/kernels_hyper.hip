@@ -4,11 +4,13 @@
 #include "morlax_internal.h"
 #include "numeric.h"
 
-#define QC 256  // stacked-affine rows per block of the df partial kernel
+#define QW 128  // stacked-affine rows per wave of the df partial kernel
+#define DAB_COLS 512  // columns of dW one block of the fused dA/dB kernel walks
 
 struct HyperWs {
-    float *h1, *f, *fac, *dfac, *df_part, *df, *dz2, *dz1, *vecs;
-    int n_chunk;
+    float *h1, *f, *fac, *dfac, *df_part, *df, *dz2, *dz1, *vecs, *da_part;
+    int32_t* mrow;  // [q_total] offset of row q of the stacked affine matrix inside hparams
+    int n_chunk, n_cs;
 };
 
 static HyperWs hyper_ws_layout(const morlax_ctx* c, void* ws, int64_t* total) {
@@ -29,8 +31,14 @@ static HyperWs hyper_ws_layout(const morlax_ctx* c, void* ws, int64_t* total) {
     }
     L.fac = take(P * fac);
     L.dfac = take(P * fac);
-    L.n_chunk = (int)((q + QC - 1) / QC);
+    L.n_chunk = (int)((q + QW - 1) / QW);
     L.df_part = take((int64_t)L.n_chunk * P * F);
+    L.mrow = reinterpret_cast<int32_t*>(take(q));
+    {
+        int wmax = c->d.width > c->d.obs_dim ? c->d.width : c->d.obs_dim;
+        L.n_cs = (wmax + DAB_COLS - 1) / DAB_COLS;
+        L.da_part = L.n_cs > 1 ? take((int64_t)L.n_cs * P * fac) : nullptr;
+    }
     if (total) *total = (int64_t)((char*)p - (char*)ws);
     return L;
 }
@@ -227,128 +235,130 @@ __global__ __launch_bounds__(256) void k_hyper_dbase(NetDev nd, const float* __r
     d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w;
 }
 
-struct RowTiles {
-    int32_t tile0[MORLAX_MAX_LAYERS + 1];
+// Fused dA / dB on fp32 MFMA, one pass over dW:
+//   dA_l(p)[o, k] = sum_i dW_l(p)[o, i] B_l(p)[k, i],   dB_l(p)[k, i] = sum_o A_l(p)[o, k] dW_l(p)[o, i].
+// A block owns (p, layer, a run of <= 512 columns).  It walks the 64 x 64 tiles of dW row block by row
+// block: wave w multiplies rows 16 w .. of the tile by B^T (dA, finished after the columns of a row block)
+// and A^T by columns 16 w .. of the tile (dB, accumulated over all row blocks in registers).
+struct DabWork {
+    int32_t n;
+    int16_t layer[4 * MORLAX_MAX_LAYERS];
+    int16_t cs[4 * MORLAX_MAX_LAYERS];
 };
 
-// dA_l(p)[o, k] = sum_i dW_l(p)[o, i] B_l(p)[k, i].  Block: 64 rows o of one layer of one p; a row
-// is handled by 16 lanes (float4 each), B staged in LDS in chunks of 512 columns.
-template <int R_MAX>
-__global__ __launch_bounds__(256) void k_hyper_dA(NetDev nd, RowTiles rt, const float* __restrict__ dmat,
-                                                 const float* __restrict__ fac, float* __restrict__ dfac, int r) {
-    extern __shared__ float sB[];  // [r][512]
+template <int RT>
+__global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const float* __restrict__ dmat,
+                                                  const float* __restrict__ fac, float* __restrict__ dfac,
+                                                  float* __restrict__ da_part, int r, int P) {
+    constexpr int AP = 16 * RT + 4;
+    __shared__ __align__(16) float sW[64][68];
+    __shared__ float sA[64][AP];
+    __shared__ float sB[16 * RT][68];
     const int p = blockIdx.y;
-    int l = 0;
-    while (l + 1 < nd.n_layers && (int)blockIdx.x >= rt.tile0[l + 1]) ++l;
-    const LayerDev L = nd.layer[l];
-    const int o0 = (blockIdx.x - rt.tile0[l]) * 64;
+    const LayerDev L = nd.layer[wk.layer[blockIdx.x]];
+    const int cs = wk.cs[blockIdx.x];
+    const int c_lo = cs * DAB_COLS;
+    const int c_hi = (L.d_in < c_lo + DAB_COLS) ? L.d_in : (c_lo + DAB_COLS);
+    const int nct = (c_hi - c_lo + 63) / 64;
+    const int n_cs = (L.d_in + DAB_COLS - 1) / DAB_COLS;
     const float* dW = dmat + (int64_t)p * nd.mat_len + L.mat_off;
-    const float* B = fac + (int64_t)p * nd.fac_len + L.fac_b;
-    const int rl = threadIdx.x / 16, il = threadIdx.x % 16;  // 16 rows per pass
-    float acc[4][R_MAX];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int k = 0; k < R_MAX; ++k) acc[a][k] = 0.f;
+    const float* Ap = fac + (int64_t)p * nd.fac_len + L.fac_a;
+    const float* Bp = fac + (int64_t)p * nd.fac_len + L.fac_b;
+    float* dAp = (n_cs > 1 ? da_part + ((int64_t)cs * P + p) * nd.fac_len : dfac + (int64_t)p * nd.fac_len) + L.fac_a;
+    float* dBp = dfac + (int64_t)p * nd.fac_len + L.fac_b;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ln = lane & 15, kg = lane >> 4;
     const bool vec = (L.d_in % 4 == 0);
-    for (int c0 = 0; c0 < L.d_in; c0 += 512) {
-        const int cw = (L.d_in - c0 < 512) ? (L.d_in - c0) : 512;
+    float4_t accB[8][RT];
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) accB[ct][rt] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int o0 = 0; o0 < L.d_out; o0 += 64) {
         __syncthreads();
-        for (int idx = threadIdx.x; idx < r * 512; idx += 256) {
-            const int k = idx / 512, ii = idx % 512;
-            sB[idx] = (ii < cw) ? B[(int64_t)k * L.d_in + c0 + ii] : 0.f;
+        for (int idx = threadIdx.x; idx < 64 * 16 * RT; idx += 256) {
+            const int row = idx / (16 * RT), k = idx % (16 * RT);
+            sA[row][k] = (o0 + row < L.d_out && k < r) ? Ap[(int64_t)(o0 + row) * r + k] : 0.f;
         }
-        __syncthreads();
+        float4_t accA[RT];
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int o = o0 + a * 16 + rl;
-            if (o >= L.d_out) continue;
-            for (int ii = il * 4; ii < cw; ii += 64) {
-                float x[4];
-                const float* src = dW + (int64_t)o * L.d_in + c0 + ii;
-                if (vec) {
-                    const float4 v = *reinterpret_cast<const float4*>(src);
-                    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-                } else {
+        for (int rt = 0; rt < RT; ++rt) accA[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) x[b] = (ii + b < cw) ? src[b] : 0.f;
-                }
-#pragma unroll
-                for (int k = 0; k < R_MAX; ++k) {
-                    if (k < r) {
-                        const float* bk = sB + k * 512 + ii;
-                        acc[a][k] += x[0] * bk[0] + x[1] * bk[1] + x[2] * bk[2] + x[3] * bk[3];
+        for (int ct = 0; ct < 8; ++ct) {
+            if (ct < nct) {
+                const int i0 = c_lo + ct * 64;
+                __syncthreads();
+                for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
+                    const int row = idx / 16, c4 = (idx % 16) * 4;
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (o0 + row < L.d_out) {
+                        const float* src = dW + (int64_t)(o0 + row) * L.d_in + i0 + c4;
+                        if (vec && i0 + c4 + 4 <= c_hi) {
+                            v = *reinterpret_cast<const float4*>(src);
+                        } else {
+                            if (i0 + c4 < c_hi) v.x = src[0];
+                            if (i0 + c4 + 1 < c_hi) v.y = src[1];
+                            if (i0 + c4 + 2 < c_hi) v.z = src[2];
+                            if (i0 + c4 + 3 < c_hi) v.w = src[3];
+                        }
                     }
+                    *reinterpret_cast<float4*>(&sW[row][c4]) = v;
+                }
+                for (int idx = threadIdx.x; idx < 16 * RT * 64; idx += 256) {
+                    const int k = idx / 64, cc = idx % 64;
+                    sB[k][cc] = (k < r && i0 + cc < c_hi) ? Bp[(int64_t)k * L.d_in + i0 + cc] : 0.f;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) {
+                    const float a = sW[16 * wave + ln][4 * kk + kg];
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        accA[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, sB[16 * rt + ln][4 * kk + kg], accA[rt], 0, 0, 0);
+                }
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) {
+                    const int row = 16 * (kk >> 2) + (kk & 3) + 4 * kg;
+                    const float b = sW[row][16 * wave + ln];
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        accB[ct][rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(sA[row][16 * rt + ln], b, accB[ct][rt], 0, 0, 0);
                 }
             }
         }
-    }
+        // dA tile: lane holds factor index 16 rt + ln of rows o0 + 16 wave + 4 kg + e
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const int o = o0 + a * 16 + rl;
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int k = 0; k < R_MAX; ++k) {
-            if (k < r) {
-                float v = acc[a][k];
-                v += __shfl_xor(v, 8, 64);
-                v += __shfl_xor(v, 4, 64);
-                v += __shfl_xor(v, 2, 64);
-                v += __shfl_xor(v, 1, 64);
-                if (il == 0 && o < L.d_out) dfac[(int64_t)p * nd.fac_len + L.fac_a + (int64_t)o * r + k] = v;
+            for (int e = 0; e < 4; ++e) {
+                const int o = o0 + 16 * wave + 4 * kg + e, k = 16 * rt + ln;
+                if (o < L.d_out && k < r) dAp[(int64_t)o * r + k] = accA[rt][e];
             }
-        }
     }
+    // dB tiles: lane holds column i of factor rows 16 rt + 4 kg + e
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = c_lo + ct * 64 + 16 * wave + ln, k = 16 * rt + 4 * kg + e;
+                if (ct < nct && i < c_hi && k < r) dBp[(int64_t)k * L.d_in + i] = accB[ct][rt][e];
+            }
 }
 
-struct ColTiles {
-    int32_t tile0[MORLAX_MAX_LAYERS + 1];
-};
-
-// dB_l(p)[k, i] = sum_o A_l(p)[o, k] dW_l(p)[o, i].  Block: 256 columns i of one layer of one p;
-// thread per column, o ascending, A staged in LDS in chunks of 512 rows.
-template <int R_MAX>
-__global__ __launch_bounds__(256) void k_hyper_dB(NetDev nd, ColTiles ct, const float* __restrict__ dmat,
-                                                 const float* __restrict__ fac, float* __restrict__ dfac, int r) {
-    extern __shared__ float sA[];  // [512][r]
+// dA of layers wider than one column run: add the column-run partials in order.
+__global__ __launch_bounds__(256) void k_hyper_dA_merge(NetDev nd, const float* __restrict__ da_part,
+                                                       float* __restrict__ dfac, int r, int P) {
     const int p = blockIdx.y;
-    int l = 0;
-    while (l + 1 < nd.n_layers && (int)blockIdx.x >= ct.tile0[l + 1]) ++l;
-    const LayerDev L = nd.layer[l];
-    const int i = (blockIdx.x - ct.tile0[l]) * 256 + threadIdx.x;
-    const float* dW = dmat + (int64_t)p * nd.mat_len + L.mat_off;
-    const float* A = fac + (int64_t)p * nd.fac_len + L.fac_a;
-    float acc[R_MAX];
-#pragma unroll
-    for (int k = 0; k < R_MAX; ++k) acc[k] = 0.f;
-    for (int o0 = 0; o0 < L.d_out; o0 += 512) {
-        const int oh = (L.d_out - o0 < 512) ? (L.d_out - o0) : 512;
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < oh * r; idx += 256) sA[idx] = A[(int64_t)o0 * r + idx];
-        __syncthreads();
-        if (i < L.d_in) {
-            int oo = 0;
-            for (; oo + 4 <= oh; oo += 4) {
-                float x[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) x[u] = dW[(int64_t)(o0 + oo + u) * L.d_in + i];
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int k = 0; k < R_MAX; ++k)
-                        if (k < r) acc[k] += sA[(oo + u) * r + k] * x[u];
-            }
-            for (; oo < oh; ++oo) {
-                const float x = dW[(int64_t)(o0 + oo) * L.d_in + i];
-#pragma unroll
-                for (int k = 0; k < R_MAX; ++k)
-                    if (k < r) acc[k] += sA[oo * r + k] * x;
-            }
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (int l = 0; l < nd.n_layers; ++l) {
+        const LayerDev L = nd.layer[l];
+        const int n_cs = (L.d_in + DAB_COLS - 1) / DAB_COLS;
+        if (n_cs > 1 && e >= L.fac_a && e < L.fac_a + (int64_t)L.d_out * r) {
+            float a = 0.f;
+            for (int cs = 0; cs < n_cs; ++cs) a += da_part[((int64_t)cs * P + p) * nd.fac_len + e];
+            dfac[(int64_t)p * nd.fac_len + e] = a;
         }
-    }
-    if (i < L.d_in) {
-#pragma unroll
-        for (int k = 0; k < R_MAX; ++k)
-            if (k < r) dfac[(int64_t)p * nd.fac_len + L.fac_b + (int64_t)k * L.d_in + i] = acc[k];
     }
 }
 
@@ -398,56 +408,74 @@ __global__ __launch_bounds__(256) void k_hyper_dM(AffineTable at, const float* _
         if (j < F) mr[j] = acc[j];
 }
 
-// df partials: part[chunk, p, j] = sum over the chunk's rows q of g[p, q] M[q, j].
-__global__ __launch_bounds__(256) void k_hyper_df_part(AffineTable at, const float* __restrict__ hp,
+// Offset inside hparams of every row of the stacked affine matrix (built once per call).
+__global__ __launch_bounds__(256) void k_hyper_mrow(AffineTable at, int32_t* __restrict__ mrow, int F) {
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    if (q >= at.q_total) return;
+    const int s = find_seg(at, q);
+    mrow[q] = (int32_t)(at.hp_m[s] + (int64_t)(q - at.q0[s]) * F);
+}
+
+// df partials on fp32 MFMA: part[chunk, p, j] = sum over the chunk's QW stacked rows q of g[p, q] M[q, j].
+// One wave per chunk; lane (ln, kg) feeds rows p = 16 pt + ln of g and columns j = 16 jt + ln of M for the
+// contraction indices q0 + 4 kg + e, e = 0..3 (one MFMA per e).
+template <int JT>
+__global__ __launch_bounds__(256) void k_hyper_df_part(const float* __restrict__ hp, const int32_t* __restrict__ mrow,
                                                       const float* __restrict__ dfac,
                                                       const float* __restrict__ dvec, float* __restrict__ part,
-                                                      int P, int F, int64_t fac_len, int64_t vec_len) {
-    __shared__ float sM[64][MORLAX_MAX_F];
-    __shared__ float sd[64][65];
-    const int chunk = blockIdx.x;
-    const int pp = threadIdx.x % 64, jq = threadIdx.x / 64;
-    const int JG = (F + 3) / 4;  // <= 16 features per thread
-    const int qa = chunk * QC;
-    const int qb = (qa + QC < at.q_total) ? (qa + QC) : at.q_total;
-    for (int p0 = 0; p0 < P; p0 += 64) {
-        float acc[16];
+                                                      int P, int F, int64_t fac_len, int64_t vec_len, int q_total,
+                                                      int n_chunk) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ln = lane & 15, kg = lane >> 4;
+    const int chunk = blockIdx.x * 4 + wave;
+    if (chunk >= n_chunk) return;
+    const int qa = chunk * QW;
+    const int qb = (qa + QW < q_total) ? (qa + QW) : q_total;
+    for (int p0 = 0; p0 < P; p0 += 128) {
+        float4_t acc[8][JT];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) acc[u] = 0.f;
-        for (int qs = qa; qs < qb; qs += 64) {
-            __syncthreads();
-            for (int idx = threadIdx.x; idx < 64 * F; idx += 256) {
-                const int qq = idx / F, j = idx % F;
-                const int q = qs + qq;
-                float v = 0.f;
-                if (q < qb) {
-                    const int s = find_seg(at, q);
-                    v = hp[at.hp_m[s] + (int64_t)(q - at.q0[s]) * F + j];
+        for (int pt = 0; pt < 8; ++pt)
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) acc[pt][jt] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int q0 = qa; q0 < qb; q0 += 16) {
+            float b[JT][4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int q = q0 + 4 * kg + e;
+                const int off = (q < qb) ? mrow[q] : 0;
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt) {
+                    const int j = 16 * jt + ln;
+                    b[jt][e] = (q < qb && j < F) ? hp[off + j] : 0.f;
                 }
-                sM[qq][j] = v;
             }
-            for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-                const int lp = idx / 64, qq = idx % 64;
-                const int q = qs + qq;
-                sd[lp][qq] = (q < qb && p0 + lp < P) ? grad_row(dfac, dvec, p0 + lp, q, fac_len, vec_len) : 0.f;
-            }
-            __syncthreads();
-            for (int qq = 0; qq < 64; ++qq) {
-                const float d = sd[pp][qq];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int j = jq * JG + u;
-                    if (u < JG && j < F) acc[u] += d * sM[qq][j];
+            for (int pt = 0; pt < 8; ++pt) {
+                const int pp = p0 + 16 * pt + ln;
+                if (p0 + 16 * pt < P) {  // uniform
+                    float a[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int q = q0 + 4 * kg + e;
+                        a[e] = (pp < P && q < qb) ? grad_row(dfac, dvec, pp, q, fac_len, vec_len) : 0.f;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int jt = 0; jt < JT; ++jt)
+                            acc[pt][jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[jt][e], acc[pt][jt], 0, 0, 0);
                 }
             }
         }
-        if (p0 + pp < P) {
+        // lane holds column j = 16 jt + ln of rows p = p0 + 16 pt + 4 kg + e
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int j = jq * JG + u;
-                if (u < JG && j < F) part[((int64_t)chunk * P + p0 + pp) * F + j] = acc[u];
-            }
-        }
+        for (int pt = 0; pt < 8; ++pt)
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int pp = p0 + 16 * pt + 4 * kg + e, j = 16 * jt + ln;
+                    if (pp < P && j < F) part[((int64_t)chunk * P + pp) * F + j] = acc[pt][jt][e];
+                }
     }
 }
 
@@ -463,42 +491,54 @@ __global__ __launch_bounds__(256) void k_hyper_df_final(const float* __restrict_
     dz2[i] = a * (1.f - fv * fv);
 }
 
-// Trunk backward in one block: dWh2, dbh2, dz1, dWh1, dbh1 (sums over p ascending).
-__global__ __launch_bounds__(256) void k_hyper_trunk_bwd(const float* __restrict__ hp, const float* __restrict__ w,
-                                                        const float* __restrict__ h1,
-                                                        const float* __restrict__ dz2, float* __restrict__ dz1,
-                                                        float* __restrict__ dhp, int P, int K, int F,
-                                                        int64_t o_wh1, int64_t o_bh1, int64_t o_wh2,
-                                                        int64_t o_bh2) {
-    for (int idx = threadIdx.x; idx < F * F; idx += 256) {
+// Trunk backward, stage 1: dWh2, dbh2 (sums over p ascending) and dz1 = (dz2 Wh2) * (1 - h1^2).
+// One thread per output element.
+__global__ __launch_bounds__(256) void k_hyper_trunk_bwd_a(const float* __restrict__ hp, const float* __restrict__ h1,
+                                                          const float* __restrict__ dz2, float* __restrict__ dz1,
+                                                          float* __restrict__ dhp, int P, int F, int64_t o_wh2,
+                                                          int64_t o_bh2) {
+    int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < F * F) {
         const int j = idx / F, i = idx % F;
         float a = 0.f;
         for (int p = 0; p < P; ++p) a += dz2[p * F + j] * h1[p * F + i];
         dhp[o_wh2 + idx] = a;
+        return;
     }
-    for (int j = threadIdx.x; j < F; j += 256) {
+    idx -= F * F;
+    if (idx < F) {
         float a = 0.f;
-        for (int p = 0; p < P; ++p) a += dz2[p * F + j];
-        dhp[o_bh2 + j] = a;
+        for (int p = 0; p < P; ++p) a += dz2[p * F + idx];
+        dhp[o_bh2 + idx] = a;
+        return;
     }
-    for (int idx = threadIdx.x; idx < P * F; idx += 256) {
+    idx -= F;
+    if (idx < P * F) {
         const int p = idx / F, i = idx % F;
         float a = 0.f;
         for (int j = 0; j < F; ++j) a += dz2[p * F + j] * hp[o_wh2 + (int64_t)j * F + i];
         const float h = h1[idx];
         dz1[idx] = a * (1.f - h * h);
     }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < F * K; idx += 256) {
+}
+
+// Stage 2: dWh1, dbh1 (sums over p ascending).
+__global__ __launch_bounds__(256) void k_hyper_trunk_bwd_b(const float* __restrict__ w, const float* __restrict__ dz1,
+                                                          float* __restrict__ dhp, int P, int K, int F, int64_t o_wh1,
+                                                          int64_t o_bh1) {
+    int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < F * K) {
         const int i = idx / K, k = idx % K;
         float a = 0.f;
         for (int p = 0; p < P; ++p) a += dz1[p * F + i] * w[p * K + k];
         dhp[o_wh1 + idx] = a;
+        return;
     }
-    for (int i = threadIdx.x; i < F; i += 256) {
+    idx -= F * K;
+    if (idx < F) {
         float a = 0.f;
-        for (int p = 0; p < P; ++p) a += dz1[p * F + i];
-        dhp[o_bh1 + i] = a;
+        for (int p = 0; p < P; ++p) a += dz1[p * F + idx];
+        dhp[o_bh1 + idx] = a;
     }
 }
 
@@ -513,29 +553,35 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
     run_trunk_and_affine(c, net, hparams, w, L, nullptr, L.vecs, s);
     k_hyper_dbase<<<(int)((nd.mat_len / 4 + 255) / 256), 256, 0, s>>>(nd, dtheta_mat, dhparams, P);
     if (r > 0) {
-        RowTiles rt;
-        ColTiles ct;
-        int ta = 0, tb = 0;
+        DabWork wk;
+        wk.n = 0;
+        bool split = false;
         for (int l = 0; l < nd.n_layers; ++l) {
-            rt.tile0[l] = ta; ta += (nd.layer[l].d_out + 63) / 64;
-            ct.tile0[l] = tb; tb += (nd.layer[l].d_in + 255) / 256;
+            const int n_cs = (nd.layer[l].d_in + DAB_COLS - 1) / DAB_COLS;
+            split |= n_cs > 1;
+            for (int cs = 0; cs < n_cs; ++cs) {
+                wk.layer[wk.n] = (int16_t)l;
+                wk.cs[wk.n] = (int16_t)cs;
+                ++wk.n;
+            }
         }
-        rt.tile0[nd.n_layers] = ta;
-        ct.tile0[nd.n_layers] = tb;
-        const size_t lds = (size_t)r * 512 * sizeof(float);
-        if (r <= 16) {
-            k_hyper_dA<16><<<dim3(ta, P), 256, lds, s>>>(nd, rt, dtheta_mat, L.fac, L.dfac, r);
-            k_hyper_dB<16><<<dim3(tb, P), 256, lds, s>>>(nd, ct, dtheta_mat, L.fac, L.dfac, r);
-        } else {
-            k_hyper_dA<32><<<dim3(ta, P), 256, lds, s>>>(nd, rt, dtheta_mat, L.fac, L.dfac, r);
-            k_hyper_dB<32><<<dim3(tb, P), 256, lds, s>>>(nd, ct, dtheta_mat, L.fac, L.dfac, r);
-        }
+        if (r <= 16) k_hyper_dAB<1><<<dim3(wk.n, P), 256, 0, s>>>(nd, wk, dtheta_mat, L.fac, L.dfac, L.da_part, r, P);
+        else k_hyper_dAB<2><<<dim3(wk.n, P), 256, 0, s>>>(nd, wk, dtheta_mat, L.fac, L.dfac, L.da_part, r, P);
+        if (split)
+            k_hyper_dA_merge<<<dim3((int)((nd.fac_len + 255) / 256), P), 256, 0, s>>>(nd, L.da_part, L.dfac, r, P);
     }
     k_hyper_dM<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.f, L.dfac, dtheta_vec, dhparams, P, F, nd.fac_len,
                                                        nd.vec_len);
-    k_hyper_df_part<<<L.n_chunk, 256, 0, s>>>(at, hparams, L.dfac, dtheta_vec, L.df_part, P, F, nd.fac_len,
-                                              nd.vec_len);
-    k_hyper_df_final<<<(P * F + 255) / 256, 256, 0, s>>>(L.df_part, L.n_chunk, L.f, L.dz2, P * F);
-    k_hyper_trunk_bwd<<<1, 256, 0, s>>>(hparams, w, L.h1, L.dz2, L.dz1, dhparams, P, K, F, nd.hp_wh1, nd.hp_bh1,
-                                        nd.hp_wh2, nd.hp_bh2);
+    k_hyper_mrow<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.mrow, F);
+    const int n_chunk = (at.q_total + QW - 1) / QW;
+    if (F <= 32)
+        k_hyper_df_part<2><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, L.dfac, dtheta_vec, L.df_part, P, F,
+                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk);
+    else
+        k_hyper_df_part<4><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, L.dfac, dtheta_vec, L.df_part, P, F,
+                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk);
+    k_hyper_df_final<<<(P * F + 255) / 256, 256, 0, s>>>(L.df_part, n_chunk, L.f, L.dz2, P * F);
+    k_hyper_trunk_bwd_a<<<(F * F + F + P * F + 255) / 256, 256, 0, s>>>(hparams, L.h1, L.dz2, L.dz1, dhparams, P, F,
+                                                                       nd.hp_wh2, nd.hp_bh2);
+    k_hyper_trunk_bwd_b<<<(F * K + F + 255) / 256, 256, 0, s>>>(w, L.dz1, dhparams, P, K, F, nd.hp_wh1, nd.hp_bh1);
 }
