@@ -330,6 +330,12 @@ struct EpiFwd {  // h = act(z + b) and, when SAVE, act'(z); compact [M][ld] stor
         put8(H + (int64_t)r * ld + c, o.h);
         if (SAVE) put8(G + (int64_t)r * ld + c, o.g);
     }
+    // row-contiguous stores through an LDS patch (see the kernel): arrays, element size, row-0 address
+    static constexpr bool kStage = true;
+    static constexpr int kArrays = SAVE ? 2 : 1;
+    static constexpr int kES = (int)sizeof(T);
+    __device__ inline char* arr(int a) const { return a == 0 ? reinterpret_cast<char*>(H) : reinterpret_cast<char*>(G); }
+    __device__ static inline const Pack8& pk(const Out& o, int a) { return a == 0 ? o.h : o.g; }
 };
 template <typename T>
 struct EpiDx {  // dZ_{l-1} = (dZ_l W_l) * act'(z_{l-1})
@@ -351,6 +357,11 @@ struct EpiDx {  // dZ_{l-1} = (dZ_l W_l) * act'(z_{l-1})
         (void)n;
         put8(dZ + (int64_t)r * ld + c, o.d);
     }
+    static constexpr bool kStage = false;  // direct 16-byte stores measured faster here
+    static constexpr int kArrays = 1;
+    static constexpr int kES = (int)sizeof(T);
+    __device__ inline char* arr(int) const { return reinterpret_cast<char*>(dZ); }
+    __device__ static inline const Pack8& pk(const Out& o, int) { return o.d; }
 };
 struct EpiDw {  // dW_l(p)[o, i]
     float* dW;
@@ -373,6 +384,11 @@ struct EpiDw {  // dW_l(p)[o, i]
                 if (i < n) d[i] = __uint_as_float(w[i]);
         }
     }
+    static constexpr bool kStage = false;
+    static constexpr int kArrays = 1;
+    static constexpr int kES = 4;
+    __device__ inline char* arr(int) const { return reinterpret_cast<char*>(dW); }
+    __device__ static inline const Pack8& pk(const Out& o, int) { return o.w; }
 };
 
 template <typename T, int ACT, bool SAVE>
@@ -517,14 +533,23 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
     // bf16 access per octet, and the two lane groups of a row together fill 32 contiguous bytes.
     const int rows = A.rows, cols = B.rows;
     float cs[Epi::kColSum ? 32 : 1];
+    // kStage epilogues send their stores through a per-wave LDS patch (32 rows x 64 columns) so that every
+    // store instruction writes whole 128-byte (bf16) or 256-byte (fp32) row segments instead of 32 bytes in
+    // each of 32 rows; with two output arrays per tile that measured faster, with one it did not.
+    constexpr int ES = Epi::kES;
+    constexpr int WP = 64 * ES + 16;            // patch pitch in bytes
+    constexpr int PPR = 64 * ES / 16;           // 16-byte pieces per patch row
+    constexpr int NB = Epi::kStage ? 4 : 2;     // octets computed before their stores are issued
+    unsigned char* patch = &lds[0][0][0] + wave * (32 * WP);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = r0 + wm + 32 * i + lr;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            typename Epi::Out outs[2];
+        for (int jb = 0; jb < 4 / NB; ++jb) {
+            typename Epi::Out outs[NB];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int o = 0; o < NB; ++o) {
+                const int j = (NB == 4) ? (o >> 1) : jb, h = o & 1;
                 const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
                 float v[8];
 #pragma unroll
@@ -533,7 +558,7 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
                 // out-of-range octets are computed on a clamped, valid position and not stored
                 const int rc = r < rows ? r : rows - 1;
                 const int cc = c < cols ? c : 0;
-                epi.compute(rc, cc, 8, v, outs[h]);
+                epi.compute(rc, cc, 8, v, outs[o]);
                 if (Epi::kColSum) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -542,10 +567,34 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
                     }
                 }
             }
+            if (Epi::kStage) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
-                if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[h]);
+                for (int a = 0; a < Epi::kArrays; ++a) {
+#pragma unroll
+                    for (int o = 0; o < NB; ++o) {
+                        unsigned char* dst = patch + lr * WP + (32 * (o >> 1) + 16 * (o & 1) + 8 * lg) * ES;
+                        const Pack8& pk = Epi::pk(outs[o], a);
+                        *reinterpret_cast<uint4*>(dst) = pk.lo;
+                        if (ES == 4) *reinterpret_cast<uint4*>(dst + 16) = pk.hi;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    char* base = epi.arr(a);
+#pragma unroll
+                    for (int it = 0; it < 32 * PPR / 64; ++it) {
+                        const int q = it * 64 + lane, prow = q / PPR, pc = q % PPR;
+                        const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * WP + pc * 16);
+                        const int gr = r0 + wm + 32 * i + prow, gc = c0 + wn + pc * (16 / ES);
+                        if (gr < rows && gc < cols)
+                            *reinterpret_cast<uint4*>(base + ((int64_t)gr * epi.ld + gc) * ES) = u;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            } else {
+#pragma unroll
+                for (int o = 0; o < NB; ++o) {
+                    const int c = c0 + wn + 32 * jb + 16 * (o & 1) + 8 * lg;
+                    if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[o]);
+                }
             }
         }
     }
@@ -558,7 +607,7 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
         fold_slots<4>(cs, lr);
         fold_slots<2>(cs, lr);
         fold_slots<1>(cs, lr);
-        float* red = reinterpret_cast<float*>(&lds[0][0][0]);  // the staging tiles are no longer read
+        float* red = reinterpret_cast<float*>(&lds[0][0][0] + 4 * 32 * WP);  // behind the store patches
         {
             const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
             red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
