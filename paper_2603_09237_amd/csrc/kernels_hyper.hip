@@ -273,7 +273,33 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
     for (int ct = 0; ct < 8; ++ct)
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) accB[ct][rt] = float4_t{0.f, 0.f, 0.f, 0.f};
-    for (int o0 = 0; o0 < L.d_out; o0 += 64) {
+    // The tiles are walked row block by row block; the next tile of dW is fetched into registers while the
+    // current one is multiplied out of LDS.
+    const int nrb = (L.d_out + 63) / 64, ntile = nrb * nct;
+    auto fetch = [&](int tile, float4 (&regs)[4]) {
+        const int o0 = (tile / nct) * 64, i0 = c_lo + (tile % nct) * 64;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = threadIdx.x + 256 * q, row = idx / 16, c4 = (idx % 16) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (o0 + row < L.d_out) {
+                const float* src = dW + (int64_t)(o0 + row) * L.d_in + i0 + c4;
+                if (vec && i0 + c4 + 4 <= c_hi) {
+                    v = *reinterpret_cast<const float4*>(src);
+                } else {
+                    if (i0 + c4 < c_hi) v.x = src[0];
+                    if (i0 + c4 + 1 < c_hi) v.y = src[1];
+                    if (i0 + c4 + 2 < c_hi) v.z = src[2];
+                    if (i0 + c4 + 3 < c_hi) v.w = src[3];
+                }
+            }
+            regs[q] = v;
+        }
+    };
+    float4 nxt[4];
+    fetch(0, nxt);
+    for (int rb = 0; rb < nrb; ++rb) {
+        const int o0 = rb * 64;
         __syncthreads();
         for (int idx = threadIdx.x; idx < 64 * 16 * RT; idx += 256) {
             const int row = idx / (16 * RT), k = idx % (16 * RT);
@@ -287,26 +313,16 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
             if (ct < nct) {
                 const int i0 = c_lo + ct * 64;
                 __syncthreads();
-                for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
-                    const int row = idx / 16, c4 = (idx % 16) * 4;
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (o0 + row < L.d_out) {
-                        const float* src = dW + (int64_t)(o0 + row) * L.d_in + i0 + c4;
-                        if (vec && i0 + c4 + 4 <= c_hi) {
-                            v = *reinterpret_cast<const float4*>(src);
-                        } else {
-                            if (i0 + c4 < c_hi) v.x = src[0];
-                            if (i0 + c4 + 1 < c_hi) v.y = src[1];
-                            if (i0 + c4 + 2 < c_hi) v.z = src[2];
-                            if (i0 + c4 + 3 < c_hi) v.w = src[3];
-                        }
-                    }
-                    *reinterpret_cast<float4*>(&sW[row][c4]) = v;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = threadIdx.x + 256 * q;
+                    *reinterpret_cast<float4*>(&sW[idx / 16][(idx % 16) * 4]) = nxt[q];
                 }
                 for (int idx = threadIdx.x; idx < 16 * RT * 64; idx += 256) {
                     const int k = idx / 64, cc = idx % 64;
                     sB[k][cc] = (k < r && i0 + cc < c_hi) ? Bp[(int64_t)k * L.d_in + i0 + cc] : 0.f;
                 }
+                if (rb * nct + ct + 1 < ntile) fetch(rb * nct + ct + 1, nxt);
                 __syncthreads();
 #pragma unroll
                 for (int kk = 0; kk < 16; ++kk) {
@@ -479,16 +495,23 @@ __global__ __launch_bounds__(256) void k_hyper_df_part(const float* __restrict__
     }
 }
 
-// df[p, j] = sum_chunk part; dz2 = df * (1 - f^2)
+// df[p, j] = sum_chunk part; dz2 = df * (1 - f^2).  64 outputs per block; the four thread groups take the
+// chunks c = g, g + 4, ... and are merged in group order.
 __global__ __launch_bounds__(256) void k_hyper_df_final(const float* __restrict__ part, int n_chunk,
                                                        const float* __restrict__ f, float* __restrict__ dz2,
                                                        int PF) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= PF) return;
+    __shared__ float red[4][64];
+    const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + o;
     float a = 0.f;
-    for (int c = 0; c < n_chunk; ++c) a += part[(int64_t)c * PF + i];
-    const float fv = f[i];
-    dz2[i] = a * (1.f - fv * fv);
+    if (i < PF)
+        for (int c = g; c < n_chunk; c += 4) a += part[(int64_t)c * PF + i];
+    red[g][o] = a;
+    __syncthreads();
+    if (g == 0 && i < PF) {
+        const float fv = f[i];
+        dz2[i] = (red[0][o] + red[1][o] + red[2][o] + red[3][o]) * (1.f - fv * fv);
+    }
 }
 
 // Trunk backward, stage 1: dWh2, dbh2 (sums over p ascending) and dz1 = (dz2 Wh2) * (1 - h1^2).
@@ -580,7 +603,7 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
     else
         k_hyper_df_part<4><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, L.dfac, dtheta_vec, L.df_part, P, F,
                                                             nd.fac_len, nd.vec_len, at.q_total, n_chunk);
-    k_hyper_df_final<<<(P * F + 255) / 256, 256, 0, s>>>(L.df_part, n_chunk, L.f, L.dz2, P * F);
+    k_hyper_df_final<<<(P * F + 63) / 64, 256, 0, s>>>(L.df_part, n_chunk, L.f, L.dz2, P * F);
     k_hyper_trunk_bwd_a<<<(F * F + F + P * F + 255) / 256, 256, 0, s>>>(hparams, L.h1, L.dz2, L.dz1, dhparams, P, F,
                                                                        nd.hp_wh2, nd.hp_bh2);
     k_hyper_trunk_bwd_b<<<(F * K + F + 255) / 256, 256, 0, s>>>(w, L.dz1, dhparams, P, K, F, nd.hp_wh1, nd.hp_bh1);
