@@ -423,6 +423,108 @@ __device__ inline void fold_slots(float* cs, int lr) {
     }
 }
 
+// ---- epilogue shared by the grouped GEMM kernels.  `lds0` is the workgroup's LDS, free for reuse (at
+// least 36 KB); all four waves call this after a barrier.
+template <class Epi>
+__device__ inline void gemm_epilogue(const Epi& epi, float16_t (&acc)[2][2], unsigned char* lds0, int p, int tm,
+                                     int tiles_m, int r0, int c0, int rows, int cols) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lr = lane & 31, lg = lane >> 5;
+    // The products were issued with the operands swapped, so each 32x32 accumulator holds the transposed
+    // tile: lane (lr, lg) owns output row lr; with the row permutation of the B fragments its 16 values
+    // are the columns 16 h + 8 lg + 0..7 for h = 0, 1 (accumulator elements 8 h .. 8 h + 7) -- one 16-byte
+    // bf16 access per octet, and the two lane groups of a row together fill 32 contiguous bytes.
+    float cs[Epi::kColSum ? 32 : 1];
+    // kStage epilogues send their stores through a per-wave LDS patch (32 rows x 64 columns) so that every
+    // store instruction writes whole 128-byte (bf16) or 256-byte (fp32) row segments instead of 32 bytes in
+    // each of 32 rows; with two output arrays per tile that measured faster, with one it did not.
+    constexpr int ES = Epi::kES;
+    constexpr int WP = 64 * ES + 16;            // patch pitch in bytes
+    constexpr int PPR = 64 * ES / 16;           // 16-byte pieces per patch row
+    constexpr int NB = Epi::kStage ? 4 : 2;     // octets computed before their stores are issued
+    unsigned char* patch = lds0 + wave * (32 * WP);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = r0 + wm + 32 * i + lr;
+#pragma unroll
+        for (int jb = 0; jb < 4 / NB; ++jb) {
+            typename Epi::Out outs[NB];
+#pragma unroll
+            for (int o = 0; o < NB; ++o) {
+                const int j = (NB == 4) ? (o >> 1) : jb, h = o & 1;
+                const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = acc[i][j][8 * h + u];
+                const bool ok = (r < rows) && (c < cols);
+                // out-of-range octets are computed on a clamped, valid position and not stored
+                const int rc = r < rows ? r : rows - 1;
+                const int cc = c < cols ? c : 0;
+                epi.compute(rc, cc, 8, v, outs[o]);
+                if (Epi::kColSum) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int t = Epi::kColSum ? (16 * j + 8 * h + u) : 0;
+                        cs[t] = (i == 0 ? 0.f : cs[t]) + (ok ? v[u] : 0.f);
+                    }
+                }
+            }
+            if (Epi::kStage) {
+#pragma unroll
+                for (int a = 0; a < Epi::kArrays; ++a) {
+#pragma unroll
+                    for (int o = 0; o < NB; ++o) {
+                        unsigned char* dst = patch + lr * WP + (32 * (o >> 1) + 16 * (o & 1) + 8 * lg) * ES;
+                        const Pack8& pk = Epi::pk(outs[o], a);
+                        *reinterpret_cast<uint4*>(dst) = pk.lo;
+                        if (ES == 4) *reinterpret_cast<uint4*>(dst + 16) = pk.hi;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    char* base = epi.arr(a);
+#pragma unroll
+                    for (int it = 0; it < 32 * PPR / 64; ++it) {
+                        const int q = it * 64 + lane, prow = q / PPR, pc = q % PPR;
+                        const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * WP + pc * 16);
+                        const int gr = r0 + wm + 32 * i + prow, gc = c0 + wn + pc * (16 / ES);
+                        if (gr < rows && gc < cols)
+                            *reinterpret_cast<uint4*>(base + ((int64_t)gr * epi.ld + gc) * ES) = u;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            } else {
+#pragma unroll
+                for (int o = 0; o < NB; ++o) {
+                    const int c = c0 + wn + 32 * jb + 16 * (o & 1) + 8 * lg;
+                    if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[o]);
+                }
+            }
+        }
+    }
+    if (Epi::kColSum) {
+        // Column sums over the tile's 128 rows, fixed order.  Slot t = 16 j + 8 h + u of a lane is column
+        // wn + 32 j + 16 h + 8 lg + u; the 32 lanes of a half-wave (same lg) fold their 32 slots pairwise so
+        // that lane lr ends up with the half-wave total of slot lr.
+        fold_slots<16>(cs, lr);
+        fold_slots<8>(cs, lr);
+        fold_slots<4>(cs, lr);
+        fold_slots<2>(cs, lr);
+        fold_slots<1>(cs, lr);
+        float* red = reinterpret_cast<float*>(lds0 + 4 * 32 * WP);  // behind the store patches
+        {
+            const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
+            red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
+        }
+        __syncthreads();
+        if (threadIdx.x < 128) {
+            const int wsel = threadIdx.x >> 6, col = threadIdx.x & 63;
+            const float v = red[wsel * 64 + col] + red[(2 + wsel) * 64 + col];
+            if (c0 + threadIdx.x < cols)
+                epi.part[((int64_t)p * tiles_m + tm) * epi.ld + c0 + threadIdx.x] = v;
+        }
+    }
+}
+
 template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
 struct GemmArgs {
     Operand<T, KA, FAST, NCH> a;
@@ -527,99 +629,158 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
         }
         __syncthreads();
     }
-    // The products were issued with the operands swapped, so each 32x32 accumulator holds the transposed
-    // tile: lane (lr, lg) owns output row lr; with the row permutation of the B fragments its 16 values
-    // are the columns 16 h + 8 lg + 0..7 for h = 0, 1 (accumulator elements 8 h .. 8 h + 7) -- one 16-byte
-    // bf16 access per octet, and the two lane groups of a row together fill 32 contiguous bytes.
-    const int rows = A.rows, cols = B.rows;
-    float cs[Epi::kColSum ? 32 : 1];
-    // kStage epilogues send their stores through a per-wave LDS patch (32 rows x 64 columns) so that every
-    // store instruction writes whole 128-byte (bf16) or 256-byte (fp32) row segments instead of 32 bytes in
-    // each of 32 rows; with two output arrays per tile that measured faster, with one it did not.
-    constexpr int ES = Epi::kES;
-    constexpr int WP = 64 * ES + 16;            // patch pitch in bytes
-    constexpr int PPR = 64 * ES / 16;           // 16-byte pieces per patch row
-    constexpr int NB = Epi::kStage ? 4 : 2;     // octets computed before their stores are issued
-    unsigned char* patch = &lds[0][0][0] + wave * (32 * WP);
+    gemm_epilogue(epi, acc, &lds[0][0][0], p, tm, g.tiles_m, r0, c0, A.rows, B.rows);
+}
+
+// ---- bf16 grouped GEMM with direct-to-LDS loads ------------------------------------------------
+// Same tiles, wave layout and epilogues as k_grouped_gemm, for bf16 operands whose shapes need no
+// masking (the launcher checks them).  Operand tiles go from global memory straight into LDS, 16 bytes
+// per lane, DMA_NST - 1 contraction steps ahead of the products, so that the latency of a load from HBM
+// is covered by several steps of MFMAs instead of one.  A DMA instruction fills 1 KB of LDS, lane l
+// writing bytes 16 l .. 16 l + 15 of it; which global chunk a lane fetches is free, and that is where
+// the bank swizzles below are applied.
+//   SRC_KCONTIG  operand, stage = 128 rows x 4 chunks (8 contraction indices each): chunk (r, c) sits at
+//                position 4 r + (c ^ swz(r)); fragments are read with one 16-byte LDS read.
+//   SRC_KSTRIDED operand (global [k][row]), stage = 32 k x 16 chunks (8 rows each): chunk (k, ic) sits at
+//                position 16 k + (ic ^ 2 (k & 3)); fragments are read with two transposing 8-byte reads,
+//                each of which hands lane b of a 16-lane group the elements [k0 .. k0+3][row b] of the
+//                4 x 16 block whose 64-bit words the lanes 4 e + c (k = k0 + e, rows 4 c .. 4 c + 3) address.
+#define DMA_NST 4
+#define DMA_STAGE_BYTES 16384  // A tile 8 KB, then B tile 8 KB
+
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+__device__ inline void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+__device__ inline int swz_rk(int r) { return ((r >> 1) & 1) | ((((r >> 2) ^ (r >> 3)) & 1) << 1); }
+
+template <int KIND>
+struct DmaOperand {
+    const char* base;   // per-preference base, bytes
+    uint32_t voff[2];   // lane offsets of its two DMA instructions per stage
+    int64_t kstep;      // bytes per contraction step (32 indices)
+    uint32_t roff;      // lane's LDS byte offset of fragment (block 0, ks 0) within the operand's stage tile
+
+    __device__ inline void init(const bf16_t* b, int ld, int rows, int t0, int wbase, bool brole) {
+        base = reinterpret_cast<const char*>(b);
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = r0 + wm + 32 * i + lr;
-#pragma unroll
-        for (int jb = 0; jb < 4 / NB; ++jb) {
-            typename Epi::Out outs[NB];
-#pragma unroll
-            for (int o = 0; o < NB; ++o) {
-                const int j = (NB == 4) ? (o >> 1) : jb, h = o & 1;
-                const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
-                float v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = acc[i][j][8 * h + u];
-                const bool ok = (r < rows) && (c < cols);
-                // out-of-range octets are computed on a clamped, valid position and not stored
-                const int rc = r < rows ? r : rows - 1;
-                const int cc = c < cols ? c : 0;
-                epi.compute(rc, cc, 8, v, outs[o]);
-                if (Epi::kColSum) {
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int t = Epi::kColSum ? (16 * j + 8 * h + u) : 0;
-                        cs[t] = (i == 0 ? 0.f : cs[t]) + (ok ? v[u] : 0.f);
-                    }
-                }
-            }
-            if (Epi::kStage) {
-#pragma unroll
-                for (int a = 0; a < Epi::kArrays; ++a) {
-#pragma unroll
-                    for (int o = 0; o < NB; ++o) {
-                        unsigned char* dst = patch + lr * WP + (32 * (o >> 1) + 16 * (o & 1) + 8 * lg) * ES;
-                        const Pack8& pk = Epi::pk(outs[o], a);
-                        *reinterpret_cast<uint4*>(dst) = pk.lo;
-                        if (ES == 4) *reinterpret_cast<uint4*>(dst + 16) = pk.hi;
-                    }
-                    __builtin_amdgcn_wave_barrier();
-                    char* base = epi.arr(a);
-#pragma unroll
-                    for (int it = 0; it < 32 * PPR / 64; ++it) {
-                        const int q = it * 64 + lane, prow = q / PPR, pc = q % PPR;
-                        const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * WP + pc * 16);
-                        const int gr = r0 + wm + 32 * i + prow, gc = c0 + wn + pc * (16 / ES);
-                        if (gr < rows && gc < cols)
-                            *reinterpret_cast<uint4*>(base + ((int64_t)gr * epi.ld + gc) * ES) = u;
-                    }
-                    __builtin_amdgcn_wave_barrier();
-                }
+        for (int i = 0; i < 2; ++i) {
+            const int j = 2 * wave + i;
+            if (KIND == SRC_KCONTIG) {
+                const int row = 16 * j + lane / 4, c = (lane % 4) ^ swz_rk(row);
+                int gr = t0 + row;
+                gr = gr < rows ? gr : rows - 1;
+                voff[i] = (uint32_t)((gr * ld + 8 * c) * 2);
             } else {
-#pragma unroll
-                for (int o = 0; o < NB; ++o) {
-                    const int c = c0 + wn + 32 * jb + 16 * (o & 1) + 8 * lg;
-                    if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[o]);
-                }
+                const int k = 4 * j + lane / 16, ic = (lane % 16) ^ (2 * (k & 3));
+                int gr = t0 + 8 * ic;
+                gr = gr < rows - 8 ? gr : rows - 8;
+                voff[i] = (uint32_t)((k * ld + gr) * 2);
             }
         }
-    }
-    if (Epi::kColSum) {
-        // Column sums over the tile's 128 rows, fixed order.  Slot t = 16 j + 8 h + u of a lane is column
-        // wn + 32 j + 16 h + 8 lg + u; the 32 lanes of a half-wave (same lg) fold their 32 slots pairwise so
-        // that lane lr ends up with the half-wave total of slot lr.
-        fold_slots<16>(cs, lr);
-        fold_slots<8>(cs, lr);
-        fold_slots<4>(cs, lr);
-        fold_slots<2>(cs, lr);
-        fold_slots<1>(cs, lr);
-        float* red = reinterpret_cast<float*>(&lds[0][0][0] + 4 * 32 * WP);  // behind the store patches
-        {
-            const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
-            red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
-        }
-        __syncthreads();
-        if (threadIdx.x < 128) {
-            const int wsel = threadIdx.x >> 6, col = threadIdx.x & 63;
-            const float v = red[wsel * 64 + col] + red[(2 + wsel) * 64 + col];
-            if (c0 + threadIdx.x < cols)
-                epi.part[((int64_t)p * g.tiles_m + tm) * epi.ld + c0 + threadIdx.x] = v;
+        kstep = (KIND == SRC_KCONTIG) ? 64 : (int64_t)64 * ld;
+        const int lr = lane & 31, lg = lane >> 5;
+        if (KIND == SRC_KCONTIG) {
+            const int rr = brole ? ((lr & 0x13) | ((lr & 4) << 1) | ((lr & 8) >> 1)) : lr;
+            const int row = wbase + rr;
+            roff = (uint32_t)(row * 64 + ((lg ^ swz_rk(row)) * 16));
+        } else {
+            const int a = lane & 15, q0 = (lane >> 4) & 1, e = a >> 2, c = a & 3;
+            const int cs = brole ? (((c & 1) << 1) | (c >> 1)) : c;
+            const int col = wbase + 16 * q0 + 4 * cs, k = 8 * lg + e;
+            roff = (uint32_t)((k * 16 + ((col >> 3) ^ (2 * (k & 3)))) * 16 + ((col >> 2) & 1) * 8);
         }
     }
+    // issue the loads of contraction step kt into the stage tile at LDS address `tile`
+    __device__ inline void issue(int kt, uint32_t tile) const {
+        const char* b = base + (int64_t)kt * kstep;
+        const int wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            dma16(b, voff[i], __builtin_amdgcn_readfirstlane(tile + (uint32_t)(2 * wave + i) * 1024u));
+    }
+    // fragment of 32-row block `blk` (0, 1) for the 16 contraction indices ks (0, 1) of the stage
+    __device__ inline uint4 frag(const unsigned char* tile, int blk, int ks) const {
+        if (KIND == SRC_KCONTIG) {
+            // chunk 2 ks + lg: the swizzle only touches the low two bits, so ks selects the upper half
+            return *reinterpret_cast<const uint4*>(tile + ((roff + blk * 2048) ^ (uint32_t)(ks * 32)));
+        } else {
+            typedef __attribute__((address_space(3))) short4_t lds_s4;
+            const uint32_t o = (roff ^ (uint32_t)(blk * 64)) + ks * 4096;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(tile + o));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(tile + o + 1024));
+            uint2 a = __builtin_bit_cast(uint2, lo), b2 = __builtin_bit_cast(uint2, hi);
+            return make_uint4(a.x, a.y, b2.x, b2.y);
+        }
+    }
+};
+
+template <int KA, int KB, class Epi>
+__global__ __launch_bounds__(256) void k_gemm_dma(GemmArgs<bf16_t, KA, KB, Epi, true, GEMM_NCH> g) {
+    extern __shared__ __align__(16) unsigned char dlds[];
+    const int id = xcd_remap(blockIdx.x, gridDim.x);
+    const int per_p = g.tiles_m * g.tiles_n;
+    const int p = id / per_p, tm = (id % per_p) / g.tiles_n, tn = id % g.tiles_n;
+    Epi epi = g.epi;
+    shift_epi(epi, p, g.e0_pstride, g.e1_pstride, g.e2_pstride);
+    const int r0 = tm * BM, c0 = tn * BN;
+    const int wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    DmaOperand<KA> A;
+    DmaOperand<KB> B;
+    A.init(reinterpret_cast<const bf16_t*>(g.a.base) + (int64_t)p * g.a_pstride, (int)g.a.ld, g.a.rows, r0, wm, false);
+    B.init(reinterpret_cast<const bf16_t*>(g.b.base) + (int64_t)p * g.b_pstride, (int)g.b.ld, g.b.rows, c0, wn, true);
+
+    float16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int nk = g.a.kdim / 32;
+    const uint32_t lbase = (uint32_t)(size_t)dlds;
+#pragma unroll
+    for (int st = 0; st < DMA_NST - 1; ++st)
+        if (st < nk) {
+            A.issue(st, lbase + st * DMA_STAGE_BYTES);
+            B.issue(st, lbase + st * DMA_STAGE_BYTES + 8192);
+        }
+    for (int kt = 0; kt < nk; ++kt) {
+        // each wave has 4 loads per stage in flight; the oldest stage is the one multiplied next
+        const int ahead = nk - 1 - kt;
+        if (ahead >= 2) wait_vm<8>();
+        else if (ahead == 1) wait_vm<4>();
+        else wait_vm<0>();
+        __syncthreads();  // stage kt has landed for every wave, and everyone is done with stage kt - 1
+        if (kt + DMA_NST - 1 < nk) {
+            const uint32_t tile = lbase + (uint32_t)((kt + DMA_NST - 1) % DMA_NST) * DMA_STAGE_BYTES;
+            A.issue(kt + DMA_NST - 1, tile);
+            B.issue(kt + DMA_NST - 1, tile + 8192);
+        }
+        const unsigned char* ta = dlds + (kt % DMA_NST) * DMA_STAGE_BYTES;
+        const unsigned char* tb = ta + 8192;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            uint4 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = A.frag(ta, i, ks);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[j] = B.frag(tb, j, ks);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(fb[j], fa[i], acc[i][j]);  // transposed tile
+        }
+    }
+    __syncthreads();
+    gemm_epilogue(epi, acc, dlds, p, tm, g.tiles_m, r0, c0, g.a.rows, g.b.rows);
 }
 
 // ---- optional event timing of the GEMM launches ------------------------------------------------
@@ -676,6 +837,36 @@ static GemmProf::Rec* prof_take(const morlax_ctx* c, int kind, double flops) {
     return r;
 }
 
+// The direct-to-LDS kernel serves bf16 GEMMs of compact operands whose contraction length is a multiple
+// of 32 and whose addresses are 16-byte aligned; everything else runs k_grouped_gemm.
+template <int KIND>
+static bool dma_operand_ok(const void* base, int64_t ld, int rows, int kdim, int64_t pstride) {
+    if ((reinterpret_cast<uintptr_t>(base) & 15) || (ld & 7) || (pstride & 7)) return false;
+    if (KIND == SRC_KCONTIG) return rows >= 1 && (int64_t)rows * ld * 2 < (int64_t(1) << 31);
+    return rows >= 8 && (rows & 7) == 0 && (64 * ld + rows) * 2 < (int64_t(1) << 31);
+}
+template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
+static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int nb, hipStream_t s) {
+    if constexpr (std::is_same<T, bf16_t>::value && FAST && (KA == SRC_KCONTIG || KA == SRC_KSTRIDED) &&
+                  (KB == SRC_KCONTIG || KB == SRC_KSTRIDED)) {
+        if (g.a.kdim < 32 || (g.a.kdim & 31)) return false;
+        if (!dma_operand_ok<KA>(g.a.base, g.a.ld, g.a.rows, g.a.kdim, g.a_pstride)) return false;
+        if (!dma_operand_ok<KB>(g.b.base, g.b.ld, g.b.rows, g.b.kdim, g.b_pstride)) return false;
+        static bool attr_set = false;
+        constexpr int lds_bytes = DMA_NST * DMA_STAGE_BYTES;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dma<KA, KB, Epi>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            attr_set = true;
+        }
+        k_gemm_dma<KA, KB, Epi><<<nb, 256, lds_bytes, s>>>(g);
+        return true;
+    } else {
+        (void)g; (void)nb; (void)s;
+        return false;
+    }
+}
+
 template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
 static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, hipStream_t s) {
     g.tiles_m = (g.a.rows + BM - 1) / BM;
@@ -683,7 +874,7 @@ static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi, FAS
     const int nb = g.tiles_m * g.tiles_n * P;
     GemmProf::Rec* r = prof_take(c, kind, 2.0 * g.a.rows * (double)g.b.rows * g.a.kdim * P);
     if (r) (void)hipEventRecord(r->a, s);
-    k_grouped_gemm<T, KA, KB, Epi, FAST, NCH><<<nb, 256, 0, s>>>(g);
+    if (!launch_dma(g, nb, s)) k_grouped_gemm<T, KA, KB, Epi, FAST, NCH><<<nb, 256, 0, s>>>(g);
     if (r) (void)hipEventRecord(r->b, s);
 }
 

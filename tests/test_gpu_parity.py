@@ -33,6 +33,15 @@ def torch():
     return t
 
 
+@pytest.fixture(autouse=True, scope="module")
+def _float32_default(torch):
+    # device buffers below are allocated with the default dtype and handed to fp32 kernels
+    prev = torch.get_default_dtype()
+    torch.set_default_dtype(torch.float32)
+    yield
+    torch.set_default_dtype(prev)
+
+
 @pytest.fixture(scope="module")
 def binding():
     from paper_2603_09237_amd import binding as b

@@ -14,7 +14,16 @@ import torch
 from oracle import morlax_oracle as orc
 from paper_2603_09237_amd import configs, inputs
 
-torch.set_default_dtype(torch.float64)
+
+
+@pytest.fixture(autouse=True, scope="module")
+def _float64_default():
+    # the autograd graphs below are float64; the default is restored so that other test modules
+    # (the GPU parity tests allocate float32 device buffers) are not affected
+    prev = torch.get_default_dtype()
+    torch.set_default_dtype(torch.float64)
+    yield
+    torch.set_default_dtype(prev)
 
 
 def tiny(**over):
