@@ -319,12 +319,18 @@ struct EpiFwd {  // h = act(z + b) and, when SAVE, act'(z); compact [M][ld] stor
     struct Out { Pack8 h, g; };
     __device__ inline void compute(int r, int c, int n, float v[8], Out& o) const {
         (void)r; (void)n;  // ld is a multiple of 16, so an octet is never cut
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] += bias[c + i];
+        compute_biased(v, o);
+    }
+    __device__ inline void compute_biased(float v[8], Out& o) const {  // v already holds z + b
         float g[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) act_pair<ACT>(v[i] + bias[c + i], v[i], g[i]);
+        for (int i = 0; i < 8; ++i) act_pair<ACT>(v[i], v[i], g[i]);
         o.h = pack8(v, (const T*)nullptr);
         if (SAVE) o.g = pack8(g, (const typename GradT<T>::type*)nullptr);
     }
+    static constexpr bool kBias = true;  // the persistent kernel stages the tile's bias slice in LDS
     __device__ inline void flush(int r, int c, int n, const Out& o) const {
         (void)n;
         put8(H + (int64_t)r * ld + c, o.h);
@@ -358,6 +364,7 @@ struct EpiDx {  // dZ_{l-1} = (dZ_l W_l) * act'(z_{l-1})
         put8(dZ + (int64_t)r * ld + c, o.d);
     }
     static constexpr bool kStage = false;  // direct 16-byte stores measured faster here
+    static constexpr bool kBias = false;
     static constexpr int kArrays = 1;
     static constexpr int kES = (int)sizeof(T);
     __device__ inline char* arr(int) const { return reinterpret_cast<char*>(dZ); }
@@ -385,6 +392,7 @@ struct EpiDw {  // dW_l(p)[o, i]
         }
     }
     static constexpr bool kStage = false;
+    static constexpr bool kBias = false;
     static constexpr int kArrays = 1;
     static constexpr int kES = 4;
     __device__ inline char* arr(int) const { return reinterpret_cast<char*>(dW); }
@@ -650,8 +658,20 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
+// wave-uniform 64-bit address held in scalar registers, whatever unit computed it
+__device__ inline uint64_t uniform_addr(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
 __device__ inline void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff),
+                 "s"(uniform_addr(sbase))
+                 : "memory");
+}
+__device__ inline void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr) {  // 4 bytes per lane
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff),
+                 "s"(uniform_addr(sbase))
                  : "memory");
 }
 template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
@@ -783,6 +803,297 @@ __global__ __launch_bounds__(256) void k_gemm_dma(GemmArgs<bf16_t, KA, KB, Epi, 
     gemm_epilogue(epi, acc, dlds, p, tm, g.tiles_m, r0, c0, g.a.rows, g.b.rows);
 }
 
+// ---- persistent bf16 grouped GEMM, 256 x 128 tiles -----------------------------------------------
+// Two workgroups per CU stay resident and walk over the tiles; a wave owns 128 x 64 outputs (4 x 2
+// blocks of 32 x 32, 128 accumulator registers), which halves the LDS bytes read per product against
+// the 64 x 64 wave tiles above.  Operand stages (A 16 KB, B 8 KB) are filled by direct-to-LDS loads
+// two contraction steps ahead, and the first two stages of a workgroup's next tile are requested
+// before the epilogue of the current one, so that their latency is covered by the epilogue's
+// arithmetic.  The layouts inside a stage follow DmaOperand; a row of a K-strided tile now has
+// ROWS / 8 chunks.
+#define PG_NST 3
+#define PG_A_BYTES 16384
+#define PG_B_BYTES 8192
+#define PG_STAGE_BYTES (PG_A_BYTES + PG_B_BYTES)
+#define PG_LDS_BYTES (PG_NST * PG_STAGE_BYTES)
+#define PG_TM 256
+#define PG_TN 128
+
+template <int KIND, int ROWS, int MBLK>
+struct DmaTile {
+    static constexpr int NI = ROWS / 64;   // DMA instructions per wave and stage
+    static constexpr int CPR = ROWS / 8;   // chunks per contraction index (K-strided layout)
+    const char* base;
+    uint32_t voff[NI];
+    int64_t kstep;
+    uint32_t roff[MBLK];  // LDS byte offset of the lane's fragment of block b, ks 0
+
+    __device__ inline void set_tile(const bf16_t* b, int ld, int rows, int t0) {
+        base = reinterpret_cast<const char*>(b);
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int j = NI * wave + i;
+            if (KIND == SRC_KCONTIG) {
+                const int row = 16 * j + lane / 4, c = (lane % 4) ^ swz_rk(row);
+                int gr = t0 + row;
+                gr = gr < rows ? gr : rows - 1;
+                voff[i] = (uint32_t)((gr * ld + 8 * c) * 2);
+            } else {
+                const int pos = 64 * j + lane, k = pos / CPR, ic = (pos % CPR) ^ (2 * (k & 3));
+                int gr = t0 + 8 * ic;
+                gr = gr < rows - 8 ? gr : rows - 8;
+                voff[i] = (uint32_t)((k * ld + gr) * 2);
+            }
+        }
+        kstep = (KIND == SRC_KCONTIG) ? 64 : (int64_t)64 * ld;
+    }
+    __device__ inline void set_lane(int wbase, bool brole) {
+        const int lane = threadIdx.x & 63, lr = lane & 31, lg = lane >> 5;
+#pragma unroll
+        for (int b = 0; b < MBLK; ++b) {
+            if (KIND == SRC_KCONTIG) {
+                const int rr = brole ? ((lr & 0x13) | ((lr & 4) << 1) | ((lr & 8) >> 1)) : lr;
+                const int row = wbase + 32 * b + rr;
+                roff[b] = (uint32_t)(row * 64 + ((lg ^ swz_rk(row)) * 16));
+            } else {
+                const int a = lane & 15, q0 = (lane >> 4) & 1, e = a >> 2, c = a & 3;
+                const int cs = brole ? (((c & 1) << 1) | (c >> 1)) : c;
+                const int col = wbase + 32 * b + 16 * q0 + 4 * cs, k = 8 * lg + e;
+                roff[b] = (uint32_t)((k * CPR + ((col >> 3) ^ (2 * (k & 3)))) * 16 + ((col >> 2) & 1) * 8);
+            }
+        }
+    }
+    __device__ inline void issue(int kt, uint32_t tile) const {
+        const char* b = base + (int64_t)kt * kstep;
+        const int wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            dma16(b, voff[i], __builtin_amdgcn_readfirstlane(tile + (uint32_t)(NI * wave + i) * 1024u));
+    }
+    __device__ inline uint4 frag(const unsigned char* tile, int blk, int ks) const {
+        if (KIND == SRC_KCONTIG) {
+            return *reinterpret_cast<const uint4*>(tile + (roff[blk] ^ (uint32_t)(ks * 32)));
+        } else {
+            typedef __attribute__((address_space(3))) short4_t lds_s4;
+            const uint32_t o = roff[blk] + ks * (16 * CPR * 16);
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(tile + o));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(tile + o + 4 * CPR * 16));
+            uint2 a = __builtin_bit_cast(uint2, lo), b2 = __builtin_bit_cast(uint2, hi);
+            return make_uint4(a.x, a.y, b2.x, b2.y);
+        }
+    }
+};
+
+// Epilogue of a 128 x 64 wave tile.  `lds_free` is LDS no load is in flight to (at least 16 KB + 1 KB).
+template <class Epi, int MB>
+__device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], unsigned char* lds_free,
+                                     const float* lds_bias, int p, int tm, int tiles_m, int r0, int c0, int rows,
+                                     int cols, int wm, int wn) {
+    static_assert(!(Epi::kStage && Epi::kColSum), "the staged stores and the column sums share LDS");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane & 31, lg = lane >> 5;
+    float cs[Epi::kColSum ? 32 : 1];
+    // staged stores: a per-wave patch of 32 rows x 128 bytes whose 16-byte chunks are XOR-swizzled by the
+    // row, written by the lanes that own the values and read back as whole 128-byte row segments
+    unsigned char* patch = lds_free + wave * 4096;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int r = r0 + wm + 32 * i + lr;
+        const int rc = r < rows ? r : rows - 1;
+        if (Epi::kStage) {
+            static_assert(!Epi::kStage || Epi::kES == 2, "staged stores are for 2-byte outputs");
+            uint4 second[4];
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int j = o >> 1, h = o & 1;
+                const int c = c0 + wn + 32 * j + 16 * h + 8 * lg;
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = acc[i][j][8 * h + u];
+                typename Epi::Out out;
+                if constexpr (Epi::kBias) {
+                    // lds_bias holds the bias of the tile's 128 columns (clamped at the matrix edge)
+                    const float4 b0 = *reinterpret_cast<const float4*>(lds_bias + wn + 32 * j + 16 * h + 8 * lg);
+                    const float4 b1 = *reinterpret_cast<const float4*>(lds_bias + wn + 32 * j + 16 * h + 8 * lg + 4);
+                    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                    v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+                    epi.compute_biased(v, out);
+                } else {
+                    epi.compute(rc, c < cols ? c : 0, 8, v, out);
+                }
+                const int cch = 4 * j + 2 * h + lg;
+                *reinterpret_cast<uint4*>(patch + lr * 128 + ((cch ^ (lr & 7)) * 16)) = Epi::pk(out, 0).lo;
+                if (Epi::kArrays == 2) second[o] = Epi::pk(out, 1).lo;
+            }
+#pragma unroll
+            for (int a = 0; a < Epi::kArrays; ++a) {
+                if (a == 1) {
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        const int cch = 4 * (o >> 1) + 2 * (o & 1) + lg;
+                        *reinterpret_cast<uint4*>(patch + lr * 128 + ((cch ^ (lr & 7)) * 16)) = second[o];
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                char* base = epi.arr(a);
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int q = it * 64 + lane, prow = q >> 3, pc = q & 7;
+                    const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
+                    const int gr = r0 + wm + 32 * i + prow, gc = c0 + wn + pc * 8;
+                    if (gr < rows && gc < cols) *reinterpret_cast<uint4*>(base + ((int64_t)gr * epi.ld + gc) * 2) = u;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        } else {
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                typename Epi::Out outs[2];
+#pragma unroll
+                for (int o = 0; o < 2; ++o) {
+                    const int c = c0 + wn + 32 * jb + 16 * o + 8 * lg;
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = acc[i][jb][8 * o + u];
+                    const bool ok = (r < rows) && (c < cols);
+                    epi.compute(rc, c < cols ? c : 0, 8, v, outs[o]);
+                    if (Epi::kColSum) {
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int t = Epi::kColSum ? (16 * jb + 8 * o + u) : 0;
+                            cs[t] = (i == 0 ? 0.f : cs[t]) + (ok ? v[u] : 0.f);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int o = 0; o < 2; ++o) {
+                    const int c = c0 + wn + 32 * jb + 16 * o + 8 * lg;
+                    if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[o]);
+                }
+            }
+        }
+    }
+    if (Epi::kColSum) {
+        // as in gemm_epilogue, over the 128 rows of the wave tile and then over the two waves of a column half
+        fold_slots<16>(cs, lr);
+        fold_slots<8>(cs, lr);
+        fold_slots<4>(cs, lr);
+        fold_slots<2>(cs, lr);
+        fold_slots<1>(cs, lr);
+        float* red = reinterpret_cast<float*>(lds_free);
+        {
+            const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
+            red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
+        }
+        __syncthreads();
+        if (threadIdx.x < 128) {
+            const int wsel = threadIdx.x >> 6, col = threadIdx.x & 63;
+            const float v = red[wsel * 64 + col] + red[(2 + wsel) * 64 + col];
+            if (c0 + threadIdx.x < cols) epi.part[((int64_t)p * tiles_m + tm) * epi.ld + c0 + threadIdx.x] = v;
+        }
+    }
+}
+
+template <int KA, int KB, class Epi>
+__global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, Epi, true, GEMM_NCH> g, int n_tiles) {
+    extern __shared__ __align__(16) unsigned char dlds[];
+    const int wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 64;
+    const int per_p = g.tiles_m * g.tiles_n;
+    const int nk = g.a.kdim / 32;
+    const uint32_t lbase = (uint32_t)(size_t)dlds;
+    DmaTile<KA, PG_TM, 4> A;
+    DmaTile<KB, PG_TN, 2> B;
+    A.set_lane(wm, false);
+    B.set_lane(wn, true);
+
+    // tile ids of this workgroup: blockIdx.x, + gridDim.x, ...; the XCD remap keeps the tiles that the
+    // workgroups of one XCD work on at the same time next to each other (same preference, same W(p))
+    auto locate = [&](int vid, int& p, int& tm, int& tn) {
+        const int id = xcd_remap(vid, n_tiles);
+        p = id / per_p;
+        tm = (id % per_p) / g.tiles_n;
+        tn = id % g.tiles_n;
+    };
+    int bslot = 0;
+    auto request = [&](int p, int tm, int tn) {  // first stages of a tile (and its bias slice)
+        if constexpr (Epi::kBias) {
+            bslot ^= 1;
+            if (wave < 2) {
+                int c = tn * PG_TN + 64 * wave + (threadIdx.x & 63);
+                c = c < g.b.rows ? c : g.b.rows - 1;
+                dma4(g.epi.bias + (int64_t)p * g.e0_pstride, (uint32_t)c * 4u,
+                     __builtin_amdgcn_readfirstlane(lbase + PG_LDS_BYTES + (uint32_t)(bslot * 512 + wave * 256)));
+            }
+        }
+        A.set_tile(reinterpret_cast<const bf16_t*>(g.a.base) + (int64_t)p * g.a_pstride, (int)g.a.ld, g.a.rows, tm * PG_TM);
+        B.set_tile(reinterpret_cast<const bf16_t*>(g.b.base) + (int64_t)p * g.b_pstride, (int)g.b.ld, g.b.rows, tn * PG_TN);
+#pragma unroll
+        for (int st = 0; st < PG_NST - 1; ++st)
+            if (st < nk) {
+                A.issue(st, lbase + st * PG_STAGE_BYTES);
+                B.issue(st, lbase + st * PG_STAGE_BYTES + PG_A_BYTES);
+            }
+    };
+
+    int vid = blockIdx.x;
+    if (vid >= n_tiles) return;
+    int p, tm, tn;
+    locate(vid, p, tm, tn);
+    request(p, tm, tn);
+    for (;;) {
+        float16_t acc[4][2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int kt = 0; kt < nk; ++kt) {
+            // a wave has 6 loads per stage in flight.  At the first step of a tile the stores of the
+            // previous epilogue may still be counted as well, so everything is waited for.
+            if (kt == 0 || kt == nk - 1) wait_vm<0>();
+            else wait_vm<6>();
+            __syncthreads();  // stage kt is complete, and stage kt - 1 (or the last epilogue's patch) is free
+            if (kt + PG_NST - 1 < nk) {
+                const uint32_t tile = lbase + (uint32_t)((kt + PG_NST - 1) % PG_NST) * PG_STAGE_BYTES;
+                A.issue(kt + PG_NST - 1, tile);
+                B.issue(kt + PG_NST - 1, tile + PG_A_BYTES);
+            }
+            const unsigned char* ta = dlds + (kt % PG_NST) * PG_STAGE_BYTES;
+            const unsigned char* tb = ta + PG_A_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                uint4 fa[4], fb[2];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) fb[j] = B.frag(tb, j, ks);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) fa[i] = A.frag(ta, i, ks);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(fb[j], fa[i], acc[i][j]);  // transposed tile
+            }
+        }
+        __syncthreads();  // every wave is done with the stages
+        const int pc = p, tmc = tm, tnc = tn;
+        const float* lds_bias = reinterpret_cast<const float*>(dlds + PG_LDS_BYTES + bslot * 512);
+        vid += gridDim.x;
+        const bool more = vid < n_tiles;
+        if (more) {
+            locate(vid, p, tm, tn);
+            request(p, tm, tn);  // stages 0 and 1; the epilogue below stages its stores in the third
+        }
+        Epi epi = g.epi;
+        shift_epi(epi, pc, g.e0_pstride, g.e1_pstride, g.e2_pstride);
+        tile_epilogue<Epi, 4>(epi, acc, dlds + (PG_NST - 1) * PG_STAGE_BYTES, lds_bias, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * PG_TN,
+                              g.a.rows, g.b.rows, wm, wn);
+        if (!more) break;
+    }
+}
+
 // ---- optional event timing of the GEMM launches ------------------------------------------------
 #include <vector>
 struct GemmProf {
@@ -845,13 +1156,43 @@ static bool dma_operand_ok(const void* base, int64_t ld, int rows, int kdim, int
     if (KIND == SRC_KCONTIG) return rows >= 1 && (int64_t)rows * ld * 2 < (int64_t(1) << 31);
     return rows >= 8 && (rows & 7) == 0 && (64 * ld + rows) * 2 < (int64_t(1) << 31);
 }
+static int resident_slots() {  // workgroups of the persistent kernel: two per CU
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        n = 2 * cus;
+    }
+    return n;
+}
+
 template <typename T, int KA, int KB, class Epi, bool FAST, int NCH>
-static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int nb, hipStream_t s) {
+static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, int nb, hipStream_t s) {
     if constexpr (std::is_same<T, bf16_t>::value && FAST && (KA == SRC_KCONTIG || KA == SRC_KSTRIDED) &&
                   (KB == SRC_KCONTIG || KB == SRC_KSTRIDED)) {
         if (g.a.kdim < 32 || (g.a.kdim & 31)) return false;
         if (!dma_operand_ok<KA>(g.a.base, g.a.ld, g.a.rows, g.a.kdim, g.a_pstride)) return false;
         if (!dma_operand_ok<KB>(g.b.base, g.b.ld, g.b.rows, g.b.kdim, g.b_pstride)) return false;
+        // large problems: persistent 256 x 128 tiles, as soon as they fill the resident workgroups
+        const int ptm = (g.a.rows + PG_TM - 1) / PG_TM, ptn = (g.b.rows + PG_TN - 1) / PG_TN;
+        const int pnt = ptm * ptn * P;
+        static const bool pers_on = !getenv("MORLAX_NO_PERS");
+        if (pers_on && pnt >= resident_slots() && g.a.rows >= 64) {
+            static bool pattr_set = false;
+            constexpr int plds = PG_LDS_BYTES + 1024;
+            if (!pattr_set) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_pers<KA, KB, Epi>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, plds);
+                pattr_set = true;
+            }
+            g.tiles_m = ptm;
+            g.tiles_n = ptn;
+            const int grid = pnt < resident_slots() ? pnt : resident_slots();
+            k_gemm_pers<KA, KB, Epi><<<grid, 256, plds, s>>>(g, pnt);
+            return true;
+        }
         static bool attr_set = false;
         constexpr int lds_bytes = DMA_NST * DMA_STAGE_BYTES;
         if (!attr_set) {
@@ -874,7 +1215,7 @@ static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi, FAS
     const int nb = g.tiles_m * g.tiles_n * P;
     GemmProf::Rec* r = prof_take(c, kind, 2.0 * g.a.rows * (double)g.b.rows * g.a.kdim * P);
     if (r) (void)hipEventRecord(r->a, s);
-    if (!launch_dma(g, nb, s)) k_grouped_gemm<T, KA, KB, Epi, FAST, NCH><<<nb, 256, 0, s>>>(g);
+    if (!launch_dma(g, P, nb, s)) k_grouped_gemm<T, KA, KB, Epi, FAST, NCH><<<nb, 256, 0, s>>>(g);
     if (r) (void)hipEventRecord(r->b, s);
 }
 
@@ -1294,7 +1635,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             h.epi.G = Gbuf(l - 1); h.epi.dZ = dZbuf(l - 1); h.epi.ld = W; h.epi.part = part;
             h.e0_pstride = (int64_t)M * W; h.e1_pstride = 0; h.e2_pstride = 0;
             run_gemm(c, 2, h, P, s);
-            n_part = (M + BM - 1) / BM;
+            n_part = h.tiles_m;  // row tiles of the kernel that ran (128 or 256 rows)
         } else {
             auto launch = [&](auto fast) {
                 constexpr bool F = decltype(fast)::value;
