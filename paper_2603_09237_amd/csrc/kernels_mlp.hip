@@ -293,6 +293,14 @@ __device__ inline void get8(const float* src, float v[8]) {
     const float4 a = reinterpret_cast<const float4*>(src)[0], b = reinterpret_cast<const float4*>(src)[1];
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
+__device__ inline void unpack8(const uint4& u, float v[8]) {  // eight fixed-point derivatives
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = (float)(w[i] & 0xffffu) * GFIX_STEP - 0.125f;
+        v[2 * i + 1] = (float)(w[i] >> 16) * GFIX_STEP - 0.125f;
+    }
+}
 __device__ inline void get8(const gfix16_t* src, float v[8]) {
     const uint4 u = *reinterpret_cast<const uint4*>(src);
     const uint32_t w[4] = {u.x, u.y, u.z, u.w};
@@ -331,6 +339,7 @@ struct EpiFwd {  // h = act(z + b) and, when SAVE, act'(z); compact [M][ld] stor
         if (SAVE) o.g = pack8(g, (const typename GradT<T>::type*)nullptr);
     }
     static constexpr bool kBias = true;  // the persistent kernel stages the tile's bias slice in LDS
+    static constexpr bool kPrefetch = false;
     __device__ inline void flush(int r, int c, int n, const Out& o) const {
         (void)n;
         put8(H + (int64_t)r * ld + c, o.h);
@@ -363,6 +372,16 @@ struct EpiDx {  // dZ_{l-1} = (dZ_l W_l) * act'(z_{l-1})
         (void)n;
         put8(dZ + (int64_t)r * ld + c, o.d);
     }
+    // the persistent kernel (bf16) fetches the derivatives of a 32-row block one block ahead of their use
+    static constexpr bool kPrefetch = std::is_same<T, bf16_t>::value;
+    __device__ inline uint4 fetch(int r, int c) const { return *reinterpret_cast<const uint4*>(G + (int64_t)r * ld + c); }
+    __device__ inline void compute_fetched(const uint4& gq, float v[8], Out& o) const {
+        float g[8];
+        unpack8(gq, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] *= g[i];
+        o.d = pack8(v, (const T*)nullptr);
+    }
     static constexpr bool kStage = false;  // direct 16-byte stores measured faster here
     static constexpr bool kBias = false;
     static constexpr int kArrays = 1;
@@ -393,6 +412,7 @@ struct EpiDw {  // dW_l(p)[o, i]
     }
     static constexpr bool kStage = false;
     static constexpr bool kBias = false;
+    static constexpr bool kPrefetch = false;
     static constexpr int kArrays = 1;
     static constexpr int kES = 4;
     __device__ inline char* arr(int) const { return reinterpret_cast<char*>(dW); }
@@ -650,7 +670,7 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
 //   SRC_KCONTIG  operand, stage = 128 rows x 4 chunks (8 contraction indices each): chunk (r, c) sits at
 //                position 4 r + (c ^ swz(r)); fragments are read with one 16-byte LDS read.
 //   SRC_KSTRIDED operand (global [k][row]), stage = 32 k x 16 chunks (8 rows each): chunk (k, ic) sits at
-//                position 16 k + (ic ^ 2 (k & 3)); fragments are read with two transposing 8-byte reads,
+//                position 16 k + (ic ^ 4 (k & 3)); fragments are read with two transposing 8-byte reads,
 //                each of which hands lane b of a 16-lane group the elements [k0 .. k0+3][row b] of the
 //                4 x 16 block whose 64-bit words the lanes 4 e + c (k = k0 + e, rows 4 c .. 4 c + 3) address.
 #define DMA_NST 4
@@ -676,7 +696,11 @@ __device__ inline void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr)
 }
 template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-__device__ inline int swz_rk(int r) { return ((r >> 1) & 1) | ((((r >> 2) ^ (r >> 3)) & 1) << 1); }
+// The LDS has 64 banks of 4 bytes: it serves 16 lanes of a 16-byte read, or 32 lanes of an 8-byte read,
+// per cycle, and the lanes of such a group must touch distinct slots modulo 256 bytes.  With 64-byte rows,
+// rows r .. r+3 fill one 256-byte window, so the chunk index is XORed with bits 2, 3 of the row; the
+// K-strided tiles XOR bits 2, 3 of the chunk index with the contraction index modulo 4.
+__device__ inline int swz_rk(int r) { return (r >> 2) & 3; }
 
 template <int KIND>
 struct DmaOperand {
@@ -697,7 +721,7 @@ struct DmaOperand {
                 gr = gr < rows ? gr : rows - 1;
                 voff[i] = (uint32_t)((gr * ld + 8 * c) * 2);
             } else {
-                const int k = 4 * j + lane / 16, ic = (lane % 16) ^ (2 * (k & 3));
+                const int k = 4 * j + lane / 16, ic = (lane % 16) ^ (4 * (k & 3));
                 int gr = t0 + 8 * ic;
                 gr = gr < rows - 8 ? gr : rows - 8;
                 voff[i] = (uint32_t)((k * ld + gr) * 2);
@@ -713,7 +737,7 @@ struct DmaOperand {
             const int a = lane & 15, q0 = (lane >> 4) & 1, e = a >> 2, c = a & 3;
             const int cs = brole ? (((c & 1) << 1) | (c >> 1)) : c;
             const int col = wbase + 16 * q0 + 4 * cs, k = 8 * lg + e;
-            roff = (uint32_t)((k * 16 + ((col >> 3) ^ (2 * (k & 3)))) * 16 + ((col >> 2) & 1) * 8);
+            roff = (uint32_t)((k * 16 + ((col >> 3) ^ (4 * (k & 3)))) * 16 + ((col >> 2) & 1) * 8);
         }
     }
     // issue the loads of contraction step kt into the stage tile at LDS address `tile`
@@ -840,7 +864,7 @@ struct DmaTile {
                 gr = gr < rows ? gr : rows - 1;
                 voff[i] = (uint32_t)((gr * ld + 8 * c) * 2);
             } else {
-                const int pos = 64 * j + lane, k = pos / CPR, ic = (pos % CPR) ^ (2 * (k & 3));
+                const int pos = 64 * j + lane, k = pos / CPR, ic = (pos % CPR) ^ (4 * (k & 3));
                 int gr = t0 + 8 * ic;
                 gr = gr < rows - 8 ? gr : rows - 8;
                 voff[i] = (uint32_t)((k * ld + gr) * 2);
@@ -860,7 +884,7 @@ struct DmaTile {
                 const int a = lane & 15, q0 = (lane >> 4) & 1, e = a >> 2, c = a & 3;
                 const int cs = brole ? (((c & 1) << 1) | (c >> 1)) : c;
                 const int col = wbase + 32 * b + 16 * q0 + 4 * cs, k = 8 * lg + e;
-                roff[b] = (uint32_t)((k * CPR + ((col >> 3) ^ (2 * (k & 3)))) * 16 + ((col >> 2) & 1) * 8);
+                roff[b] = (uint32_t)((k * CPR + ((col >> 3) ^ (4 * (k & 3)))) * 16 + ((col >> 2) & 1) * 8);
             }
         }
     }
@@ -888,8 +912,8 @@ struct DmaTile {
 // Epilogue of a 128 x 64 wave tile.  `lds_free` is LDS no load is in flight to (at least 16 KB + 1 KB).
 template <class Epi, int MB>
 __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], unsigned char* lds_free,
-                                     const float* lds_bias, int p, int tm, int tiles_m, int r0, int c0, int rows,
-                                     int cols, int wm, int wn) {
+                                     const float* lds_bias, const uint4 (&first)[4], int p, int tm, int tiles_m,
+                                     int r0, int c0, int rows, int cols, int wm, int wn) {
     static_assert(!(Epi::kStage && Epi::kColSum), "the staged stores and the column sums share LDS");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane & 31, lg = lane >> 5;
@@ -897,6 +921,9 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
     // staged stores: a per-wave patch of 32 rows x 128 bytes whose 16-byte chunks are XOR-swizzled by the
     // row, written by the lanes that own the values and read back as whole 128-byte row segments
     unsigned char* patch = lds_free + wave * 4096;
+    uint4 cur[4];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) cur[o] = first[o];
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
         const int r = r0 + wm + 32 * i + lr;
@@ -948,6 +975,19 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
             }
             __builtin_amdgcn_wave_barrier();
         } else {
+            // `first` holds the prefetched operands of block 0 (four octets per lane); those of block
+            // i + 1 are requested before block i is worked on
+            uint4 nxt[4];
+            if constexpr (Epi::kPrefetch) {
+                if (i + 1 < MB) {
+                    const int rn = r0 + wm + 32 * (i + 1) + lr, rnc = rn < rows ? rn : rows - 1;
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        const int c = c0 + wn + 16 * o + 8 * lg;
+                        nxt[o] = epi.fetch(rnc, c < cols ? c : 0);
+                    }
+                }
+            }
 #pragma unroll
             for (int jb = 0; jb < 2; ++jb) {
                 typename Epi::Out outs[2];
@@ -958,7 +998,8 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
 #pragma unroll
                     for (int u = 0; u < 8; ++u) v[u] = acc[i][jb][8 * o + u];
                     const bool ok = (r < rows) && (c < cols);
-                    epi.compute(rc, c < cols ? c : 0, 8, v, outs[o]);
+                    if constexpr (Epi::kPrefetch) epi.compute_fetched(cur[2 * jb + o], v, outs[o]);
+                    else epi.compute(rc, c < cols ? c : 0, 8, v, outs[o]);
                     if (Epi::kColSum) {
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
@@ -972,6 +1013,10 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
                     const int c = c0 + wn + 32 * jb + 16 * o + 8 * lg;
                     if (r < rows && c < cols) epi.flush(r, c, (cols - c < 8) ? (cols - c) : 8, outs[o]);
                 }
+            }
+            if constexpr (Epi::kPrefetch) {
+#pragma unroll
+                for (int o = 0; o < 4; ++o) cur[o] = nxt[o];
             }
         }
     }
@@ -1064,31 +1109,48 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, E
             }
             const unsigned char* ta = dlds + (kt % PG_NST) * PG_STAGE_BYTES;
             const unsigned char* tb = ta + PG_A_BYTES;
+            // all fragments of the stage are requested before the first product, so that one LDS latency is
+            // exposed per step instead of one per pair of products
+            uint4 fa[2][4], fb[2][2];
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                uint4 fa[4], fb[2];
 #pragma unroll
-                for (int j = 0; j < 2; ++j) fb[j] = B.frag(tb, j, ks);
+                for (int j = 0; j < 2; ++j) fb[ks][j] = B.frag(tb, j, ks);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) fa[i] = A.frag(ta, i, ks);
+                for (int i = 0; i < 4; ++i) fa[ks][i] = A.frag(ta, i, ks);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(fb[j], fa[i], acc[i][j]);  // transposed tile
-            }
+                    for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(fb[ks][j], fa[ks][i], acc[i][j]);  // transposed tile
+            constexpr int kReads = ((KA == SRC_KCONTIG) ? 8 : 16) + ((KB == SRC_KCONTIG) ? 4 : 8);
+            __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);  // LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);      // MFMAs
         }
         __syncthreads();  // every wave is done with the stages
         const int pc = p, tmc = tm, tnc = tn;
         const float* lds_bias = reinterpret_cast<const float*>(dlds + PG_LDS_BYTES + bslot * 512);
+        Epi epi = g.epi;
+        shift_epi(epi, pc, g.e0_pstride, g.e1_pstride, g.e2_pstride);
+        uint4 first[4] = {};
+        if constexpr (Epi::kPrefetch) {
+            // ahead of the next tile's operand loads, which would otherwise be returned first
+            const int r = tmc * PG_TM + wm + (threadIdx.x & 31), rc = r < g.a.rows ? r : g.a.rows - 1;
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int c = tnc * PG_TN + wn + 16 * o + 8 * ((threadIdx.x & 63) >> 5);
+                first[o] = epi.fetch(rc, c < g.b.rows ? c : 0);
+            }
+        }
         vid += gridDim.x;
         const bool more = vid < n_tiles;
         if (more) {
             locate(vid, p, tm, tn);
             request(p, tm, tn);  // stages 0 and 1; the epilogue below stages its stores in the third
         }
-        Epi epi = g.epi;
-        shift_epi(epi, pc, g.e0_pstride, g.e1_pstride, g.e2_pstride);
-        tile_epilogue<Epi, 4>(epi, acc, dlds + (PG_NST - 1) * PG_STAGE_BYTES, lds_bias, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * PG_TN,
+        tile_epilogue<Epi, 4>(epi, acc, dlds + (PG_NST - 1) * PG_STAGE_BYTES, lds_bias, first, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * PG_TN,
                               g.a.rows, g.b.rows, wm, wn);
         if (!more) break;
     }
