@@ -22,13 +22,19 @@ sys.path.insert(0, ROOT)
 
 # MI355X published dense peaks used for the roofline fractions
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+# grouped-GEMM launch kinds -> kernel that serves them (bf16 at full size: the persistent direct-to-LDS
+# kernel; small or fp32 problems: k_gemm_dma / k_grouped_gemm)
 KERNEL_OF_KIND = {
-    "fwd_first": "k_grouped_gemm<T, x rows, W0(p)> forward, first layer",
-    "fwd_hidden": "k_grouped_gemm<T, SRC_KCONTIG, SRC_KCONTIG, EpiFwd> forward, W x W layers",
-    "dx_hidden": "k_grouped_gemm<T, SRC_KCONTIG, SRC_KSTRIDED, EpiDx> dX, W x W layers",
-    "dw_hidden": "k_grouped_gemm<T, SRC_KSTRIDED, SRC_KSTRIDED, EpiDw> dW, W x W layers",
-    "dw_first": "k_grouped_gemm<T, SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw> dW, first layer",
+    "fwd_first": "k_grouped_gemm<x rows, W0(p), EpiFwd> forward, first layer",
+    "fwd_hidden": "k_gemm_pers<SRC_KCONTIG, SRC_KCONTIG, EpiFwd> forward, W x W layers (rollout + update)",
+    "dx_hidden": "k_gemm_pers<SRC_KCONTIG, SRC_KSTRIDED, EpiDx> dX, W x W layers",
+    "dw_hidden": "k_gemm_pers<SRC_KSTRIDED, SRC_KSTRIDED, EpiDw> dW, W x W layers",
+    "dw_first": "k_grouped_gemm<SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw> dW, first layer",
 }
+
+# HBM bytes per launch of a GEMM launch kind, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script scaled by
+# a copy of known size (profiles/grouped_gemm_cfg5_hbm_traffic.txt); workloads without such a run report null
+MEASURED_TRAFFIC_BYTES = {("cfg5-largest-K6-P128-N16384-T64-4x512-silu-bf16-4mbx2ep", "fwd_hidden"): 1073.3e6}
 
 
 def cpu_baseline(cfg_full):
@@ -66,6 +72,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (collectives and sharding are not part of it); "
@@ -87,6 +95,12 @@ def main():
     for _ in range(a.warmup):
         st.run()
     torch.cuda.synchronize()
+    if a.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     st.ctx.profile_begin()
     t0 = time.perf_counter()
@@ -116,7 +130,7 @@ def main():
                    "minibatches": cfg.minibatches, "epochs": cfg.epochs, "env_steps_per_step": env_steps,
                    "optimizer_step": "not included"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, kind)),
                      "kernel": KERNEL_OF_KIND[kind], "launches_per_step": launches / a.steps,
                      "avg_launch_ms": ms / max(launches, 1), "flop_per_launch": flops / max(launches, 1),
                      "all_gemm_ms_per_step": gemm_ms / a.steps,
