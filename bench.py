@@ -72,6 +72,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="1 (default): every launch on one stream, so that the per-kernel durations behind `roofline` are "
+                         "those of kernels running alone; 2: actor and critic chains on their own HIP streams (faster "
+                         "step, but concurrent kernels stretch each other's durations)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")
     a = ap.parse_args()
@@ -89,7 +93,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     cfg = CONFIGS[a.config]
-    st = UpdateStep(cfg)
+    st = UpdateStep(cfg, two_streams=(a.streams == 2))
     st.load_inputs(inputs.make_all(cfg))
     torch.cuda.synchronize()
     for _ in range(a.warmup):

@@ -16,7 +16,7 @@ from .configs import Config, WDTYPE_BF16
 
 
 class UpdateStep:
-    def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False):
+    def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False, two_streams: bool = False):
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -62,7 +62,12 @@ class UpdateStep:
                         for b in range(c.minibatches)]
         self.saved = {net: torch.empty(ctx.saved_bytes(net, self.mb_rows[0]), dtype=torch.uint8, device=self.dev)
                       for net in (ACTOR, CRITIC)}
-        self.ws = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device=self.dev)
+        # one workspace and one stream per network family: the actor and critic chains are independent
+        # between the loss (which needs both outputs) and the end of the minibatch
+        self.wsn = {net: torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device=self.dev)
+                    for net in (ACTOR, CRITIC)}
+        self.ws = self.wsn[ACTOR]
+        self.streams = {net: torch.cuda.Stream(device=self.dev) for net in (ACTOR, CRITIC)} if two_streams else None
         self.full_T = (0, T, 0, c.n_g)
         self.full_T1 = (0, T + 1, 0, c.n_g)
         self.logsig_off = ctx.theta_vec_len(ACTOR) - A
@@ -76,35 +81,58 @@ class UpdateStep:
         put(self.hp[ACTOR], d["hparams_actor"]); put(self.hp[CRITIC], d["hparams_critic"])
         t.cuda.synchronize()
 
+    def _per_net(self, fn):
+        """Run fn(net, ws) for the actor and the critic, on their own streams when enabled; joins before returning."""
+        t = self.torch
+        if self.streams is None:
+            for net in (ACTOR, CRITIC):
+                fn(net, self.wsn[net])
+            return
+        main = t.cuda.current_stream()
+        for net in (ACTOR, CRITIC):
+            st = self.streams[net]
+            st.wait_stream(main)
+            with t.cuda.stream(st):
+                fn(net, self.wsn[net])
+        for net in (ACTOR, CRITIC):
+            main.wait_stream(self.streams[net])
+
     def rollout(self):
         c, ctx = self.cfg, self.ctx
-        for net in (ACTOR, CRITIC):
-            ctx.hypernet_fwd(net, self.hp_old[net], self.w, self.theta_mat[net], self.theta_vec[net], self.ws)
-        ctx.policy_fwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, self.full_T, self.mu_old,
-                       eps=self.eps, act=self.act, logp=self.logp_old, saved=None, ws=self.ws)
-        ctx.policy_fwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, self.full_T1, self.v_roll,
-                       saved=None, ws=self.ws)
+
+        def fwd(net, ws):
+            ctx.hypernet_fwd(net, self.hp_old[net], self.w, self.theta_mat[net], self.theta_vec[net], ws)
+            if net == ACTOR:
+                ctx.policy_fwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, self.full_T, self.mu_old,
+                               eps=self.eps, act=self.act, logp=self.logp_old, saved=None, ws=ws)
+            else:
+                ctx.policy_fwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, self.full_T1,
+                               self.v_roll, saved=None, ws=ws)
+
+        self._per_net(fwd)
         ctx.vec_gae(self.rewards, self.v_roll, self.dones, self.w, c.gamma, c.lam, self.adv_vec, self.vtarg,
                     self.adv_s)
 
     def minibatch(self, rows):
         c, ctx = self.cfg, self.ctx
-        for net in (ACTOR, CRITIC):
-            ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], self.ws)
-        ctx.policy_fwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, rows, self.mu,
-                       saved=self.saved[ACTOR], ws=self.ws)
-        ctx.policy_fwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, rows, self.v,
-                       saved=self.saved[CRITIC], ws=self.ws)
+        out = {ACTOR: self.mu, CRITIC: self.v}
+        dout = {ACTOR: self.dmu, CRITIC: self.dv}
+
+        def fwd(net, ws):
+            ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], ws)
+            ctx.policy_fwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, out[net],
+                           saved=self.saved[net], ws=ws)
+
+        def bwd(net, ws):
+            ctx.policy_bwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, self.saved[net], dout[net],
+                           self.dlogsig if net == ACTOR else None, self.dtheta_mat[net], self.dtheta_vec[net], ws)
+            ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net], self.dhp[net], ws)
+
+        self._per_net(fwd)
         logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
         ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, self.adv_s,
                           self.v, self.vtarg, c.clip_eps, 1, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
-        ctx.policy_bwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, rows, self.saved[ACTOR],
-                       self.dmu, self.dlogsig, self.dtheta_mat[ACTOR], self.dtheta_vec[ACTOR], self.ws)
-        ctx.policy_bwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, rows, self.saved[CRITIC],
-                       self.dv, None, self.dtheta_mat[CRITIC], self.dtheta_vec[CRITIC], self.ws)
-        for net in (ACTOR, CRITIC):
-            ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net], self.dhp[net],
-                             self.ws)
+        self._per_net(bwd)
 
     def run(self, on_minibatch=None):
         """One whole update step.  `on_minibatch(e, b)` (optional) is called after each minibatch."""
