@@ -4,8 +4,10 @@
 #include "morlax_internal.h"
 #include "numeric.h"
 
-#define QW 128  // stacked-affine rows per wave of the df partial kernel
-#define DAB_COLS 512  // columns of dW one block of the fused dA/dB kernel walks
+#define QW 64  // stacked-affine rows per wave of the df partial kernel
+#define DAB_COLS 128  // columns of dW one block of the fused dA/dB kernel walks
+#define DAB_NCT (DAB_COLS / 64)
+#define DAB_MAX_CS (2048 / DAB_COLS)  // column runs of the widest layer
 
 struct HyperWs {
     float *h1, *f, *fac, *dfac, *df_part, *df, *dz2, *dz1, *vecs, *da_part;
@@ -237,13 +239,13 @@ __global__ __launch_bounds__(256) void k_hyper_dbase(NetDev nd, const float* __r
 
 // Fused dA / dB on fp32 MFMA, one pass over dW:
 //   dA_l(p)[o, k] = sum_i dW_l(p)[o, i] B_l(p)[k, i],   dB_l(p)[k, i] = sum_o A_l(p)[o, k] dW_l(p)[o, i].
-// A block owns (p, layer, a run of <= 512 columns).  It walks the 64 x 64 tiles of dW row block by row
+// A block owns (p, layer, a run of <= DAB_COLS columns).  It walks the 64 x 64 tiles of dW row block by row
 // block: wave w multiplies rows 16 w .. of the tile by B^T (dA, finished after the columns of a row block)
 // and A^T by columns 16 w .. of the tile (dB, accumulated over all row blocks in registers).
 struct DabWork {
     int32_t n;
-    int16_t layer[4 * MORLAX_MAX_LAYERS];
-    int16_t cs[4 * MORLAX_MAX_LAYERS];
+    int16_t layer[DAB_MAX_CS * MORLAX_MAX_LAYERS];
+    int16_t cs[DAB_MAX_CS * MORLAX_MAX_LAYERS];
 };
 
 template <int RT>
@@ -268,9 +270,9 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
     float* dBp = dfac + (int64_t)p * nd.fac_len + L.fac_b;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ln = lane & 15, kg = lane >> 4;
     const bool vec = (L.d_in % 4 == 0);
-    float4_t accB[8][RT];
+    float4_t accB[DAB_NCT][RT];
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct)
+    for (int ct = 0; ct < DAB_NCT; ++ct)
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) accB[ct][rt] = float4_t{0.f, 0.f, 0.f, 0.f};
     // The tiles are walked row block by row block; the next tile of dW is fetched into registers while the
@@ -309,7 +311,7 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) accA[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ct = 0; ct < 8; ++ct) {
+        for (int ct = 0; ct < DAB_NCT; ++ct) {
             if (ct < nct) {
                 const int i0 = c_lo + ct * 64;
                 __syncthreads();
@@ -352,7 +354,7 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
     }
     // dB tiles: lane holds column i of factor rows 16 rt + 4 kg + e
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct)
+    for (int ct = 0; ct < DAB_NCT; ++ct)
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -398,7 +400,21 @@ __global__ __launch_bounds__(256) void k_hyper_dM(AffineTable at, const float* _
     const float* src = (q < fac_len) ? (dfac + q) : (dvec + (q - fac_len));
     const int64_t stride = (q < fac_len) ? fac_len : vec_len;
     if (F == 32) {
-        for (int p = 0; p < P; ++p) {
+        // eight preferences per batch: their (strided, independent) loads are in flight together
+        int p = 0;
+        for (; p + 8 <= P; p += 8) {
+            float g[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) g[u] = src[(int64_t)(p + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float* fp = f + (int64_t)(p + u) * 32;
+                dc += g[u];
+#pragma unroll
+                for (int j = 0; j < 32; ++j) acc[j] += g[u] * fp[j];
+            }
+        }
+        for (; p < P; ++p) {
             const float g = src[(int64_t)p * stride];
             const float* fp = f + (int64_t)p * 32;
             dc += g;
@@ -504,8 +520,17 @@ __global__ __launch_bounds__(256) void k_hyper_df_final(const float* __restrict_
     const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int i = blockIdx.x * 64 + o;
     float a = 0.f;
-    if (i < PF)
-        for (int c = g; c < n_chunk; c += 4) a += part[(int64_t)c * PF + i];
+    if (i < PF) {
+        int c = g;
+        for (; c + 28 < n_chunk; c += 32) {  // eight chunks of this group per batch, loads in flight together
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(c + 4 * u) * PF + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += v[u];
+        }
+        for (; c < n_chunk; c += 4) a += part[(int64_t)c * PF + i];
+    }
     red[g][o] = a;
     __syncthreads();
     if (g == 0 && i < PF) {
@@ -524,14 +549,30 @@ __global__ __launch_bounds__(256) void k_hyper_trunk_bwd_a(const float* __restri
     if (idx < F * F) {
         const int j = idx / F, i = idx % F;
         float a = 0.f;
-        for (int p = 0; p < P; ++p) a += dz2[p * F + j] * h1[p * F + i];
+        int p = 0;
+        for (; p + 8 <= P; p += 8) {
+            float x[8], y[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { x[u] = dz2[(p + u) * F + j]; y[u] = h1[(p + u) * F + i]; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += x[u] * y[u];
+        }
+        for (; p < P; ++p) a += dz2[p * F + j] * h1[p * F + i];
         dhp[o_wh2 + idx] = a;
         return;
     }
     idx -= F * F;
     if (idx < F) {
         float a = 0.f;
-        for (int p = 0; p < P; ++p) a += dz2[p * F + idx];
+        int p = 0;
+        for (; p + 8 <= P; p += 8) {
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = dz2[(p + u) * F + idx];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += x[u];
+        }
+        for (; p < P; ++p) a += dz2[p * F + idx];
         dhp[o_bh2 + idx] = a;
         return;
     }
@@ -553,14 +594,30 @@ __global__ __launch_bounds__(256) void k_hyper_trunk_bwd_b(const float* __restri
     if (idx < F * K) {
         const int i = idx / K, k = idx % K;
         float a = 0.f;
-        for (int p = 0; p < P; ++p) a += dz1[p * F + i] * w[p * K + k];
+        int p = 0;
+        for (; p + 8 <= P; p += 8) {
+            float x[8], y[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { x[u] = dz1[(p + u) * F + i]; y[u] = w[(p + u) * K + k]; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += x[u] * y[u];
+        }
+        for (; p < P; ++p) a += dz1[p * F + i] * w[p * K + k];
         dhp[o_wh1 + idx] = a;
         return;
     }
     idx -= F * K;
     if (idx < F) {
         float a = 0.f;
-        for (int p = 0; p < P; ++p) a += dz1[p * F + idx];
+        int p = 0;
+        for (; p + 8 <= P; p += 8) {
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = dz1[(p + u) * F + idx];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += x[u];
+        }
+        for (; p < P; ++p) a += dz1[p * F + idx];
         dhp[o_bh1 + idx] = a;
     }
 }

@@ -1317,14 +1317,27 @@ __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, con
     const T* hrow = Hin + ((int64_t)p * M + (m0 + lr)) * W;
     const T* wrow = theta_mat + (int64_t)p * mat_len + mat_off + (int64_t)lr * W;
     const bool a_ok = (m0 + lr) < M, b_ok = lr < out_dim;
-    float4_t c = {0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < W; k0 += 4 * VE) {
-        const int k = k0 + lg * VE;
-        uint4 fa = make_uint4(0, 0, 0, 0), fb = make_uint4(0, 0, 0, 0);
-        if (a_ok && k < W) fa = *reinterpret_cast<const uint4*>(hrow + k);
-        if (b_ok && k < W) fb = *reinterpret_cast<const uint4*>(wrow + k);
-        Mma16<T>::run(fa, fb, c);
+    // eight contraction steps per batch: their loads are issued together, and two accumulators alternate so
+    // that consecutive MFMAs do not wait for each other
+    float4_t c = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < W; k0 += 32 * VE) {
+        uint4 fa[8], fb[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + (4 * u + lg) * VE;
+            fa[u] = make_uint4(0, 0, 0, 0);
+            fb[u] = make_uint4(0, 0, 0, 0);
+            if (a_ok && k < W) fa[u] = *reinterpret_cast<const uint4*>(hrow + k);
+            if (b_ok && k < W) fb[u] = *reinterpret_cast<const uint4*>(wrow + k);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u += 2) {
+            Mma16<T>::run(fa[u], fb[u], c);
+            Mma16<T>::run(fa[u + 1], fb[u + 1], c2);
+        }
     }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c[e] += c2[e];
     // lane holds column lr of rows m0 + 4*lg + e
     const float bias = b_ok ? theta_vec[(int64_t)p * vec_len + vec_off + lr] : 0.f;
     float ls = 0.f, sg = 0.f;
