@@ -21,12 +21,16 @@ weights; the trunk f is a two-layer tanh MLP; the Gaussian log-std is state
 independent and produced by the actor hypernet; the actor mean is tanh(z);
 GAE is the textbook recursion with `done` as a select; advantages are
 scalarised then normalised over the minibatch with population std + 1e-8;
-losses carry no extra coefficients and no entropy term.
+losses carry no extra coefficients and no entropy term; the optimiser is Adam
+with one learning rate per hypernet; a time-limit episode end bootstraps from
+the next value but restarts the advantage sum.
 
 Pinned by tests/test_oracle_*.py: closed forms and brute force for GAE,
 float64 torch.autograd and central finite differences for every gradient,
 library routines (torch linear/tanh/silu, torch Normal.log_prob) for the
-forward pieces, structural invariants for the hypernet.  Not pinned
+forward pieces, structural invariants for the hypernet, closed forms and
+torch.optim.Adam for the optimiser step, reduction to the untruncated recursion
+on a cut trajectory for the truncation mask.  Not pinned
 ("parity unpinned"): which of the readings above the authors' own code uses,
 because that code is not available.
 """
@@ -343,14 +347,20 @@ def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulat
 
 # --------------------------------------------------------------------------- advantage estimation
 
-def vec_gae(r, v, done, w, gamma, lam):
+def vec_gae(r, v, done, w, gamma, lam, trunc=None):
     """Generalised advantage estimation applied to each objective on its own, then scalarised with
     the environment's trade-off vector (Sec. III-C, update phase).  r [T,N,K], v [T+1,N,K],
     done [T,N] (1: the transition at step t ended the episode), w [P,K].  Backward in time,
     per (n, k): if done: delta = r_t - V_t and the running sum restarts at delta; otherwise
     delta = r_t + gamma V_{t+1} - V_t and A_t = delta + gamma lam A_{t+1}; A_T = 0.
     Value target Vhat_t = A_t + V_t.  Scalar advantage A^s[t,n] = sum_k w[g(n),k] A_t[n,k].
-    `done` acts as a select, so nothing after an episode end can reach the steps before it."""
+    `done` acts as a select, so nothing after an episode end can reach the steps before it.
+
+    trunc [T,N] (optional; Sec. III-D separates failures from time limits in value estimation):
+    1 where the episode end at step t was a time limit.  Reading taken: a truncated step still
+    bootstraps from V_{t+1}, which the caller supplies as the value of the state the episode was cut
+    at, but like every episode end it restarts the running sum: delta = r_t + gamma V_{t+1} - V_t,
+    A_t = delta.  A step with trunc = 1 counts as an episode end whatever `done` says."""
     r = np.asarray(r, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     done = np.asarray(done)
@@ -365,6 +375,9 @@ def vec_gae(r, v, done, w, gamma, lam):
         delta_live = r[t] + gamma * v[t + 1] - v[t]
         delta_done = r[t] - v[t]
         acc = np.where(dn, delta_done, delta_live + gamma * lam * acc)
+        if trunc is not None:
+            tr = (np.asarray(trunc)[t] != 0)[:, None]
+            acc = np.where(tr, delta_live, acc)
         adv[t] = acc
     vtarg = adv + v[:T]
     wn = w[g]                                  # [N, K]
@@ -437,6 +450,22 @@ def ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, v, vtarg, clip_eps,
 
 # --------------------------------------------------------------------------- one update step
 
+def adam_step(theta, g, m, v, lr, beta1, beta2, eps, t):
+    """One Adam step (Kingma & Ba 2015, Algorithm 1) on a flat parameter vector; t = 1 for the first
+    step.  The paper updates the two hypernets separately so that they can learn at different rates
+    (Sec. III-C, update phase) and does not name the optimiser; Adam is the reading taken.
+      m <- beta1 m + (1 - beta1) g,  v <- beta2 v + (1 - beta2) g^2,
+      theta <- theta - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+    Returns (theta, m, v) as new float64 arrays."""
+    theta = np.asarray(theta, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    m = beta1 * np.asarray(m, dtype=np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, dtype=np.float64) + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return theta - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
+
+
 def minibatch_rows(d, T, b, MB):
     """Minibatch b of MB: every time step, and in each preference group the b-th slice of n_g / MB
     environments, so every minibatch holds every preference."""
@@ -447,14 +476,17 @@ def minibatch_rows(d, T, b, MB):
 
 
 def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rewards, dones, eps,
-                gamma, lam, clip_eps, minibatches=1, epochs=1, emulate_bf16=False, keep=False):
+                gamma, lam, clip_eps, minibatches=1, epochs=1, emulate_bf16=False, keep=False, optimizer=None):
     """One MORLAX iteration after the trade-offs are drawn (Sec. III-C): rollout forward of the
     actor family (sampling actions and their log-density) and of the critic family at every state,
     vector GAE, then for every epoch and minibatch the losses and their gradients with respect to
     both hypernets.  The actor loss reaches only the actor hypernet and the value loss only the
-    critic hypernet (decoupled updates).  No optimiser step is taken, so every minibatch is
-    evaluated at the same update-time parameters.  Returns a dict; with keep=True it also holds
-    the intermediate tensors."""
+    critic hypernet (decoupled updates).  Without `optimizer` no parameter changes, so every
+    minibatch is evaluated at the same update-time parameters.  With optimizer = dict(lr_actor,
+    lr_critic, beta1, beta2, eps) each minibatch is followed by one Adam step on either hypernet with
+    its own learning rate (moments start at zero, step counter t = 1, 2, ...), and the result holds
+    the final parameters and moments.  Returns a dict; with keep=True it also holds the intermediate
+    tensors of the first minibatch."""
     T = rewards.shape[0]
     wq = (lambda m: round_bf16(m)) if (emulate_bf16 and d.wdtype == 1) else (lambda m: m)
     emu = bool(emulate_bf16 and d.wdtype == 1)
@@ -467,6 +499,11 @@ def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rew
     v_roll, _, _ = policy_fwd(d, CRITIC, tm_c0, tv_c0, obs, full_rows(d, T + 1), emulate_bf16=emu)
     adv_vec, vtarg, adv_s = vec_gae(rewards, v_roll, dones, w, gamma, lam)
     grads = []
+    if optimizer is not None:
+        hp_actor = np.asarray(hp_actor, dtype=np.float64).copy()
+        hp_critic = np.asarray(hp_critic, dtype=np.float64).copy()
+        mom = {n: [np.zeros_like(h), np.zeros_like(h)] for n, h in ((ACTOR, hp_actor), (CRITIC, hp_critic))}
+        t_opt = 0
     for e in range(epochs):
         for b in range(minibatches):
             rows = minibatch_rows(d, T, b, minibatches)
@@ -483,12 +520,22 @@ def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rew
             g_a = hypernet_bwd(d, ACTOR, hp_actor, w, dm_a, dvec_a)
             g_c = hypernet_bwd(d, CRITIC, hp_critic, w, dm_c, dvec_c)
             grads.append({"rows": rows, "dhp_actor": g_a, "dhp_critic": g_c, "stats": stats})
+            if optimizer is not None:
+                t_opt += 1
+                o = optimizer
+                hp_actor, mom[ACTOR][0], mom[ACTOR][1] = adam_step(hp_actor, g_a, mom[ACTOR][0], mom[ACTOR][1],
+                                                                  o["lr_actor"], o["beta1"], o["beta2"], o["eps"], t_opt)
+                hp_critic, mom[CRITIC][0], mom[CRITIC][1] = adam_step(hp_critic, g_c, mom[CRITIC][0], mom[CRITIC][1],
+                                                                     o["lr_critic"], o["beta1"], o["beta2"], o["eps"], t_opt)
             if keep and e == 0 and b == 0:
                 res.update(mu=mu, v=vv, dmu=dmu, dlogsig=dlogsig, dv=dv, dtheta_mat_actor=dm_a,
                            dtheta_vec_actor=dvec_a, dtheta_mat_critic=dm_c, dtheta_vec_critic=dvec_c,
                            theta_mat_actor=tm_a, theta_vec_actor=tv_a, theta_mat_critic=tm_c,
                            theta_vec_critic=tv_c)
     res["grads"] = grads
+    if optimizer is not None:
+        res.update(hp_actor=hp_actor, hp_critic=hp_critic, adam_m_actor=mom[ACTOR][0], adam_v_actor=mom[ACTOR][1],
+                   adam_m_critic=mom[CRITIC][0], adam_v_critic=mom[CRITIC][1])
     if keep:
         res.update(mu_old=mu_old, act=act, logp_old=logp_old, v_roll=v_roll, adv_vec=adv_vec,
                    vtarg=vtarg, adv_s=adv_s)
