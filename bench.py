@@ -65,6 +65,61 @@ def cpu_baseline(cfg_full):
                       f"cost per env-step does not depend on P; {dt:.1f} s of numpy float64"}
 
 
+def bench_kernel(a, cfg):
+    """One bandwidth-bound kernel alone at the workload's size: K launches between two events on the launch stream."""
+    import numpy as np
+    import torch
+    from paper_2603_09237_amd import binding, inputs
+    ctx = binding.Context.from_config(cfg)
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    T, N, K = cfg.T, cfg.N, cfg.K
+    if a.row == "adam_step":
+        n = [ctx.hparam_count(net) for net in (0, 1)]
+        th = [torch.randn(k, device="cuda") for k in n]
+        g = [torch.randn(k, device="cuda") * 1e-2 for k in n]
+        m = [torch.zeros(k, device="cuda") for k in n]
+        v = [torch.zeros(k, device="cuda") for k in n]
+        step = [0]
+
+        def launch():
+            step[0] += 1
+            for net in (0, 1):
+                ctx.adam_step(net, th[net], g[net], m[net], v[net], 3e-4, 0.9, 0.999, 1e-8, step[0])
+        units, unit_name, bytes_per_launch = sum(n), "parameters/s", 28.0 * sum(n)   # 4 arrays read, 3 written
+        metric = "adam_step_params_per_sec"
+    else:
+        r, vv, w = dev(inputs.make_rewards(cfg)), dev(inputs.make_values(cfg)), dev(inputs.make_preferences(cfg))
+        rng = np.random.default_rng(3)
+        done = dev((rng.random((T, N)) < cfg.p_done).astype(np.uint8))
+        trunc = dev((rng.random((T, N)) < 0.01).astype(np.uint8))
+        vt, a_s = torch.empty(T, N, K, device="cuda"), torch.empty(T, N, device="cuda")
+        if a.row == "vec_gae":
+            launch = lambda: ctx.vec_gae(r, vv, done, w, cfg.gamma, cfg.lam, None, vt, a_s)
+        else:
+            launch = lambda: ctx.vec_gae_trunc(r, vv, done, trunc, w, cfg.gamma, cfg.lam, None, vt, a_s)
+        # r, v read, vtarg written (4K each, v has T+1 steps), done (+trunc) read, adv_s written
+        per_cell = 4 * K + 4 * K * (T + 1) / T + 1 + (1 if a.row == "vec_gae_trunc" else 0) + 4 * K + 4
+        units, unit_name, bytes_per_launch = T * N, "env-steps/s", per_cell * T * N
+        metric = a.row + "_env_steps_per_sec"
+    for _ in range(max(a.warmup, 1)):
+        launch()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(a.steps):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    gbs = bytes_per_launch / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": metric, "value": units / (ms * 1e-3), "unit": unit_name, "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic", "config": {"workload": cfg.name, "row": a.row},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
+                     "traffic": None, "bytes_per_launch": bytes_per_launch}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +131,10 @@ def main():
                     help="1 (default): every launch on one stream, so that the per-kernel durations behind `roofline` are "
                          "those of kernels running alone; 2: actor and critic chains on their own HIP streams (faster "
                          "step, but concurrent kernels stretch each other's durations)")
+    ap.add_argument("--with-optimizer", action="store_true",
+                    help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
+    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc"), default="update_step",
+                    help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")
     a = ap.parse_args()
@@ -93,7 +152,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     cfg = CONFIGS[a.config]
-    st = UpdateStep(cfg, two_streams=(a.streams == 2))
+    if a.row != "update_step":
+        bench_kernel(a, cfg)
+        return
+    opt = dict(lr_actor=3e-4, lr_critic=1e-3, beta1=0.9, beta2=0.999, eps=1e-8) if a.with_optimizer else None
+    st = UpdateStep(cfg, two_streams=(a.streams == 2), optimizer=opt)
     st.load_inputs(inputs.make_all(cfg))
     torch.cuda.synchronize()
     for _ in range(a.warmup):
@@ -132,7 +195,7 @@ def main():
         "config": {"workload": cfg.name, "K": cfg.K, "P": cfg.P, "N": cfg.N, "T": cfg.T, "obs_dim": cfg.obs_dim,
                    "act_dim": cfg.act_dim, "mlp": f"{cfg.n_hidden}x{cfg.width}", "rank": cfg.rank,
                    "minibatches": cfg.minibatches, "epochs": cfg.epochs, "env_steps_per_step": env_steps,
-                   "optimizer_step": "not included"},
+                   "optimizer_step": "adam, one learning rate per hypernet" if a.with_optimizer else "not included"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, kind)),
                      "kernel": KERNEL_OF_KIND[kind], "launches_per_step": launches / a.steps,

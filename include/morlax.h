@@ -141,6 +141,29 @@ int morlax_vec_gae(morlax_ctx* ctx, const float* r, const float* v, const uint8_
                    const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
                    float* adv_s, void* stream);
 
+/* The same scan with time limits told apart from failures (Sec. III-D: terminations and truncations
+ * are distinguished in value estimation).  trunc [T, N] u8, non-zero: the episode was cut by a time
+ * limit at step t.  Such a step keeps the bootstrap, delta = r_t + gamma V_{t+1} - V_t with V_{t+1}
+ * the value of the state the episode was cut at (the caller stores it in v[t+1]), and restarts the
+ * sum like any episode end: A_t = delta.  A step with trunc != 0 is an episode end whatever done[t]
+ * says; with trunc all zero the results equal morlax_vec_gae's bit for bit.  Other arguments,
+ * layouts and errors as morlax_vec_gae; trunc is a device pointer and must not be NULL. */
+int morlax_vec_gae_trunc(morlax_ctx* ctx, const float* r, const float* v, const uint8_t* done,
+                         const uint8_t* trunc, const float* w, float gamma, float lambda,
+                         float* adv_vec, float* vtarg, float* adv_s, void* stream);
+
+/* One Adam step on the hypernet parameters of `net` (Sec. III-C, update phase: the two hypernets are
+ * updated separately so that they can learn at different rates; the paper does not name the
+ * optimiser, Adam with bias correction is the reading taken).  All arrays are device pointers to
+ * morlax_hparam_count(ctx, net) floats; hparams, m and v are updated in place, dhparams is read:
+ *   m <- beta1 m + (1 - beta1) g,   v <- beta2 v + (1 - beta2) g^2,
+ *   hparams <- hparams - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps).
+ * step counts from 1; the caller zeroes m and v before the first step and keeps one (m, v, step,
+ * lr) per hypernet.  MORLAX_ERR_SHAPE for step < 1, betas outside [0, 1), eps <= 0 or lr < 0. */
+int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const float* dhparams, float* m,
+                     float* v, float lr, float beta1, float beta2, float eps, int32_t step,
+                     void* stream);
+
 /* Clipped PPO surrogate and vector value loss with their gradients on one minibatch (Sec. III-C,
  * update phase).  B = selected cells.  Ahat = (adv_s - mean) / (std + 1e-8) over the selection
  * (population std) when norm_adv != 0, else adv_s.  logp = Gaussian log-density of act under

@@ -36,8 +36,8 @@ _lib = None
 EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hparam_count",
            "morlax_theta_mat_len", "morlax_theta_vec_len", "morlax_saved_bytes", "morlax_workspace_bytes",
            "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
-           "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad", "morlax_profile_begin",
-           "morlax_profile_end")
+           "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
+           "morlax_ppo_loss_grad", "morlax_profile_begin", "morlax_profile_end")
 
 GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first")
 
@@ -74,6 +74,8 @@ def load():
     lib.morlax_policy_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.morlax_policy_bwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.morlax_vec_gae.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.morlax_vec_gae_trunc.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.morlax_adam_step.argtypes = [vp, C.c_int, vp, vp, vp, vp, f32, f32, f32, f32, i32, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
                                          vp, vp, vp, vp, vp, vp]
     lib.morlax_profile_begin.argtypes = [vp]
@@ -81,7 +83,8 @@ def load():
     lib.morlax_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double)]
     lib.morlax_profile_end.restype = C.c_int
     for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
-                 "morlax_policy_bwd", "morlax_vec_gae", "morlax_ppo_loss_grad"):
+                 "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
+                 "morlax_ppo_loss_grad"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -196,6 +199,16 @@ class Context:
         self._check(self.lib.morlax_vec_gae(self.h, _ptr(r), _ptr(v), _ptr(done), _ptr(w), float(gamma), float(lam),
                                             _ptr(adv_vec), _ptr(vtarg), _ptr(adv_s),
                                             stream if stream is not None else _stream()))
+
+    def vec_gae_trunc(self, r, v, done, trunc, w, gamma, lam, adv_vec, vtarg, adv_s, stream=None):
+        self._check(self.lib.morlax_vec_gae_trunc(self.h, _ptr(r), _ptr(v), _ptr(done), _ptr(trunc), _ptr(w),
+                                                  float(gamma), float(lam), _ptr(adv_vec), _ptr(vtarg), _ptr(adv_s),
+                                                  stream if stream is not None else _stream()))
+
+    def adam_step(self, net, hparams, dhparams, m, v, lr, beta1, beta2, eps, step, stream=None):
+        self._check(self.lib.morlax_adam_step(self.h, net, _ptr(hparams), _ptr(dhparams), _ptr(m), _ptr(v),
+                                              float(lr), float(beta1), float(beta2), float(eps), int(step),
+                                              stream if stream is not None else _stream()))
 
     def ppo_loss_grad(self, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv,
                       dmu, dlogsig, dv, stats, ws, stream=None):

@@ -24,7 +24,8 @@ void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s) {
 // is sequential per lane; loads of U steps are issued before the U dependent updates.
 template <int U>
 __global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
-                                                const uint8_t* __restrict__ done, const float* __restrict__ w,
+                                                const uint8_t* __restrict__ done,
+                                                const uint8_t* __restrict__ trunc, const float* __restrict__ w,
                                                 float gamma, float gl, float* __restrict__ adv_vec,
                                                 float* __restrict__ vtarg, float* __restrict__ adv_s,
                                                 int T, int N, int K, int n_g) {
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, co
     int t = T - 1;
     while (t >= 0) {
         float rt[U], vt[U];
-        uint8_t dn[U];
+        uint8_t dn[U], tr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int tt = t - u;
@@ -50,6 +51,7 @@ __global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, co
             rt[u] = ok ? r[(int64_t)tt * NK + idx] : 0.f;
             vt[u] = ok ? v[(int64_t)tt * NK + idx] : 0.f;
             dn[u] = ok ? done[(int64_t)tt * N + n] : (uint8_t)0;
+            tr[u] = (ok && trunc) ? trunc[(int64_t)tt * N + n] : (uint8_t)0;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -58,6 +60,7 @@ __global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, co
             const float d_done = rt[u] - vt[u];
             const float d_live = rt[u] + gamma * vn - vt[u];
             acc = dn[u] ? d_done : (d_live + gl * acc);
+            acc = tr[u] ? d_live : acc;  // a time limit keeps the bootstrap and restarts the sum
             float s = wk * acc;
             float tot = s;
             for (int j = 1; j < K; ++j) tot += __shfl_down(s, j, WAVE);
@@ -74,13 +77,13 @@ __global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, co
 }
 
 void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const uint8_t* done,
-                    const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
-                    float* adv_s, hipStream_t s) {
+                    const uint8_t* trunc, const float* w, float gamma, float lambda, float* adv_vec,
+                    float* vtarg, float* adv_s, hipStream_t s) {
     const int K = c->d.K, N = c->d.N, T = c->d.T;
     const int G = WAVE / K;
     const int waves = (N + G - 1) / G;
     const int blocks = (waves + 3) / 4;
-    k_vec_gae<8><<<blocks, 256, 0, s>>>(r, v, done, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s, T, N, K,
+    k_vec_gae<16><<<blocks, 256, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s, T, N, K,
                                         c->n_g);
 }
 
@@ -290,4 +293,55 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
                                                         (float)(1.0 / cnt), dmu, dv, L.stat_part, L.dls_part,
                                                         N, c->n_g, A, K);
     k_loss_final<<<P + 1, 256, 0, s>>>(L.stat_part, L.dls_part, L.adv_stat, nbm, P, A, cnt, dlogsig, stats);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Adam step on a flat parameter vector (optimiser of the decoupled hypernet updates, Sec. III-C):
+//   m <- b1 m + (1 - b1) g,  v <- b2 v + (1 - b2) g^2,
+//   theta <- theta - lr (m c1) / (sqrt(v c2) + eps),  c1 = 1 / (1 - b1^t), c2 = 1 / (1 - b2^t)
+// (the host computes c1 and c2 in double precision).  Four elements per thread; bound: HBM, 28 bytes
+// per parameter (theta, g, m, v read; theta, m, v written).
+__global__ __launch_bounds__(256) void k_adam_step(float* __restrict__ theta, const float* __restrict__ g,
+                                                  float* __restrict__ m, float* __restrict__ v, int64_t n,
+                                                  float lr, float b1, float b2, float eps, float c1, float c2) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n) return;
+    float th[4], gg[4], mm[4], vv[4];
+    const bool full = i + 4 <= n;
+    if (full) {
+        const float4 a = *reinterpret_cast<const float4*>(theta + i), b = *reinterpret_cast<const float4*>(g + i);
+        const float4 c = *reinterpret_cast<const float4*>(m + i), d = *reinterpret_cast<const float4*>(v + i);
+        th[0] = a.x; th[1] = a.y; th[2] = a.z; th[3] = a.w;
+        gg[0] = b.x; gg[1] = b.y; gg[2] = b.z; gg[3] = b.w;
+        mm[0] = c.x; mm[1] = c.y; mm[2] = c.z; mm[3] = c.w;
+        vv[0] = d.x; vv[1] = d.y; vv[2] = d.z; vv[3] = d.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool ok = i + e < n;
+            th[e] = ok ? theta[i + e] : 0.f; gg[e] = ok ? g[i + e] : 0.f;
+            mm[e] = ok ? m[i + e] : 0.f; vv[e] = ok ? v[i + e] : 0.f;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        mm[e] = b1 * mm[e] + (1.f - b1) * gg[e];
+        vv[e] = b2 * vv[e] + (1.f - b2) * gg[e] * gg[e];
+        th[e] -= lr * (mm[e] * c1) / (sqrtf(vv[e] * c2) + eps);
+    }
+    if (full) {
+        *reinterpret_cast<float4*>(theta + i) = make_float4(th[0], th[1], th[2], th[3]);
+        *reinterpret_cast<float4*>(m + i) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+        *reinterpret_cast<float4*>(v + i) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (i + e < n) { theta[i + e] = th[e]; m[i + e] = mm[e]; v[i + e] = vv[e]; }
+    }
+}
+
+void launch_adam_step(float* theta, const float* g, float* m, float* v, int64_t n, float lr, float b1, float b2,
+                      float eps, float c1, float c2, hipStream_t s) {
+    const int64_t blocks = (n + 1023) / 1024;
+    k_adam_step<<<(unsigned)blocks, 256, 0, s>>>(theta, g, m, v, n, lr, b1, b2, eps, c1, c2);
 }

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/morlax.h: context construction (layouts of the
 // hypernet parameter vector and of theta), argument validation (all of it before the first HIP
 // call) and dispatch to the kernel launchers.
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -278,7 +279,37 @@ extern "C" int morlax_vec_gae(morlax_ctx* ctx, const float* r, const float* v, c
     OPT(adv_vec, who);
     if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f))
         return fail(MORLAX_ERR_SHAPE, "%s: gamma and lambda must lie in [0, 1]", who);
-    launch_vec_gae(ctx, r, v, done, w, gamma, lambda, adv_vec, vtarg, adv_s, (hipStream_t)stream);
+    launch_vec_gae(ctx, r, v, done, nullptr, w, gamma, lambda, adv_vec, vtarg, adv_s, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_vec_gae_trunc(morlax_ctx* ctx, const float* r, const float* v, const uint8_t* done,
+                                    const uint8_t* trunc, const float* w, float gamma, float lambda,
+                                    float* adv_vec, float* vtarg, float* adv_s, void* stream) {
+    const char* who = "morlax_vec_gae_trunc";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    REQ(r, who); REQ(v, who); REQ(done, who); REQ(trunc, who); REQ(w, who); REQ(vtarg, who); REQ(adv_s, who);
+    OPT(adv_vec, who);
+    if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f))
+        return fail(MORLAX_ERR_SHAPE, "%s: gamma and lambda must lie in [0, 1]", who);
+    launch_vec_gae(ctx, r, v, done, trunc, w, gamma, lambda, adv_vec, vtarg, adv_s, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const float* dhparams, float* m, float* v,
+                                float lr, float beta1, float beta2, float eps, int32_t step, void* stream) {
+    const char* who = "morlax_adam_step";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
+    REQ(hparams, who); REQ(dhparams, who); REQ(m, who); REQ(v, who);
+    if (step < 1) return fail(MORLAX_ERR_SHAPE, "%s: step counts from 1", who);
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+        return fail(MORLAX_ERR_SHAPE, "%s: beta1 and beta2 must lie in [0, 1)", who);
+    if (!(eps > 0.f) || !(lr >= 0.f)) return fail(MORLAX_ERR_SHAPE, "%s: eps must be positive and lr non-negative", who);
+    const double c1 = 1.0 / (1.0 - std::pow((double)beta1, (double)step));
+    const double c2 = 1.0 / (1.0 - std::pow((double)beta2, (double)step));
+    launch_adam_step(hparams, dhparams, m, v, morlax_hparam_count(ctx, net), lr, beta1, beta2, eps, (float)c1,
+                     (float)c2, (hipStream_t)stream);
     return finish(who);
 }
 

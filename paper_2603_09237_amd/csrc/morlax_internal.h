@@ -66,8 +66,10 @@ struct RowSel {  // a validated morlax_rows plus derived sizes
 void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s);
 
 void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const uint8_t* done,
-                    const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
-                    float* adv_s, hipStream_t s);
+                    const uint8_t* trunc, const float* w, float gamma, float lambda, float* adv_vec,
+                    float* vtarg, float* adv_s, hipStream_t s);
+void launch_adam_step(float* theta, const float* g, float* m, float* v, int64_t n, float lr, float b1, float b2,
+                      float eps, float c1, float c2, hipStream_t s);
 
 int64_t loss_ws_bytes(const morlax_ctx* c, const RowSel& rs);
 void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu, const float* logsig,

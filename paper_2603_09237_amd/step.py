@@ -16,7 +16,10 @@ from .configs import Config, WDTYPE_BF16
 
 
 class UpdateStep:
-    def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False, two_streams: bool = False):
+    def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False, two_streams: bool = False,
+                 optimizer: dict | None = None):
+        """optimizer = dict(lr_actor, lr_critic, beta1, beta2, eps): take one Adam step on either hypernet
+        after every minibatch (a true PPO update); None: gradients only, parameters stay fixed."""
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -68,6 +71,11 @@ class UpdateStep:
                     for net in (ACTOR, CRITIC)}
         self.ws = self.wsn[ACTOR]
         self.streams = {net: torch.cuda.Stream(device=self.dev) for net in (ACTOR, CRITIC)} if two_streams else None
+        self.optimizer = optimizer
+        self.opt_step = 0
+        if optimizer is not None:
+            self.adam_m = {net: torch.zeros_like(self.hp[net]) for net in (ACTOR, CRITIC)}
+            self.adam_v = {net: torch.zeros_like(self.hp[net]) for net in (ACTOR, CRITIC)}
         self.full_T = (0, T, 0, c.n_g)
         self.full_T1 = (0, T + 1, 0, c.n_g)
         self.logsig_off = ctx.theta_vec_len(ACTOR) - A
@@ -123,10 +131,18 @@ class UpdateStep:
             ctx.policy_fwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, out[net],
                            saved=self.saved[net], ws=ws)
 
+        if self.optimizer is not None:
+            self.opt_step += 1
+        o = self.optimizer
+
         def bwd(net, ws):
             ctx.policy_bwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, self.saved[net], dout[net],
                            self.dlogsig if net == ACTOR else None, self.dtheta_mat[net], self.dtheta_vec[net], ws)
             ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net], self.dhp[net], ws)
+            if o is not None:
+                ctx.adam_step(net, self.hp[net], self.dhp[net], self.adam_m[net], self.adam_v[net],
+                              o["lr_actor"] if net == ACTOR else o["lr_critic"], o["beta1"], o["beta2"], o["eps"],
+                              self.opt_step)
 
         self._per_net(fwd)
         logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off

@@ -100,4 +100,16 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
         ctx.ppo_loss_grad((0, 1, 0, 1), good, good, 1, good, good, good, good, good, 0.2, 1, good, good, good,
                           good, good, stream=0)
     assert e.value.code == binding.ERR_SHAPE           # logsig_stride < act_dim
+    with pytest.raises(binding.MorlaxError) as e:      # the optimiser step counts from 1
+        ctx.adam_step(0, good, good, good, good, 1e-3, 0.9, 0.999, 1e-8, 0, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.adam_step(0, good, good, good, good, 1e-3, 1.0, 0.999, 1e-8, 1, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.adam_step(1, good, good, None, good, 1e-3, 0.9, 0.999, 1e-8, 1, stream=0)
+    assert e.value.code == binding.ERR_NULL
+    with pytest.raises(binding.MorlaxError) as e:      # the truncation mask is not optional here
+        ctx.vec_gae_trunc(good, good, good, None, good, 0.99, 0.95, None, good, good, stream=0)
+    assert e.value.code == binding.ERR_NULL
     ctx.close()
