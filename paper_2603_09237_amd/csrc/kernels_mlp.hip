@@ -1373,30 +1373,65 @@ __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, con
     }
 }
 
-// dZ_{L-1}[m, i] = (sum_j dz_L[m, j] W_L(p)[j, i]) * act'(z_{L-1})[m, i], dz_L = dout * (1 - mu^2) for the
-// tanh head.  Block: 64 rows x 128 columns of one preference; thread: 4 rows x 8 columns.
+// dz_L = dout * (1 - mu^2) for the tanh head (else dout), gathered once per call into compact rows
+// dzh[p][m][0..15] (unrounded, zero beyond out_dim) for the two kernels below; the bias gradient
+// db_L(p)[j] = sum_m dz_L[m, j] leaves as per-block partials pb[p][block][j] (256 rows per block, summed in a
+// fixed order).
 template <typename T>
-__global__ __launch_bounds__(256) void k_head_bwd_dz(const float* __restrict__ dout,
-                                                    const float* __restrict__ saved_out,
+__global__ __launch_bounds__(256) void k_head_dzh(const float* __restrict__ dout, const float* __restrict__ saved_out,
+                                                 float* __restrict__ dzh, float* __restrict__ pb, int out_dim, int M,
+                                                 RowMap rm, int tanh_head) {
+    __shared__ float red[4][MORLAX_MAX_OUT];
+    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
+    float d[MORLAX_MAX_OUT];
+#pragma unroll
+    for (int j = 0; j < MORLAX_MAX_OUT; ++j) d[j] = 0.f;
+    if (m < M) {
+        const int64_t row = rm.row(p, m);
+#pragma unroll
+        for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
+            if (j < out_dim) {
+                d[j] = dout[row * out_dim + j];
+                if (tanh_head) {
+                    const float mu = saved_out[((int64_t)p * M + m) * OUT_PITCH + j];
+                    d[j] *= (1.f - mu * mu);
+                }
+            }
+        }
+        float4* dst = reinterpret_cast<float4*>(dzh + ((int64_t)p * M + m) * MORLAX_MAX_OUT);
+#pragma unroll
+        for (int q = 0; q < MORLAX_MAX_OUT / 4; ++q) dst[q] = make_float4(d[4 * q], d[4 * q + 1], d[4 * q + 2], d[4 * q + 3]);
+    }
+    // bias partials: butterfly inside each wave, then the four waves in order
+#pragma unroll
+    for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
+        float v = d[j];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][j] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < MORLAX_MAX_OUT)
+        pb[((int64_t)p * gridDim.x + blockIdx.x) * MORLAX_MAX_OUT + threadIdx.x] =
+            (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+// dZ_{L-1}[m, i] = (sum_j dz_L[m, j] W_L(p)[j, i]) * act'(z_{L-1})[m, i].  Block: 64 rows x 128 columns of
+// one preference; thread: 4 rows x 8 columns.
+template <typename T>
+__global__ __launch_bounds__(256) void k_head_bwd_dz(const float* __restrict__ dzh,
                                                     const T* __restrict__ theta_mat, int64_t mat_len,
                                                     int64_t mat_off,
                                                     const typename GradT<T>::type* __restrict__ G,
                                                     T* __restrict__ dZ, float* __restrict__ part,
-                                                    int W, int out_dim, int M, RowMap rm, int tanh_head) {
+                                                    int W, int out_dim, int M) {
     __shared__ float sdz[64][MORLAX_MAX_OUT];
     __shared__ float red[16][128];
     const int p = blockIdx.z, m0 = blockIdx.y * 64, i0 = blockIdx.x * 128;
     for (int idx = threadIdx.x; idx < 64 * MORLAX_MAX_OUT; idx += 256) {
         const int mm = idx / MORLAX_MAX_OUT, j = idx % MORLAX_MAX_OUT;
         float d = 0.f;
-        if (m0 + mm < M && j < out_dim) {
-            d = dout[rm.row(p, m0 + mm) * out_dim + j];
-            if (tanh_head) {
-                const float mu = saved_out[((int64_t)p * M + m0 + mm) * OUT_PITCH + j];
-                d *= (1.f - mu * mu);
-            }
-            d = to_f(cvt<T>(d));  // GEMM input rounding
-        }
+        if (m0 + mm < M) d = to_f(cvt<T>(dzh[((int64_t)p * M + m0 + mm) * MORLAX_MAX_OUT + j]));  // GEMM input rounding
         sdz[mm][j] = d;
     }
     __syncthreads();
@@ -1447,90 +1482,86 @@ __global__ __launch_bounds__(256) void k_head_bwd_dz(const float* __restrict__ d
     }
 }
 
-// dW_L(p)[j, i] = sum_m dz_L[m, j] h_{L-1}[m, i] and db_L(p)[j] = sum_m dz_L[m, j], in two stages.
-// Stage 1: a block takes HB_ROWS rows x 64 columns of one preference.  The dz rows (<= 16 columns,
-// rounded to the GEMM input type) and the h tile sit in LDS; wave w multiplies dz^T [16 x rows] by
-// h [rows x 16 columns 16 w ..] with fp32 16x16x4 MFMAs (bf16 h is widened on the way out of LDS, which
-// is exact).  Partials go to pw[p][chunk][j][i] and pb[p][chunk][j]; stage 2 (k_head_bwd_dw_final) adds
-// the chunks in order.
+// dW_L(p)[j, i] = sum_m dz_L[m, j] h_{L-1}[m, i] in two stages.  Stage 1: a block takes one of HB_SPLIT row
+// ranges of one preference and 128 columns, and walks its rows 128 at a time: the dz rows (rounded to the
+// GEMM input type) and the h tile sit in LDS, the next h tile is already on its way in registers; wave w
+// multiplies dz^T [16 x 128] by h [128 x columns 32 w .. 32 w + 31] with fp32 16x16x4 MFMAs (bf16 h is
+// widened on the way out of LDS, which is exact).  Partials go to pw[p][range][j][i]; stage 2
+// (k_head_bwd_dw_final) adds the ranges, and the bias partials of k_head_dzh, in order.
 #define HB_ROWS 128
+#define HB_SPLIT 4
 template <typename T>
-__global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ dout,
-                                                    const float* __restrict__ saved_out,
-                                                    const T* __restrict__ Hin, float* __restrict__ pw,
-                                                    float* __restrict__ pb, int W, int out_dim, int M, RowMap rm,
-                                                    int tanh_head) {
+__global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ dzh, const T* __restrict__ Hin,
+                                                    float* __restrict__ pw, int W, int M) {
     constexpr int VE = Elems<T>::VE;
-    constexpr int HP = 64 + VE;                            // h tile pitch in elements (16 bytes of padding)
-    __shared__ float sdr[HB_ROWS][MORLAX_MAX_OUT];         // rounded dz (GEMM input)
-    __shared__ float sdu[HB_ROWS][MORLAX_MAX_OUT];         // unrounded dz (bias gradient)
+    constexpr int HP = 128 + VE;                           // h tile pitch in elements (16 bytes of padding)
+    constexpr int CPR = 128 / VE;                          // 16-byte pieces per tile row
+    constexpr int NPT = HB_ROWS * CPR / 256;               // pieces per thread
+    __shared__ float sdr[HB_ROWS][MORLAX_MAX_OUT];
     __shared__ __align__(16) T sh[HB_ROWS][HP];
-    __shared__ float bpart[16][MORLAX_MAX_OUT];
-    const int p = blockIdx.z, chunk = blockIdx.y, m0 = chunk * HB_ROWS, i0 = blockIdx.x * 64;
-    const int n_chunk = gridDim.y;
-    // stage h: 16-byte pieces, rows beyond M and columns beyond W as zeros
-    for (int idx = threadIdx.x; idx < HB_ROWS * (64 / VE); idx += 256) {
-        const int mm = idx / (64 / VE), cc = (idx % (64 / VE)) * VE;
-        uint4 u = make_uint4(0, 0, 0, 0);
-        if (m0 + mm < M && i0 + cc < W)
-            u = *reinterpret_cast<const uint4*>(Hin + ((int64_t)p * M + m0 + mm) * W + i0 + cc);
-        *reinterpret_cast<uint4*>(&sh[mm][cc]) = u;
-    }
-    if (threadIdx.x < HB_ROWS) {
-        const int mm = threadIdx.x;
-        const bool ok = m0 + mm < M;
-        int64_t row = 0;
-        if (ok) row = rm.row(p, m0 + mm);
-#pragma unroll
-        for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
-            float d = 0.f;
-            if (ok && j < out_dim) {
-                d = dout[row * out_dim + j];
-                if (tanh_head) {
-                    const float mu = saved_out[((int64_t)p * M + m0 + mm) * OUT_PITCH + j];
-                    d *= (1.f - mu * mu);
-                }
-            }
-            sdu[mm][j] = d;
-            sdr[mm][j] = to_f(cvt<T>(d));
-        }
-    }
-    __syncthreads();
-    if (blockIdx.x == 0) {
-        const int j = threadIdx.x & 15, part = threadIdx.x >> 4;
-        float b = 0.f;
-        for (int mm = part * (HB_ROWS / 16); mm < (part + 1) * (HB_ROWS / 16); ++mm) b += sdu[mm][j];
-        bpart[part][j] = b;
-    }
+    const int p = blockIdx.z, rs = blockIdx.y, i0 = blockIdx.x * 128;
+    const int per = ((M + HB_SPLIT - 1) / HB_SPLIT + HB_ROWS - 1) / HB_ROWS * HB_ROWS;  // rows per range
+    const int m_lo = rs * per, m_hi = (m_lo + per < M) ? (m_lo + per) : M;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ln = lane & 15, kg = lane >> 4;
-    float4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-    for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
-        const int m = 4 * kk + kg;
-        const float a = sdr[m][ln];                 // dz^T[j = ln][m]
-        const float b = to_f(sh[m][16 * wave + ln]);  // h[m][column 16 wave + ln]
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
-    }
-    // lane holds column ln of rows j = 4 kg + e
-    const int col = i0 + 16 * wave + ln;
-    if (col < W) {
+    float4_t acc[2][2];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = 4 * kg + e;
-            if (j < out_dim) pw[(((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + j) * W + col] = acc[e];
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) acc[c][q] = float4_t{0.f, 0.f, 0.f, 0.f};
+    uint4 nxt[NPT];
+    auto fetch = [&](int m0) {
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {
+            const int idx = threadIdx.x + 256 * q, mm = idx / CPR, cc = (idx % CPR) * VE;
+            uint4 u = make_uint4(0, 0, 0, 0);
+            if (m0 + mm < m_hi && i0 + cc < W)
+                u = *reinterpret_cast<const uint4*>(Hin + ((int64_t)p * M + m0 + mm) * W + i0 + cc);
+            nxt[q] = u;
+        }
+    };
+    if (m_lo < m_hi) fetch(m_lo);
+    for (int m0 = m_lo; m0 < m_hi; m0 += HB_ROWS) {
+        __syncthreads();  // the previous tile has been multiplied
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            *reinterpret_cast<uint4*>(&sh[idx / CPR][(idx % CPR) * VE]) = nxt[q];
+        }
+        for (int idx = threadIdx.x; idx < HB_ROWS * (MORLAX_MAX_OUT / 4); idx += 256) {
+            const int mm = idx / (MORLAX_MAX_OUT / 4), q = idx % (MORLAX_MAX_OUT / 4);
+            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m0 + mm < m_hi) d = *reinterpret_cast<const float4*>(dzh + ((int64_t)p * M + m0 + mm) * MORLAX_MAX_OUT + 4 * q);
+            sdr[mm][4 * q] = to_f(cvt<T>(d.x)); sdr[mm][4 * q + 1] = to_f(cvt<T>(d.y));
+            sdr[mm][4 * q + 2] = to_f(cvt<T>(d.z)); sdr[mm][4 * q + 3] = to_f(cvt<T>(d.w));
+        }
+        if (m0 + HB_ROWS < m_hi) fetch(m0 + HB_ROWS);
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
+            const int m = 4 * kk + kg;
+            const float a = sdr[m][ln];                              // dz^T[j = ln][m]
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const float b = to_f(sh[m][32 * wave + 16 * c + ln]);  // h[m][column]
+                acc[c][kk & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[c][kk & 1], 0, 0, 0);
+            }
         }
     }
-    __syncthreads();
-    if (blockIdx.x == 0 && threadIdx.x < out_dim) {
-        float v = 0.f;
-        for (int part = 0; part < 16; ++part) v += bpart[part][threadIdx.x];
-        pb[((int64_t)p * n_chunk + chunk) * MORLAX_MAX_OUT + threadIdx.x] = v;
+    // lane holds column ln of rows j = 4 kg + e
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int col = i0 + 32 * wave + 16 * c + ln;
+        if (col < W) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                pw[(((int64_t)p * HB_SPLIT + rs) * MORLAX_MAX_OUT + 4 * kg + e) * W + col] = acc[c][0][e] + acc[c][1][e];
+        }
     }
 }
 
 __global__ __launch_bounds__(256) void k_head_bwd_dw_final(const float* __restrict__ pw, const float* __restrict__ pb,
-                                                          int n_chunk, float* __restrict__ dtheta_mat,
+                                                          int n_chunk_w, int n_chunk_b, float* __restrict__ dtheta_mat,
                                                           float* __restrict__ dtheta_vec, int64_t mat_len,
                                                           int64_t vec_len, int64_t mat_off, int64_t vec_off, int W,
                                                           int out_dim) {
@@ -1538,12 +1569,12 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw_final(const float* __restri
     if (idx < out_dim * W) {
         const int j = idx / W, i = idx % W;
         float v = 0.f;
-        for (int c = 0; c < n_chunk; ++c) v += pw[(((int64_t)p * n_chunk + c) * MORLAX_MAX_OUT + j) * W + i];
+        for (int c = 0; c < n_chunk_w; ++c) v += pw[(((int64_t)p * n_chunk_w + c) * MORLAX_MAX_OUT + j) * W + i];
         dtheta_mat[(int64_t)p * mat_len + mat_off + idx] = v;
     }
     if (idx < out_dim) {
         float v = 0.f;
-        for (int c = 0; c < n_chunk; ++c) v += pb[((int64_t)p * n_chunk + c) * MORLAX_MAX_OUT + idx];
+        for (int c = 0; c < n_chunk_b; ++c) v += pb[((int64_t)p * n_chunk_b + c) * MORLAX_MAX_OUT + idx];
         dtheta_vec[(int64_t)p * vec_len + vec_off + idx] = v;
     }
 }
@@ -1567,6 +1598,22 @@ __global__ void k_copy_dlogsig(const float* __restrict__ dlogsig, float* __restr
     dtheta_vec[(int64_t)p * vec_len + off + a] = dlogsig ? dlogsig[idx] : 0.f;
 }
 
+// Rows of the fp32 observation tensor picked by the row map, rounded to the GEMM input type, as compact
+// [P][M][O] rows (O a multiple of 8): the first layer's GEMMs then run on the direct-to-LDS kernels.
+template <typename T>
+__global__ __launch_bounds__(256) void k_gather_x(const float* __restrict__ x, T* __restrict__ xc, int O, int M,
+                                                 RowMap rm) {
+    const int p = blockIdx.y;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one 8-element piece
+    const int per_row = O / 8;
+    if (idx >= (int64_t)M * per_row) return;
+    const int m = (int)(idx / per_row), c = (int)(idx % per_row) * 8;
+    const float* src = x + rm.row(p, m) * O + c;
+    float v[8];
+    get8(src, v);
+    store8(xc + ((int64_t)p * M + m) * O + c, v);
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 static int64_t esize(const morlax_ctx* c) { return c->d.wdtype == 1 ? 2 : 4; }
 static int64_t act_elems(const morlax_ctx* c, const RowSel& rs) {
@@ -1578,13 +1625,25 @@ int64_t mlp_saved_bytes(const morlax_ctx* c, int net, const RowSel& rs) {
     return 2 * (int64_t)c->d.n_hidden * act_elems(c, rs) * esize(c) +
            align_up((int64_t)c->d.P * rs.M * OUT_PITCH * 4, 256);
 }
-static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
+// fp32 scratch behind the two activation buffers: [0, head_lo): partial column sums of dZ, or the output
+// layer's dW partials followed by its bias partials; [head_lo, ..): the compact dz rows of the output layer
+// (still read while the column sums of the layer below are written).
+static int64_t head_pw_elems(const morlax_ctx* c) { return (int64_t)c->d.P * HB_SPLIT * MORLAX_MAX_OUT * c->d.width; }
+static int64_t head_lo_elems(const morlax_ctx* c, const RowSel& rs) {
     const int64_t colsum = (int64_t)c->d.P * ((rs.M + 63) / 64) * c->d.width;
-    const int64_t head = (int64_t)c->d.P * ((rs.M + HB_ROWS - 1) / HB_ROWS) * MORLAX_MAX_OUT * (c->d.width + 1);
+    const int64_t head = head_pw_elems(c) + (int64_t)c->d.P * ((rs.M + 255) / 256) * MORLAX_MAX_OUT;
     return align_up(colsum > head ? colsum : head, 64);
 }
+static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
+    return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64);
+}
+static int64_t x0_elems(const morlax_ctx* c, const RowSel& rs) {
+    return align_up((int64_t)c->d.P * rs.M * c->d.obs_dim, 64);
+}
+// compact first-layer input: bf16 networks whose observation width suits the direct-to-LDS GEMMs
+static bool use_x0(const morlax_ctx* c) { return c->d.wdtype == 1 && c->d.obs_dim % 32 == 0; }
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
-    return 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4;
+    return 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4 + (use_x0(c) ? x0_elems(c, rs) * esize(c) : 0);
 }
 
 static RowMap make_rowmap(const morlax_ctx* c, const RowSel& rs) {
@@ -1618,7 +1677,19 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         ep.G = Gbuf(l);
         ep.ld = W;
         ep.part = nullptr;
-        if (l == 0) {
+        if (l == 0 && use_x0(c)) {
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                T* x0 = reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
+                const int64_t pieces = (int64_t)M * (O / 8);
+                k_gather_x<T><<<dim3((unsigned)((pieces + 255) / 256), P), 256, 0, s>>>(x, x0, O, M, rm);
+                GemmArgs<T, SRC_KCONTIG, SRC_KCONTIG, EpiFwd<T, ACT, SAVE>, true, GEMM_NCH> g;
+                g.a.base = x0; g.a.ld = O; g.a.rows = M; g.a.kdim = O; g.a.rm = rm;
+                g.b.base = theta_mat + Ld.mat_off; g.b.ld = O; g.b.rows = W; g.b.kdim = O; g.b.rm = rm;
+                g.a_pstride = (int64_t)M * O; g.b_pstride = nd.mat_len;
+                g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
+                run_gemm(c, 0, g, P, s);
+            }
+        } else if (l == 0) {
             auto launch = [&](auto fast) {
                 constexpr bool F = decltype(fast)::value;
                 GemmArgs<T, SRC_X_KCONTIG, SRC_KCONTIG, EpiFwd<T, ACT, SAVE>, F, GEMM_NCH> g;
@@ -1679,17 +1750,18 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     const LayerDev& Lh = nd.layer[L];
     // output layer
     {
-        const int n_chunk = (M + HB_ROWS - 1) / HB_ROWS;
+        const int n_chunk_b = (M + 255) / 256;
         float* pw = part;
-        float* pb = part + (int64_t)P * n_chunk * MORLAX_MAX_OUT * W;
-        k_head_bwd_dw<T><<<dim3((W + 63) / 64, n_chunk, P), 256, 0, s>>>(dout, saved_out, Hbuf(L - 1), pw, pb, W,
-                                                                          nd.out_dim, M, rm, tanh_head);
+        float* pb = part + head_pw_elems(c);
+        float* dzh = part + head_lo_elems(c, rs);
+        k_head_dzh<T><<<dim3(n_chunk_b, P), 256, 0, s>>>(dout, saved_out, dzh, pb, nd.out_dim, M, rm, tanh_head);
+        k_head_bwd_dw<T><<<dim3((W + 127) / 128, HB_SPLIT, P), 256, 0, s>>>(dzh, Hbuf(L - 1), pw, W, M);
         k_head_bwd_dw_final<<<dim3((nd.out_dim * W + 255) / 256, P), 256, 0, s>>>(
-            pw, pb, n_chunk, dtheta_mat, dtheta_vec, nd.mat_len, nd.vec_len, Lh.mat_off, Lh.vec_off, W, nd.out_dim);
+            pw, pb, HB_SPLIT, n_chunk_b, dtheta_mat, dtheta_vec, nd.mat_len, nd.vec_len, Lh.mat_off, Lh.vec_off, W,
+            nd.out_dim);
+        k_head_bwd_dz<T><<<dim3((W + 127) / 128, (M + 63) / 64, P), 256, 0, s>>>(
+            dzh, theta_mat, nd.mat_len, Lh.mat_off, Gbuf(L - 1), dZbuf(L - 1), part, W, nd.out_dim, M);
     }
-    k_head_bwd_dz<T><<<dim3((W + 127) / 128, (M + 63) / 64, P), 256, 0, s>>>(
-        dout, saved_out, theta_mat, nd.mat_len, Lh.mat_off, Gbuf(L - 1), dZbuf(L - 1), part, W, nd.out_dim, M, rm,
-        tanh_head);
     for (int l = L - 1; l >= 0; --l) {
         const LayerDev& Ld = nd.layer[l];
         k_colsum_final<<<dim3((W + 255) / 256, P), 256, 0, s>>>(part, n_part, dtheta_vec, nd.vec_len, Ld.vec_off, W);
@@ -1711,6 +1783,18 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             h.e0_pstride = (int64_t)M * W; h.e1_pstride = 0; h.e2_pstride = 0;
             run_gemm(c, 2, h, P, s);
             n_part = h.tiles_m;  // row tiles of the kernel that ran (128 or 256 rows)
+        } else if (use_x0(c)) {
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                T* x0 = reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
+                const int64_t pieces = (int64_t)M * (O / 8);
+                k_gather_x<T><<<dim3((unsigned)((pieces + 255) / 256), P), 256, 0, s>>>(x, x0, O, M, rm);
+                GemmArgs<T, SRC_KSTRIDED, SRC_KSTRIDED, EpiDw, true, GEMM_NCH> g;
+                g.a.base = dZbuf(0); g.a.ld = W; g.a.rows = W; g.a.kdim = M; g.a.rm = rm;
+                g.b.base = x0; g.b.ld = O; g.b.rows = O; g.b.kdim = M; g.b.rm = rm;
+                g.a_pstride = (int64_t)M * W; g.b_pstride = (int64_t)M * O;
+                g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
+                run_gemm(c, 4, g, P, s);
+            }
         } else {
             auto launch = [&](auto fast) {
                 constexpr bool F = decltype(fast)::value;

@@ -83,7 +83,7 @@ void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const u
     const int G = WAVE / K;
     const int waves = (N + G - 1) / G;
     const int blocks = (waves + 3) / 4;
-    k_vec_gae<16><<<blocks, 256, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s, T, N, K,
+    k_vec_gae<8><<<blocks, 256, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s, T, N, K,
                                         c->n_g);
 }
 
