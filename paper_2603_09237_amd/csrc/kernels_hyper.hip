@@ -96,8 +96,24 @@ __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const floa
     for (int j = 0; j < MORLAX_MAX_F; ++j) m[j] = (j < F) ? mr[j] : 0.f;
     float* dst = (q < fac_len) ? (fac + q) : (theta_vec + (q - fac_len));
     const int64_t stride = (q < fac_len) ? fac_len : vec_len;
+    // blockIdx.y takes a run of preferences (one run: more did not pay, the per-thread row of M is reloaded)
+    const int per = (P + gridDim.y - 1) / gridDim.y;
+    const int p_lo = blockIdx.y * per, p_hi = (p_lo + per < P) ? (p_lo + per) : P;
     if (F == 32) {
-        for (int p = 0; p < P; ++p) {
+        // four preferences per batch: their feature rows (wave-uniform loads) are requested together
+        int p = p_lo;
+        for (; p + 4 <= p_hi; p += 4) {
+            float a[4] = {c, c, c, c};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float* fp = f + (int64_t)(p + u) * 32;
+#pragma unroll
+                for (int j = 0; j < 32; ++j) a[u] += m[j] * fp[j];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dst[(int64_t)(p + u) * stride] = a[u];
+        }
+        for (; p < p_hi; ++p) {
             const float* fp = f + (int64_t)p * 32;
             float a = c;
 #pragma unroll
@@ -105,7 +121,7 @@ __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const floa
             dst[(int64_t)p * stride] = a;
         }
     } else {
-        for (int p = 0; p < P; ++p) {
+        for (int p = p_lo; p < p_hi; ++p) {
             const float* fp = f + (int64_t)p * F;
             float a = c;
 #pragma unroll
@@ -190,7 +206,7 @@ static void run_trunk_and_affine(const morlax_ctx* c, int net, const float* hp, 
     const int P = c->d.P, F = c->d.hyper_width;
     k_hyper_trunk<<<P, 64, 0, s>>>(hp, w, L.h1, L.f, c->d.K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
     float* tv = theta_vec_or_null ? theta_vec_or_null : vec_scratch;
-    k_hyper_affine<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, hp, L.f, L.fac, tv, P, F, nd.fac_len, nd.vec_len);
+    k_hyper_affine<<<dim3((at.q_total + 255) / 256, 1), 256, 0, s>>>(at, hp, L.f, L.fac, tv, P, F, nd.fac_len, nd.vec_len);
 }
 
 static MatTiles mat_tiles(const NetDev& nd) {

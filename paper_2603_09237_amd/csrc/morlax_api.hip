@@ -109,6 +109,13 @@ extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
         return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: mean_tanh must be 0 or 1");
     if ((int64_t)(d.T + 1) * d.N >= (int64_t)1 << 31)
         return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: (T+1) * N must stay below 2^31");
+    // the GEMM kernels address an operand with 32-bit byte offsets from a per-preference (activations) or
+    // whole-tensor (observations) base
+    if ((int64_t)(d.T + 1) * d.N * d.obs_dim * 4 >= (int64_t)1 << 32)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: the observation tensor (T+1) * N * obs_dim must stay below 4 GiB");
+    if ((int64_t)(d.T + 1) * (d.N / d.P) * d.width * 4 >= (int64_t)1 << 31)
+        return fail(MORLAX_ERR_UNSUPPORTED,
+                    "morlax_create: one preference's activations (T+1) * (N/P) * width must stay below 2 GiB");
     morlax_ctx* c = new (std::nothrow) morlax_ctx;
     if (!c) return fail(MORLAX_ERR_HIP, "morlax_create: out of host memory");
     memset(c, 0, sizeof(*c));

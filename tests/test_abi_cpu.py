@@ -49,6 +49,8 @@ def test_layout_queries_match_oracle_and_generator(lib):
     (dict(width=40), binding.ERR_UNSUPPORTED), (dict(act=2), binding.ERR_UNSUPPORTED),
     (dict(wdtype=3), binding.ERR_UNSUPPORTED), (dict(rank=64), binding.ERR_UNSUPPORTED),
     (dict(hyper_width=128), binding.ERR_UNSUPPORTED), (dict(n_hidden=9), binding.ERR_UNSUPPORTED),
+    (dict(N=1 << 20, P=2, T=1023, obs_dim=1024), binding.ERR_UNSUPPORTED),      # observations beyond 32-bit offsets
+    (dict(N=1 << 16, P=2, T=16383, width=2048), binding.ERR_UNSUPPORTED),       # one preference's activations too
 ])
 def test_create_rejects_bad_dims(lib, over, code):
     d = configs.CONFIGS[1].dims_dict()

@@ -52,6 +52,10 @@ def binding():
 RAGGED = scaled(CONFIGS[1], name="ragged-K3-P3-N69-T7", K=3, P=3, N=69, T=7, obs_dim=11, act_dim=3, n_hidden=2,
                 width=48, act=1, rank=3, hyper_width=20)
 RAGGED_BF16 = scaled(RAGGED, name="ragged-bf16", wdtype=1, N=3 * 150, T=5, width=144)
+# enough tiles for the persistent GEMM kernel, with a cut last row tile (2016 rows per preference) and a cut
+# last column tile (width 160), and an observation width that takes the gathered first-layer path
+RAGGED_PERS = scaled(RAGGED, name="ragged-persistent-bf16", wdtype=1, P=32, N=32 * 126, T=16, width=160, obs_dim=32,
+                     rank=4)
 
 
 def all_cfgs():
@@ -549,7 +553,7 @@ def test_update_step_fp32_matches_oracle(cfg, torch, binding):
                 assert_close32(g[o:o + n] / scale, r / scale, f"{key}[{name}] mb {i}", rel=1e-3, abs_=1e-4)
 
 
-@pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), CONFIGS[3]],
+@pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), RAGGED_PERS, CONFIGS[3]],
                          ids=lambda c: c.name)
 def test_update_step_bf16_matches_oracle(cfg, torch, binding):
     say(f"update_step bf16 {cfg.name}")
