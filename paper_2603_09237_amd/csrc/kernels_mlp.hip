@@ -1620,10 +1620,16 @@ static int64_t act_elems(const morlax_ctx* c, const RowSel& rs) {
     return align_up((int64_t)c->d.P * rs.M * c->d.width, 64);
 }
 
+static int64_t x0_elems(const morlax_ctx* c, const RowSel& rs) {
+    return align_up((int64_t)c->d.P * rs.M * c->d.obs_dim, 64);
+}
+// compact first-layer input: bf16 networks whose observation width suits the direct-to-LDS GEMMs
+static bool use_x0(const morlax_ctx* c) { return c->d.wdtype == 1 && c->d.obs_dim % 32 == 0; }
+// saved: per hidden layer h and act', then the head's output rows, then (when used) the gathered observations
 int64_t mlp_saved_bytes(const morlax_ctx* c, int net, const RowSel& rs) {
     (void)net;
     return 2 * (int64_t)c->d.n_hidden * act_elems(c, rs) * esize(c) +
-           align_up((int64_t)c->d.P * rs.M * OUT_PITCH * 4, 256);
+           align_up((int64_t)c->d.P * rs.M * OUT_PITCH * 4, 256) + (use_x0(c) ? x0_elems(c, rs) * esize(c) : 0);
 }
 // fp32 scratch behind the two activation buffers: [0, head_lo): partial column sums of dZ, or the output
 // layer's dW partials followed by its bias partials; [head_lo, ..): the compact dz rows of the output layer
@@ -1637,11 +1643,6 @@ static int64_t head_lo_elems(const morlax_ctx* c, const RowSel& rs) {
 static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
     return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64);
 }
-static int64_t x0_elems(const morlax_ctx* c, const RowSel& rs) {
-    return align_up((int64_t)c->d.P * rs.M * c->d.obs_dim, 64);
-}
-// compact first-layer input: bf16 networks whose observation width suits the direct-to-LDS GEMMs
-static bool use_x0(const morlax_ctx* c) { return c->d.wdtype == 1 && c->d.obs_dim % 32 == 0; }
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
     return 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4 + (use_x0(c) ? x0_elems(c, rs) * esize(c) : 0);
 }
@@ -1679,7 +1680,9 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         ep.part = nullptr;
         if (l == 0 && use_x0(c)) {
             if constexpr (std::is_same<T, bf16_t>::value) {
-                T* x0 = reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
+                T* x0 = sv ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
+                                                  align_up((int64_t)P * M * OUT_PITCH * 4, 256))
+                           : reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
                 const int64_t pieces = (int64_t)M * (O / 8);
                 k_gather_x<T><<<dim3((unsigned)((pieces + 255) / 256), P), 256, 0, s>>>(x, x0, O, M, rm);
                 GemmArgs<T, SRC_KCONTIG, SRC_KCONTIG, EpiFwd<T, ACT, SAVE>, true, GEMM_NCH> g;
@@ -1785,9 +1788,9 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             n_part = h.tiles_m;  // row tiles of the kernel that ran (128 or 256 rows)
         } else if (use_x0(c)) {
             if constexpr (std::is_same<T, bf16_t>::value) {
-                T* x0 = reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
-                const int64_t pieces = (int64_t)M * (O / 8);
-                k_gather_x<T><<<dim3((unsigned)((pieces + 255) / 256), P), 256, 0, s>>>(x, x0, O, M, rm);
+                // the rows gathered by the forward pass
+                const T* x0 = reinterpret_cast<const T*>(reinterpret_cast<const char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
+                                                         align_up((int64_t)P * M * OUT_PITCH * 4, 256));
                 GemmArgs<T, SRC_KSTRIDED, SRC_KSTRIDED, EpiDw, true, GEMM_NCH> g;
                 g.a.base = dZbuf(0); g.a.ld = W; g.a.rows = W; g.a.kdim = M; g.a.rm = rm;
                 g.b.base = x0; g.b.ld = O; g.b.rows = O; g.b.kdim = M; g.b.rm = rm;
