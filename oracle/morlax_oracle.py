@@ -30,7 +30,8 @@ float64 torch.autograd and central finite differences for every gradient,
 library routines (torch linear/tanh/silu, torch Normal.log_prob) for the
 forward pieces, structural invariants for the hypernet, closed forms and
 torch.optim.Adam for the optimiser step, reduction to the untruncated recursion
-on a cut trajectory for the truncation mask.  Not pinned
+on a cut trajectory for the truncation mask, Kolmogorov-Smirnov tests against the Beta marginals
+of the uniform distribution on the simplex for the trade-off sampler.  Not pinned
 ("parity unpinned"): which of the readings above the authors' own code uses,
 because that code is not available.
 """
@@ -103,6 +104,26 @@ def env_pref_index(N, P):
         raise ValueError("need P > 1 and P | N")
     n_g = N // P
     return (np.arange(N, dtype=np.int64) // n_g).astype(np.int32)
+
+
+def sample_preferences(u, kappa=0):
+    """Trade-off vectors of one iteration (Sec. III-C, sampling phase): P - kappa draws from the
+    symmetric Dirichlet distribution with all concentrations 1, i.e. uniform on the simplex, and kappa
+    extreme points of the simplex.  u [P, K]: independent uniforms in (0, 1), supplied by the caller.
+    A Dirichlet(1, ..., 1) vector is a vector of independent unit exponentials divided by its sum, and
+    -ln(u) is a unit exponential, so w[p] = -ln(u[p]) / sum_k -ln(u[p, k]).  Reading taken for the
+    extremes: the last kappa rows are the unit vectors e_0, ..., e_{kappa-1} (kappa <= min(P, K));
+    their uniforms are ignored."""
+    u = np.asarray(u, dtype=np.float64)
+    P, K = u.shape
+    if not (0 <= kappa <= min(P, K)):
+        raise ValueError("kappa must lie in [0, min(P, K)]")
+    e = -np.log(u)
+    w = e / e.sum(axis=1, keepdims=True)
+    for i in range(kappa):
+        w[P - kappa + i] = 0.0
+        w[P - kappa + i, i] = 1.0
+    return w
 
 
 def check_preferences(w, tol=1e-6):

@@ -60,6 +60,39 @@ def test_adam_matches_torch_optim(betas, eps):
         assert np.allclose(th, p.detach().numpy(), rtol=1e-11, atol=1e-13), t
 
 
+@pytest.mark.parametrize("K", [2, 3, 6])
+def test_sampled_preferences_are_uniform_on_the_simplex(K):
+    """Every coordinate of a uniform point of the (K-1)-simplex is Beta(1, K-1) distributed, and for K = 3
+    the pair (w_0, w_1) is uniform on the triangle, so P(w_0 < a, w_1 < b) = 2ab for a + b <= 1."""
+    from scipy import stats
+    rng = np.random.default_rng(100 + K)
+    P = 20000
+    w = orc.sample_preferences(rng.random((P, K)))
+    assert (w >= 0).all() and np.allclose(w.sum(1), 1.0, rtol=0, atol=1e-12)
+    for k in range(K):
+        assert stats.kstest(w[:, k], stats.beta(1, K - 1).cdf).pvalue > 1e-3, k
+    # normalised uniforms (a plausible mistake) are not uniform on the simplex
+    bad = rng.random((P, K)); bad /= bad.sum(1, keepdims=True)
+    if K > 2:
+        assert stats.kstest(bad[:, 0], stats.beta(1, K - 1).cdf).pvalue < 1e-6
+    if K == 3:
+        for a, b in ((0.3, 0.4), (0.5, 0.5), (0.2, 0.7)):
+            frac = np.mean((w[:, 0] < a) & (w[:, 1] < b))
+            assert abs(frac - 2 * a * b) < 4 * np.sqrt(2 * a * b / P) + 1e-3
+
+
+def test_extreme_trade_offs_are_the_last_rows():
+    rng = np.random.default_rng(7)
+    u = rng.random((8, 3))
+    w0 = orc.sample_preferences(u, 0)
+    w2 = orc.sample_preferences(u, 2)
+    assert np.array_equal(w2[:6], w0[:6])
+    assert np.array_equal(w2[6], [1.0, 0.0, 0.0]) and np.array_equal(w2[7], [0.0, 1.0, 0.0])
+    assert orc.check_preferences(w2)
+    with pytest.raises(ValueError):
+        orc.sample_preferences(u, 4)
+
+
 def _rand(T=11, N=6, K=3, P=2, seed=0):
     rng = np.random.default_rng(seed)
     return (rng.standard_normal((T, N, K)), rng.standard_normal((T + 1, N, K)),
