@@ -152,6 +152,14 @@ int morlax_vec_gae_trunc(morlax_ctx* ctx, const float* r, const float* v, const 
                          const uint8_t* trunc, const float* w, float gamma, float lambda,
                          float* adv_vec, float* vtarg, float* adv_s, void* stream);
 
+/* Trade-off vectors of one iteration (Sec. III-C, sampling phase): P - kappa rows drawn from the
+ * symmetric Dirichlet distribution with all concentrations 1 (uniform on the simplex) and kappa
+ * extreme points.  u [P, K] (device): independent uniforms in (0, 1) supplied by the caller, so that
+ * the draw is reproducible; w [P, K] (device, overwritten): w[p] = -ln u[p] / sum_k -ln u[p, k] for
+ * p < P - kappa, and row P - kappa + i = unit vector e_i (reading taken for "the extreme endpoints
+ * within the simplex"; their uniforms are ignored).  MORLAX_ERR_SHAPE unless 0 <= kappa <= min(P, K). */
+int morlax_sample_preferences(morlax_ctx* ctx, const float* u, int32_t kappa, float* w, void* stream);
+
 /* One Adam step on the hypernet parameters of `net` (Sec. III-C, update phase: the two hypernets are
  * updated separately so that they can learn at different rates; the paper does not name the
  * optimiser, Adam with bias correction is the reading taken).  All arrays are device pointers to

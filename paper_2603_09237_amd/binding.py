@@ -37,7 +37,7 @@ EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hpara
            "morlax_theta_mat_len", "morlax_theta_vec_len", "morlax_saved_bytes", "morlax_workspace_bytes",
            "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
            "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
-           "morlax_ppo_loss_grad", "morlax_profile_begin", "morlax_profile_end")
+           "morlax_sample_preferences", "morlax_ppo_loss_grad", "morlax_profile_begin", "morlax_profile_end")
 
 GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first")
 
@@ -76,6 +76,7 @@ def load():
     lib.morlax_vec_gae.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
     lib.morlax_vec_gae_trunc.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
     lib.morlax_adam_step.argtypes = [vp, C.c_int, vp, vp, vp, vp, f32, f32, f32, f32, i32, vp]
+    lib.morlax_sample_preferences.argtypes = [vp, vp, i32, vp, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
                                          vp, vp, vp, vp, vp, vp]
     lib.morlax_profile_begin.argtypes = [vp]
@@ -84,7 +85,7 @@ def load():
     lib.morlax_profile_end.restype = C.c_int
     for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
                  "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
-                 "morlax_ppo_loss_grad"):
+                 "morlax_sample_preferences", "morlax_ppo_loss_grad"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -204,6 +205,10 @@ class Context:
         self._check(self.lib.morlax_vec_gae_trunc(self.h, _ptr(r), _ptr(v), _ptr(done), _ptr(trunc), _ptr(w),
                                                   float(gamma), float(lam), _ptr(adv_vec), _ptr(vtarg), _ptr(adv_s),
                                                   stream if stream is not None else _stream()))
+
+    def sample_preferences(self, u, kappa, w, stream=None):
+        self._check(self.lib.morlax_sample_preferences(self.h, _ptr(u), int(kappa), _ptr(w),
+                                                       stream if stream is not None else _stream()))
 
     def adam_step(self, net, hparams, dhparams, m, v, lr, beta1, beta2, eps, step, stream=None):
         self._check(self.lib.morlax_adam_step(self.h, net, _ptr(hparams), _ptr(dhparams), _ptr(m), _ptr(v),

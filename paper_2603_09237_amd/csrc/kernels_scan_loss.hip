@@ -345,3 +345,32 @@ void launch_adam_step(float* theta, const float* g, float* m, float* v, int64_t 
     const int64_t blocks = (n + 1023) / 1024;
     k_adam_step<<<(unsigned)blocks, 256, 0, s>>>(theta, g, m, v, n, lr, b1, b2, eps, c1, c2);
 }
+
+// ------------------------------------------------------------------------------------------------
+// Trade-off vectors of one iteration (Sec. III-C, sampling phase): P - kappa rows uniform on the simplex
+// (unit exponentials -ln u divided by their sum) and, in the last kappa rows, the unit vectors e_0 ..
+// e_{kappa-1}.  One thread per row; K <= 16.
+__global__ __launch_bounds__(256) void k_sample_preferences(const float* __restrict__ u, float* __restrict__ w,
+                                                           int P, int K, int kappa) {
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= P) return;
+    if (p >= P - kappa) {
+        for (int k = 0; k < K; ++k) w[p * K + k] = (k == p - (P - kappa)) ? 1.f : 0.f;
+        return;
+    }
+    float e[MORLAX_MAX_OUT];
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < MORLAX_MAX_OUT; ++k) {
+        e[k] = (k < K) ? -logf(u[p * K + k]) : 0.f;
+        sum += e[k];
+    }
+    const float inv = 1.f / sum;
+#pragma unroll
+    for (int k = 0; k < MORLAX_MAX_OUT; ++k)
+        if (k < K) w[p * K + k] = e[k] * inv;
+}
+
+void launch_sample_preferences(const morlax_ctx* c, const float* u, int kappa, float* w, hipStream_t s) {
+    k_sample_preferences<<<(c->d.P + 255) / 256, 256, 0, s>>>(u, w, c->d.P, c->d.K, kappa);
+}

@@ -303,6 +303,16 @@ extern "C" int morlax_vec_gae_trunc(morlax_ctx* ctx, const float* r, const float
     return finish(who);
 }
 
+extern "C" int morlax_sample_preferences(morlax_ctx* ctx, const float* u, int32_t kappa, float* w, void* stream) {
+    const char* who = "morlax_sample_preferences";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    REQ(u, who); REQ(w, who);
+    const int lim = ctx->d.P < ctx->d.K ? ctx->d.P : ctx->d.K;
+    if (kappa < 0 || kappa > lim) return fail(MORLAX_ERR_SHAPE, "%s: kappa must lie in [0, min(P, K)]", who);
+    launch_sample_preferences(ctx, u, kappa, w, (hipStream_t)stream);
+    return finish(who);
+}
+
 extern "C" int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const float* dhparams, float* m, float* v,
                                 float lr, float beta1, float beta2, float eps, int32_t step, void* stream) {
     const char* who = "morlax_adam_step";

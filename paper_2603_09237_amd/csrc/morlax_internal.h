@@ -68,6 +68,7 @@ void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s);
 void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const uint8_t* done,
                     const uint8_t* trunc, const float* w, float gamma, float lambda, float* adv_vec,
                     float* vtarg, float* adv_s, hipStream_t s);
+void launch_sample_preferences(const morlax_ctx* c, const float* u, int kappa, float* w, hipStream_t s);
 void launch_adam_step(float* theta, const float* g, float* m, float* v, int64_t n, float lr, float b1, float b2,
                       float eps, float c1, float c2, hipStream_t s);
 

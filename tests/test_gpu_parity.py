@@ -73,6 +73,27 @@ def test_env_pref_index_bit_exact(cfg, torch, binding):
     assert np.array_equal(out.cpu().numpy(), orc.env_pref_index(cfg.N, cfg.P))
 
 
+@pytest.mark.parametrize("cfg,kappa", [(CONFIGS[1], 0), (CONFIGS[1], 2), (RAGGED, 3), (CONFIGS[5], 6),
+                                       (scaled(CONFIGS[2], name="P1024", P=1024, N=4096), 1)],
+                         ids=lambda x: getattr(x, "name", str(x)))
+def test_sample_preferences_matches_oracle(cfg, kappa, torch, binding):
+    say(f"sample_preferences {cfg.name} kappa={kappa}")
+    rng = np.random.default_rng(77)
+    u = rng.random((cfg.P, cfg.K), dtype=np.float32)
+    u = np.clip(u, 1e-7, 1.0 - 1e-7).astype(np.float32)
+    ctx = binding.Context.from_config(cfg)
+    w = torch.full((cfg.P, cfg.K), 7.0, device="cuda")
+    ctx.sample_preferences(dev(u), kappa, w)
+    torch.cuda.synchronize()
+    got = to_np(w)
+    assert_close32(got, orc.sample_preferences(u, kappa), "w")
+    assert orc.check_preferences(got, tol=1e-5)
+    if kappa:                                         # the extreme points are exact
+        assert np.array_equal(got[cfg.P - kappa:], np.eye(cfg.K, dtype=np.float32)[:kappa])
+    with pytest.raises(binding.MorlaxError):
+        ctx.sample_preferences(dev(u), min(cfg.P, cfg.K) + 1, w)
+
+
 # ------------------------------------------------------------------------------------------------
 def run_gae(cfg, torch, binding, r, v, done, w, want_vec=True):
     ctx = binding.Context.from_config(cfg)
