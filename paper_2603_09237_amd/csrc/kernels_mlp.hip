@@ -837,15 +837,20 @@ __global__ __launch_bounds__(256) void k_gemm_dma(GemmArgs<bf16_t, KA, KB, Epi, 
 // ROWS / 8 chunks.
 #define PG_NST 3
 #define PG_A_BYTES 16384
-#define PG_B_BYTES 8192
-#define PG_STAGE_BYTES (PG_A_BYTES + PG_B_BYTES)
-#define PG_LDS_BYTES (PG_NST * PG_STAGE_BYTES)
 #define PG_TM 256
-#define PG_TN 128
+// TN = 128: four waves (2 x 2), two workgroups per CU.  TN = 256: eight waves (2 x 4), one workgroup per CU;
+// a third fewer operand bytes per product travel from the L2 into LDS.
+template <int TN> struct PgShape {
+    static constexpr int kWaves = TN / 32;                 // 128 x 64 outputs per wave
+    static constexpr int kBBytes = TN * 64;
+    static constexpr int kStage = PG_A_BYTES + kBBytes;
+    static constexpr int kLds = PG_NST * kStage;
+    static constexpr int kLoads = (PG_A_BYTES + kBBytes) / 1024 / kWaves;  // DMA instructions per wave and stage
+};
 
-template <int KIND, int ROWS, int MBLK>
+template <int KIND, int ROWS, int MBLK, int NW>
 struct DmaTile {
-    static constexpr int NI = ROWS / 64;   // DMA instructions per wave and stage
+    static constexpr int NI = ROWS / 16 / NW;  // DMA instructions per wave and stage
     static constexpr int CPR = ROWS / 8;   // chunks per contraction index (K-strided layout)
     const char* base;
     uint32_t voff[NI];
@@ -909,8 +914,9 @@ struct DmaTile {
     }
 };
 
-// Epilogue of a 128 x 64 wave tile.  `lds_free` is LDS no load is in flight to (at least 16 KB + 1 KB).
-template <class Epi, int MB>
+// Epilogue of a 128 x 64 wave tile.  `lds_free` is LDS no load is in flight to (4 KB per wave, or 1 KB
+// for the column sums).
+template <class Epi, int MB, int TN>
 __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], unsigned char* lds_free,
                                      const float* lds_bias, const uint4 (&first)[4], int p, int tm, int tiles_m,
                                      int r0, int c0, int rows, int cols, int wm, int wn) {
@@ -1033,24 +1039,25 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
             red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
         }
         __syncthreads();
-        if (threadIdx.x < 128) {
-            const int wsel = threadIdx.x >> 6, col = threadIdx.x & 63;
-            const float v = red[wsel * 64 + col] + red[(2 + wsel) * 64 + col];
+        if (threadIdx.x < TN) {  // the two waves of a 64-column strip: wave ids s and s + TN / 64
+            const int strip = threadIdx.x >> 6, col = threadIdx.x & 63;
+            const float v = red[strip * 64 + col] + red[(TN / 64 + strip) * 64 + col];
             if (c0 + threadIdx.x < cols) epi.part[((int64_t)p * tiles_m + tm) * epi.ld + c0 + threadIdx.x] = v;
         }
     }
 }
 
-template <int KA, int KB, class Epi>
-__global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, Epi, true, GEMM_NCH> g, int n_tiles) {
+template <int KA, int KB, class Epi, int TN>
+__global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, Epi, true, GEMM_NCH> g, int n_tiles) {
+    typedef PgShape<TN> S;
     extern __shared__ __align__(16) unsigned char dlds[];
     const int wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 64;
+    const int wm = (wave / (TN / 64)) * 128, wn = (wave % (TN / 64)) * 64;
     const int per_p = g.tiles_m * g.tiles_n;
     const int nk = g.a.kdim / 32;
     const uint32_t lbase = (uint32_t)(size_t)dlds;
-    DmaTile<KA, PG_TM, 4> A;
-    DmaTile<KB, PG_TN, 2> B;
+    DmaTile<KA, PG_TM, 4, S::kWaves> A;
+    DmaTile<KB, TN, 2, S::kWaves> B;
     A.set_lane(wm, false);
     B.set_lane(wn, true);
 
@@ -1066,20 +1073,20 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, E
     auto request = [&](int p, int tm, int tn) {  // first stages of a tile (and its bias slice)
         if constexpr (Epi::kBias) {
             bslot ^= 1;
-            if (wave < 2) {
-                int c = tn * PG_TN + 64 * wave + (threadIdx.x & 63);
+            if (wave < TN / 64) {
+                int c = tn * TN + 64 * wave + (threadIdx.x & 63);
                 c = c < g.b.rows ? c : g.b.rows - 1;
                 dma4(g.epi.bias + (int64_t)p * g.e0_pstride, (uint32_t)c * 4u,
-                     __builtin_amdgcn_readfirstlane(lbase + PG_LDS_BYTES + (uint32_t)(bslot * 512 + wave * 256)));
+                     __builtin_amdgcn_readfirstlane(lbase + S::kLds + (uint32_t)(bslot * (4 * TN) + wave * 256)));
             }
         }
         A.set_tile(reinterpret_cast<const bf16_t*>(g.a.base) + (int64_t)p * g.a_pstride, (int)g.a.ld, g.a.rows, tm * PG_TM);
-        B.set_tile(reinterpret_cast<const bf16_t*>(g.b.base) + (int64_t)p * g.b_pstride, (int)g.b.ld, g.b.rows, tn * PG_TN);
+        B.set_tile(reinterpret_cast<const bf16_t*>(g.b.base) + (int64_t)p * g.b_pstride, (int)g.b.ld, g.b.rows, tn * TN);
 #pragma unroll
         for (int st = 0; st < PG_NST - 1; ++st)
             if (st < nk) {
-                A.issue(st, lbase + st * PG_STAGE_BYTES);
-                B.issue(st, lbase + st * PG_STAGE_BYTES + PG_A_BYTES);
+                A.issue(st, lbase + st * S::kStage);
+                B.issue(st, lbase + st * S::kStage + PG_A_BYTES);
             }
     };
 
@@ -1097,17 +1104,17 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, E
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
         for (int kt = 0; kt < nk; ++kt) {
-            // a wave has 6 loads per stage in flight.  At the first step of a tile the stores of the
+            // a wave has kLoads loads per stage in flight.  At the first step of a tile the stores of the
             // previous epilogue may still be counted as well, so everything is waited for.
             if (kt == 0 || kt == nk - 1) wait_vm<0>();
-            else wait_vm<6>();
+            else wait_vm<S::kLoads>();
             __syncthreads();  // stage kt is complete, and stage kt - 1 (or the last epilogue's patch) is free
             if (kt + PG_NST - 1 < nk) {
-                const uint32_t tile = lbase + (uint32_t)((kt + PG_NST - 1) % PG_NST) * PG_STAGE_BYTES;
+                const uint32_t tile = lbase + (uint32_t)((kt + PG_NST - 1) % PG_NST) * S::kStage;
                 A.issue(kt + PG_NST - 1, tile);
                 B.issue(kt + PG_NST - 1, tile + PG_A_BYTES);
             }
-            const unsigned char* ta = dlds + (kt % PG_NST) * PG_STAGE_BYTES;
+            const unsigned char* ta = dlds + (kt % PG_NST) * S::kStage;
             const unsigned char* tb = ta + PG_A_BYTES;
             // all fragments of the stage are requested before the first product, so that one LDS latency is
             // exposed per step instead of one per pair of products
@@ -1131,7 +1138,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, E
         }
         __syncthreads();  // every wave is done with the stages
         const int pc = p, tmc = tm, tnc = tn;
-        const float* lds_bias = reinterpret_cast<const float*>(dlds + PG_LDS_BYTES + bslot * 512);
+        const float* lds_bias = reinterpret_cast<const float*>(dlds + S::kLds + bslot * (4 * TN));
         Epi epi = g.epi;
         shift_epi(epi, pc, g.e0_pstride, g.e1_pstride, g.e2_pstride);
         uint4 first[4] = {};
@@ -1140,7 +1147,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, E
             const int r = tmc * PG_TM + wm + (threadIdx.x & 31), rc = r < g.a.rows ? r : g.a.rows - 1;
 #pragma unroll
             for (int o = 0; o < 4; ++o) {
-                const int c = tnc * PG_TN + wn + 16 * o + 8 * ((threadIdx.x & 63) >> 5);
+                const int c = tnc * TN + wn + 16 * o + 8 * ((threadIdx.x & 63) >> 5);
                 first[o] = epi.fetch(rc, c < g.b.rows ? c : 0);
             }
         }
@@ -1150,7 +1157,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB, E
             locate(vid, p, tm, tn);
             request(p, tm, tn);  // stages 0 and 1; the epilogue below stages its stores in the third
         }
-        tile_epilogue<Epi, 4>(epi, acc, dlds + (PG_NST - 1) * PG_STAGE_BYTES, lds_bias, first, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * PG_TN,
+        tile_epilogue<Epi, 4, TN>(epi, acc, dlds + (PG_NST - 1) * S::kStage, lds_bias, first, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * TN,
                               g.a.rows, g.b.rows, wm, wn);
         if (!more) break;
     }
@@ -1237,23 +1244,38 @@ static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, int nb, hi
         if (g.a.kdim < 32 || (g.a.kdim & 31)) return false;
         if (!dma_operand_ok<KA>(g.a.base, g.a.ld, g.a.rows, g.a.kdim, g.a_pstride)) return false;
         if (!dma_operand_ok<KB>(g.b.base, g.b.ld, g.b.rows, g.b.kdim, g.b_pstride)) return false;
-        // large problems: persistent 256 x 128 tiles, as soon as they fill the resident workgroups
-        const int ptm = (g.a.rows + PG_TM - 1) / PG_TM, ptn = (g.b.rows + PG_TN - 1) / PG_TN;
-        const int pnt = ptm * ptn * P;
+        // large problems: persistent kernel, 256 x 256 tiles (one workgroup of eight waves per CU) when the
+        // output is at least that wide and there is a tile for every CU, else 256 x 128 tiles (two workgroups
+        // of four waves per CU) as soon as those fill the resident workgroups
         static const bool pers_on = !getenv("MORLAX_NO_PERS");
-        if (pers_on && pnt >= resident_slots() && g.a.rows >= 64) {
+        static const bool wide_on = !getenv("MORLAX_NO_WIDE");
+        const int ptm = (g.a.rows + PG_TM - 1) / PG_TM;
+        auto launch_pers = [&](auto tn_tag, int slots) {
+            constexpr int TN = decltype(tn_tag)::value;
+            const int ptn = (g.b.rows + TN - 1) / TN, pnt = ptm * ptn * P;
             static bool pattr_set = false;
-            constexpr int plds = PG_LDS_BYTES + 1024;
+            constexpr int plds = PgShape<TN>::kLds + 8 * TN;
             if (!pattr_set) {
-                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_pers<KA, KB, Epi>),
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_pers<KA, KB, Epi, TN>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, plds);
                 pattr_set = true;
             }
             g.tiles_m = ptm;
             g.tiles_n = ptn;
-            const int grid = pnt < resident_slots() ? pnt : resident_slots();
-            k_gemm_pers<KA, KB, Epi><<<grid, 256, plds, s>>>(g, pnt);
-            return true;
+            const int grid = pnt < slots ? pnt : slots;
+            k_gemm_pers<KA, KB, Epi, TN><<<grid, 2 * TN, plds, s>>>(g, pnt);
+        };
+        if (pers_on && g.a.rows >= 64) {
+            const int slots = resident_slots();
+            // (with fewer than four wide tiles per workgroup the narrow shape measured faster: dW at W = 512)
+            if (wide_on && g.b.rows >= 256 && ptm * ((g.b.rows + 255) / 256) * P >= 4 * (slots / 2)) {
+                launch_pers(std::integral_constant<int, 256>{}, slots / 2);
+                return true;
+            }
+            if (ptm * ((g.b.rows + 127) / 128) * P >= slots) {
+                launch_pers(std::integral_constant<int, 128>{}, slots);
+                return true;
+            }
         }
         static bool attr_set = false;
         constexpr int lds_bytes = DMA_NST * DMA_STAGE_BYTES;
