@@ -347,6 +347,7 @@ struct EpiFwd {  // h = act(z + b) and, when SAVE, act'(z); compact [M][ld] stor
     }
     // row-contiguous stores through an LDS patch (see the kernel): arrays, element size, row-0 address
     static constexpr bool kStage = true;
+    static constexpr bool kStagePers = true;
     static constexpr int kArrays = SAVE ? 2 : 1;
     static constexpr int kES = (int)sizeof(T);
     __device__ inline char* arr(int a) const { return a == 0 ? reinterpret_cast<char*>(H) : reinterpret_cast<char*>(G); }
@@ -382,7 +383,8 @@ struct EpiDx {  // dZ_{l-1} = (dZ_l W_l) * act'(z_{l-1})
         for (int i = 0; i < 8; ++i) v[i] *= g[i];
         o.d = pack8(v, (const T*)nullptr);
     }
-    static constexpr bool kStage = false;  // direct 16-byte stores measured faster here
+    static constexpr bool kStage = false;  // direct 16-byte stores measured faster in the 128 x 128 kernels,
+    static constexpr bool kStagePers = true;  // row-contiguous staged stores in the persistent one
     static constexpr bool kBias = false;
     static constexpr int kArrays = 1;
     static constexpr int kES = (int)sizeof(T);
@@ -411,6 +413,7 @@ struct EpiDw {  // dW_l(p)[o, i]
         }
     }
     static constexpr bool kStage = false;
+    static constexpr bool kStagePers = false;
     static constexpr bool kBias = false;
     static constexpr bool kPrefetch = false;
     static constexpr int kArrays = 1;
@@ -914,13 +917,14 @@ struct DmaTile {
     }
 };
 
-// Epilogue of a 128 x 64 wave tile.  `lds_free` is LDS no load is in flight to (4 KB per wave, or 1 KB
-// for the column sums).
+// Epilogue of a 128 x 64 wave tile.  `lds_free` is LDS no load is in flight to (4 KB per wave) for the
+// staged stores; `red` (64 floats per wave) takes the column sums and is the space of the bias slices, which
+// an epilogue with column sums does not use.
 template <class Epi, int MB, int TN>
 __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], unsigned char* lds_free,
-                                     const float* lds_bias, const uint4 (&first)[4], int p, int tm, int tiles_m,
-                                     int r0, int c0, int rows, int cols, int wm, int wn) {
-    static_assert(!(Epi::kStage && Epi::kColSum), "the staged stores and the column sums share LDS");
+                                     const float* lds_bias, float* red, const uint4 (&first)[4], int p, int tm,
+                                     int tiles_m, int r0, int c0, int rows, int cols, int wm, int wn) {
+    static_assert(!(Epi::kBias && Epi::kColSum), "the bias slice and the column sums share LDS");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane & 31, lg = lane >> 5;
     float cs[Epi::kColSum ? 32 : 1];
@@ -934,9 +938,20 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
     for (int i = 0; i < MB; ++i) {
         const int r = r0 + wm + 32 * i + lr;
         const int rc = r < rows ? r : rows - 1;
-        if (Epi::kStage) {
-            static_assert(!Epi::kStage || Epi::kES == 2, "staged stores are for 2-byte outputs");
+        if (Epi::kStagePers) {
+            static_assert(!Epi::kStagePers || Epi::kES == 2, "staged stores are for 2-byte outputs");
             uint4 second[4];
+            uint4 nxt[4];
+            if constexpr (Epi::kPrefetch) {  // operands of block i + 1 are requested before block i is worked on
+                if (i + 1 < MB) {
+                    const int rn = r0 + wm + 32 * (i + 1) + lr, rnc = rn < rows ? rn : rows - 1;
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        const int c = c0 + wn + 16 * o + 8 * lg;
+                        nxt[o] = epi.fetch(rnc, c < cols ? c : 0);
+                    }
+                }
+            }
 #pragma unroll
             for (int o = 0; o < 4; ++o) {
                 const int j = o >> 1, h = o & 1;
@@ -952,8 +967,18 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
                     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
                     v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
                     epi.compute_biased(v, out);
+                } else if constexpr (Epi::kPrefetch) {
+                    epi.compute_fetched(cur[o], v, out);
                 } else {
                     epi.compute(rc, c < cols ? c : 0, 8, v, out);
+                }
+                if (Epi::kColSum) {
+                    const bool ok = (r < rows) && (c < cols);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int t = Epi::kColSum ? (8 * o + u) : 0;
+                        cs[t] = (i == 0 ? 0.f : cs[t]) + (ok ? v[u] : 0.f);
+                    }
                 }
                 const int cch = 4 * j + 2 * h + lg;
                 *reinterpret_cast<uint4*>(patch + lr * 128 + ((cch ^ (lr & 7)) * 16)) = Epi::pk(out, 0).lo;
@@ -980,6 +1005,10 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
                 }
             }
             __builtin_amdgcn_wave_barrier();
+            if constexpr (Epi::kPrefetch) {
+#pragma unroll
+                for (int o = 0; o < 4; ++o) cur[o] = nxt[o];
+            }
         } else {
             // `first` holds the prefetched operands of block 0 (four octets per lane); those of block
             // i + 1 are requested before block i is worked on
@@ -1033,7 +1062,6 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
         fold_slots<4>(cs, lr);
         fold_slots<2>(cs, lr);
         fold_slots<1>(cs, lr);
-        float* red = reinterpret_cast<float*>(lds_free);
         {
             const int j = lr >> 4, h = (lr >> 3) & 1, u = lr & 7;
             red[wave * 64 + 32 * j + 16 * h + 8 * lg + u] = cs[0];
@@ -1157,7 +1185,8 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
             locate(vid, p, tm, tn);
             request(p, tm, tn);  // stages 0 and 1; the epilogue below stages its stores in the third
         }
-        tile_epilogue<Epi, 4, TN>(epi, acc, dlds + (PG_NST - 1) * S::kStage, lds_bias, first, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * TN,
+        tile_epilogue<Epi, 4, TN>(epi, acc, dlds + (PG_NST - 1) * S::kStage, lds_bias,
+                                  reinterpret_cast<float*>(dlds + S::kLds), first, pc, tmc, g.tiles_m, tmc * PG_TM, tnc * TN,
                               g.a.rows, g.b.rows, wm, wn);
         if (!more) break;
     }
