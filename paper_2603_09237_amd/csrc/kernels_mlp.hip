@@ -830,14 +830,13 @@ __global__ __launch_bounds__(256) void k_gemm_dma(GemmArgs<bf16_t, KA, KB, Epi, 
     gemm_epilogue(epi, acc, dlds, p, tm, g.tiles_m, r0, c0, g.a.rows, g.b.rows);
 }
 
-// ---- persistent bf16 grouped GEMM, 256 x 128 tiles -----------------------------------------------
-// Two workgroups per CU stay resident and walk over the tiles; a wave owns 128 x 64 outputs (4 x 2
-// blocks of 32 x 32, 128 accumulator registers), which halves the LDS bytes read per product against
-// the 64 x 64 wave tiles above.  Operand stages (A 16 KB, B 8 KB) are filled by direct-to-LDS loads
-// two contraction steps ahead, and the first two stages of a workgroup's next tile are requested
-// before the epilogue of the current one, so that their latency is covered by the epilogue's
-// arithmetic.  The layouts inside a stage follow DmaOperand; a row of a K-strided tile now has
-// ROWS / 8 chunks.
+// ---- persistent bf16 grouped GEMM, 256 x TN tiles -----------------------------------------------
+// Resident workgroups walk over the tiles; a wave owns 128 x 64 outputs (4 x 2 blocks of 32 x 32, 128
+// accumulator registers), which reads three quarters of the LDS bytes per product that the 64 x 64 wave
+// tiles above read.  Operand stages (A 16 KB, B TN * 64 bytes) are filled by direct-to-LDS loads two
+// contraction steps ahead, and the first two stages of a workgroup's next tile are requested before the
+// epilogue of the current one, so that their latency is covered by the epilogue's arithmetic.  The
+// layouts inside a stage follow DmaOperand; a row of a K-strided tile has ROWS / 8 chunks.
 #define PG_NST 3
 #define PG_A_BYTES 16384
 #define PG_TM 256
@@ -961,7 +960,7 @@ __device__ inline void tile_epilogue(const Epi& epi, float16_t (&acc)[MB][2], un
                 for (int u = 0; u < 8; ++u) v[u] = acc[i][j][8 * h + u];
                 typename Epi::Out out;
                 if constexpr (Epi::kBias) {
-                    // lds_bias holds the bias of the tile's 128 columns (clamped at the matrix edge)
+                    // lds_bias holds the bias of the tile's columns (clamped at the matrix edge)
                     const float4 b0 = *reinterpret_cast<const float4*>(lds_bias + wn + 32 * j + 16 * h + 8 * lg);
                     const float4 b1 = *reinterpret_cast<const float4*>(lds_bias + wn + 32 * j + 16 * h + 8 * lg + 4);
                     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
@@ -1276,8 +1275,6 @@ static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, int nb, hi
         // large problems: persistent kernel, 256 x 256 tiles (one workgroup of eight waves per CU) when the
         // output is at least that wide and there is a tile for every CU, else 256 x 128 tiles (two workgroups
         // of four waves per CU) as soon as those fill the resident workgroups
-        static const bool pers_on = !getenv("MORLAX_NO_PERS");
-        static const bool wide_on = !getenv("MORLAX_NO_WIDE");
         const int ptm = (g.a.rows + PG_TM - 1) / PG_TM;
         auto launch_pers = [&](auto tn_tag, int slots) {
             constexpr int TN = decltype(tn_tag)::value;
@@ -1294,10 +1291,10 @@ static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, int nb, hi
             const int grid = pnt < slots ? pnt : slots;
             k_gemm_pers<KA, KB, Epi, TN><<<grid, 2 * TN, plds, s>>>(g, pnt);
         };
-        if (pers_on && g.a.rows >= 64) {
+        if (g.a.rows >= 64) {
             const int slots = resident_slots();
             // (with fewer than four wide tiles per workgroup the narrow shape measured faster: dW at W = 512)
-            if (wide_on && g.b.rows >= 256 && ptm * ((g.b.rows + 255) / 256) * P >= 4 * (slots / 2)) {
+            if (g.b.rows >= 256 && ptm * ((g.b.rows + 255) / 256) * P >= 4 * (slots / 2)) {
                 launch_pers(std::integral_constant<int, 256>{}, slots / 2);
                 return true;
             }
