@@ -127,10 +127,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+    ap.add_argument("--streams", default="1", choices=("1", "2", "side"),
                     help="1 (default): every launch on one stream, so that the per-kernel durations behind `roofline` are "
-                         "those of kernels running alone; 2: actor and critic chains on their own HIP streams (faster "
-                         "step, but concurrent kernels stretch each other's durations)")
+                         "those of kernels running alone; side: the hypernet calls on a second stream next to the grouped "
+                         "GEMMs, which stay on the main stream; 2: actor and critic chains on their own streams (two GEMMs "
+                         "in flight stretch each other's event-timed durations)")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
     ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc"), default="update_step",
@@ -156,7 +157,7 @@ def main():
         bench_kernel(a, cfg)
         return
     opt = dict(lr_actor=3e-4, lr_critic=1e-3, beta1=0.9, beta2=0.999, eps=1e-8) if a.with_optimizer else None
-    st = UpdateStep(cfg, two_streams=(a.streams == 2), optimizer=opt)
+    st = UpdateStep(cfg, two_streams=(a.streams == "2"), side_hypernet=(a.streams == "side"), optimizer=opt)
     st.load_inputs(inputs.make_all(cfg))
     torch.cuda.synchronize()
     for _ in range(a.warmup):

@@ -17,9 +17,12 @@ from .configs import Config, WDTYPE_BF16
 
 class UpdateStep:
     def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False, two_streams: bool = False,
-                 optimizer: dict | None = None):
+                 optimizer: dict | None = None, side_hypernet: bool = False):
         """optimizer = dict(lr_actor, lr_critic, beta1, beta2, eps): take one Adam step on either hypernet
-        after every minibatch (a true PPO update); None: gradients only, parameters stay fixed."""
+        after every minibatch (a true PPO update); None: gradients only, parameters stay fixed.
+        side_hypernet: the hypernet calls (backward, optimiser step, the next minibatch's forward) run on a second
+        stream next to the grouped GEMMs of the other network / the next minibatch; the GEMM chain stays on the
+        caller's stream.  two_streams: the older split, one stream per network family."""
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -71,6 +74,8 @@ class UpdateStep:
                     for net in (ACTOR, CRITIC)}
         self.ws = self.wsn[ACTOR]
         self.streams = {net: torch.cuda.Stream(device=self.dev) for net in (ACTOR, CRITIC)} if two_streams else None
+        self.side = torch.cuda.Stream(device=self.dev) if side_hypernet else None
+        self.ws_side = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device=self.dev) if side_hypernet else None
         self.optimizer = optimizer
         self.opt_step = 0
         if optimizer is not None:
@@ -152,9 +157,85 @@ class UpdateStep:
 
     def run(self, on_minibatch=None):
         """One whole update step.  `on_minibatch(e, b)` (optional) is called after each minibatch."""
+        if self.side is not None:
+            return self._run_side(on_minibatch)
         self.rollout()
         for e in range(self.cfg.epochs):
             for b, rows in enumerate(self.mb_rows):
                 self.minibatch(rows)
                 if on_minibatch is not None:
                     on_minibatch(e, b)
+
+    def _run_side(self, on_minibatch):
+        """The same calls with the hypernet work of one network overlapping the grouped GEMMs of the other:
+        main stream = rollout, grouped forward / loss / grouped backward; side stream = hypernet backward,
+        optimiser step and the hypernet forward of the next minibatch.  Events order every buffer hand-over:
+        theta(net) is rewritten only after the main stream's last reader (grouped backward of net), dtheta(net)
+        only after the side stream's hypernet backward has read it."""
+        t, c, ctx = self.torch, self.cfg, self.ctx
+        main, side = t.cuda.current_stream(), self.side
+        nets = (ACTOR, CRITIC)
+        out = {ACTOR: self.mu, CRITIC: self.v}
+        dout = {ACTOR: self.dmu, CRITIC: self.dv}
+        o = self.optimizer
+        theta_ready = {n: t.cuda.Event() for n in nets}
+        theta_free = {n: t.cuda.Event() for n in nets}
+        dtheta_ready = {n: t.cuda.Event() for n in nets}
+        dtheta_free = {n: None for n in nets}
+
+        # rollout on the main stream; theta(net) is free for the update-time parameters after its forward
+        for net in nets:
+            ctx.hypernet_fwd(net, self.hp_old[net], self.w, self.theta_mat[net], self.theta_vec[net], self.wsn[net])
+        ctx.policy_fwd(ACTOR, self.theta_mat[ACTOR], self.theta_vec[ACTOR], self.obs, self.full_T, self.mu_old,
+                       eps=self.eps, act=self.act, logp=self.logp_old, saved=None, ws=self.ws)
+        theta_free[ACTOR].record(main)
+        ctx.policy_fwd(CRITIC, self.theta_mat[CRITIC], self.theta_vec[CRITIC], self.obs, self.full_T1, self.v_roll,
+                       saved=None, ws=self.ws)
+        theta_free[CRITIC].record(main)
+        with t.cuda.stream(side):
+            for net in nets:
+                side.wait_event(theta_free[net])
+                ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], self.ws_side)
+                theta_ready[net].record(side)
+        ctx.vec_gae(self.rewards, self.v_roll, self.dones, self.w, c.gamma, c.lam, self.adv_vec, self.vtarg,
+                    self.adv_s)
+
+        steps = [(e, b) for e in range(c.epochs) for b in range(len(self.mb_rows))]
+        for i, (e, b) in enumerate(steps):
+            rows = self.mb_rows[b]
+            last = i + 1 == len(steps)
+            if o is not None:
+                self.opt_step += 1
+            for net in nets:
+                main.wait_event(theta_ready[net])
+                ctx.policy_fwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, out[net],
+                               saved=self.saved[net], ws=self.ws)
+            logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
+            ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, self.adv_s,
+                              self.v, self.vtarg, c.clip_eps, 1, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
+            for net in nets:
+                if dtheta_free[net] is not None:
+                    main.wait_event(dtheta_free[net])
+                ctx.policy_bwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, self.saved[net], dout[net],
+                               self.dlogsig if net == ACTOR else None, self.dtheta_mat[net], self.dtheta_vec[net],
+                               self.ws)
+                dtheta_ready[net].record(main)
+                with t.cuda.stream(side):
+                    side.wait_event(dtheta_ready[net])
+                    ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net],
+                                     self.dhp[net], self.ws_side)
+                    dtheta_free[net] = t.cuda.Event()
+                    dtheta_free[net].record(side)
+                    if o is not None:
+                        ctx.adam_step(net, self.hp[net], self.dhp[net], self.adam_m[net], self.adam_v[net],
+                                      o["lr_actor"] if net == ACTOR else o["lr_critic"], o["beta1"], o["beta2"],
+                                      o["eps"], self.opt_step)
+                    if not last:
+                        ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net],
+                                         self.ws_side)
+                        theta_ready[net] = t.cuda.Event()
+                        theta_ready[net].record(side)
+            if on_minibatch is not None:
+                main.wait_stream(side)
+                on_minibatch(e, b)
+        main.wait_stream(side)

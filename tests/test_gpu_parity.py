@@ -490,13 +490,16 @@ def test_adam_step_matches_oracle(cfg, n_steps, torch, binding):
         assert np.abs(to_np(d_th) - th).max() > 0.5 * lr
 
 
-def test_update_step_with_optimizer_matches_oracle(torch, binding):
-    """A true PPO update: each minibatch is followed by an Adam step with a learning rate per hypernet."""
+@pytest.mark.parametrize("schedule", ["serial", "side_hypernet", "two_streams"])
+def test_update_step_with_optimizer_matches_oracle(schedule, torch, binding):
+    """A true PPO update: each minibatch is followed by an Adam step with a learning rate per hypernet.  The
+    stream schedules only reorder independent launches, so each must reach the same parameters."""
     from paper_2603_09237_amd.step import UpdateStep
     cfg = scaled(CONFIGS[1], name="cfg1-adam", minibatches=2, epochs=2)
-    say(f"update_step + adam {cfg.name}")
+    say(f"update_step + adam {cfg.name} {schedule}")
     opt = dict(lr_actor=3e-3, lr_critic=1e-2, beta1=0.9, beta2=0.999, eps=1e-8)
-    st = UpdateStep(cfg, optimizer=opt)
+    st = UpdateStep(cfg, optimizer=opt, side_hypernet=(schedule == "side_hypernet"),
+                    two_streams=(schedule == "two_streams"))
     d = inputs.make_all(cfg)
     st.load_inputs(d)
     st.run()
