@@ -30,6 +30,7 @@ KERNEL_OF_KIND = {
     "dx_hidden": "k_gemm_pers<SRC_KCONTIG, SRC_KSTRIDED, EpiDx> dX, W x W layers",
     "dw_hidden": "k_gemm_pers<SRC_KSTRIDED, SRC_KSTRIDED, EpiDw> dW, W x W layers",
     "dw_first": "k_grouped_gemm<SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw> dW, first layer",
+    "fwd_fused": "k_mlp_fused_fwd: first layer and all W x W layers of a 128-row tile in one launch (rollout + update)",
 }
 
 # HBM bytes per launch of a GEMM launch kind, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script scaled by

@@ -193,9 +193,10 @@ int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* 
  * by a pair of HIP events recorded on the launch stream.  morlax_profile_end() waits for the last
  * event (it synchronises with the stream) and returns, per GEMM kind k in
  * {0 forward first layer, 1 forward hidden layer, 2 dX hidden layer, 3 dW hidden layer, 4 dW first
- * layer}: ms[k] total kernel time, launches[k], flops[k] total algorithmic flops (2 * rows * cols *
- * depth summed over preferences; tile padding not counted).  The three arrays are HOST pointers of
- * length 5.  Profiling stops at morlax_profile_end(). */
+ * layer, 5 fused forward of all hidden layers in one launch}: ms[k] total kernel time, launches[k],
+ * flops[k] total algorithmic flops (2 * rows * cols * depth summed over layers and preferences; tile
+ * padding not counted).  The three arrays are HOST pointers of length 6.  Profiling stops at
+ * morlax_profile_end(). */
 int morlax_profile_begin(morlax_ctx* ctx);
 int morlax_profile_end(morlax_ctx* ctx, double* ms, int64_t* launches, double* flops);
 

@@ -39,7 +39,7 @@ EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hpara
            "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
            "morlax_sample_preferences", "morlax_ppo_loss_grad", "morlax_profile_begin", "morlax_profile_end")
 
-GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first")
+GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first", "fwd_fused")
 
 
 def load():

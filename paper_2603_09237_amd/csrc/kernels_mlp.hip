@@ -12,6 +12,7 @@
 // axis in memory (W in the dX product, both operands of the dW product) are transposed on the way
 // into LDS.  The skinny output layer (<= 16 columns) uses 16x16 MFMA tiles straight from global
 // memory in the forward pass and plain vector code in the backward pass.
+#include <cstdlib>
 #include <type_traits>
 
 #include "morlax_internal.h"
@@ -244,6 +245,24 @@ template <> struct Mma32<float> {
     }
 };
 
+template <typename T> struct Mma16;
+template <> struct Mma16<bf16_t> {
+    static __device__ inline void run(const uint4& a, const uint4& b, float4_t& c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                    0, 0, 0);
+    }
+};
+template <> struct Mma16<float> {
+    static __device__ inline void run(const uint4& a, const uint4& b, float4_t& c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+// out = head(h W_L(p)^T + b_L(p)); actor: optional sampling a = mu + sigma eps and its log-density.
+// A wave owns 16 rows; lane (row = lane % 16, chunk = lane / 16) feeds 16x16 MFMA tiles from global.
 // h = act(z) and g = act'(z).  SiLU uses the hardware exp2 / reciprocal approximations (about 1 ulp
 // each): s = 1 / (1 + e^-z), h = z s, g = s (1 + z - h).  tanh keeps the library routine.
 template <int ACT>
@@ -1191,6 +1210,270 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
     }
 }
 
+// ---- fused forward of all hidden layers (bf16, width 512) ----------------------------------------
+// One workgroup of eight waves carries 128 rows of one preference through every hidden layer.  The
+// activations of the tile live in LDS (128 rows x 1 KB, 16-byte chunks XOR-swizzled by the row) and are
+// rewritten in place layer after layer; HBM sees the gathered observations once and, in the saving
+// variant, the stores of h and act'(z) that the backward pass reads -- never a load of an activation.
+// Wave w owns output features [64 w, 64 w + 64) of every layer for all 128 rows: its slice of W_l(p) is
+// used by no other wave, so the W fragments go from global memory (L2) straight into registers, 64
+// contiguous bytes per lane and 64 contraction steps ("super-step"), one super-step ahead of their use.
+// Inside a super-step lane group g of product jj covers contraction indices 64 s + 32 g + 8 jj .. + 8 for
+// both operands.  The bias enters as the initial value of the accumulators.
+#define FF_ROWS 128
+#define FF_W 512
+#define FF_ACT_BYTES (FF_ROWS * FF_W * 2)
+
+struct FusedFwdArgs {
+    const bf16_t* x0;         // gathered observations, compact [P][M][O]
+    const bf16_t* theta_mat;  // [P][mat_len]
+    const float* theta_vec;   // [P][vec_len]
+    int64_t mat_len, vec_len;
+    int64_t mat_off[MORLAX_MAX_LAYERS], vec_off[MORLAX_MAX_LAYERS];
+    bf16_t* H;    // saving: h of layer l at H + l * lstride; else the last layer's h only
+    gfix16_t* G;  // saving: act'(z) of layer l at G + l * lstride
+    int64_t lstride;
+    int32_t L, O, M, tiles_m, n_tiles;
+    // output layer (applied to the tile's last hidden activations while they are still in LDS)
+    int64_t head_mat_off, head_vec_off, logsig_off;
+    int32_t out_dim, tanh_head;
+    RowMap rm;
+    float* out;        // time-major [.., N, out_dim]
+    float* saved_out;  // saving: compact [P][M][OUT_PITCH]
+    const float* eps;  // actor with sampling: noise, and the two outputs below
+    float* act;
+    float* logp;
+};
+
+__device__ inline int swap_bits23(int i) { return (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1); }
+
+// a value the compiler can no longer trace back to its source: address arithmetic derived from it stays
+// where it is written instead of being hoisted out of the layer loop into registers held across the products
+__device__ inline int opaque(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+template <int ACT, bool SAVE>
+__global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
+    extern __shared__ __align__(16) unsigned char dlds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 31, lg = lane >> 5;
+    const int tile = xcd_remap(blockIdx.x, a.n_tiles);
+    const int p = tile / a.tiles_m, m0 = (tile % a.tiles_m) * FF_ROWS;
+    const int rows = a.M - m0 < FF_ROWS ? a.M - m0 : FF_ROWS;
+    const int wn = wave * 64;
+
+    const bf16_t* Wp = a.theta_mat + (int64_t)p * a.mat_len;
+    const float* bp = a.theta_vec + (int64_t)p * a.vec_len;
+    const int frow = swap_bits23(lr);
+    auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's two rows of W_l(p), at its contraction offset
+        const int K = l == 0 ? a.O : FF_W;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            w[j] = reinterpret_cast<const char*>(Wp + a.mat_off[l] + (int64_t)(wn + 32 * j + frow) * K) + lg * 64;
+    };
+    // unit u of a layer = 32 contraction indices per lane group: bytes [32 (u & 1), + 32) of the lane's 64
+    // contiguous bytes of super-step u / 2
+    auto load_w = [&](uint4 (&wf)[2][2], const char* w0, const char* w1, int u) {
+        const int off = (u >> 1) * 128 + (u & 1) * 32;
+        wf[0][0] = *reinterpret_cast<const uint4*>(w0 + off);
+        wf[0][1] = *reinterpret_cast<const uint4*>(w0 + off + 16);
+        wf[1][0] = *reinterpret_cast<const uint4*>(w1 + off);
+        wf[1][1] = *reinterpret_cast<const uint4*>(w1 + off + 16);
+    };
+    // W fragments: two buffers, a unit's request one unit ahead of its use (a longer distance with four
+    // buffers measured slower: the registers it takes spill in the epilogue)
+    const char* wp[2];
+    uint4 wfa[2][2], wfb[2][2];
+    float16_t acc[4][2];
+    w_rows(0, wp);
+    load_w(wfa, wp[0], wp[1], 0);
+
+    {  // the tile's observations; rows past the end repeat the last row (their results are never stored)
+        const int cpr = a.O >> 3;
+        const bf16_t* xs = a.x0 + ((int64_t)p * a.M + m0) * a.O;
+        for (int id = threadIdx.x; id < FF_ROWS * cpr; id += 512) {
+            const int r = id / cpr, c = id % cpr, rc = r < rows ? r : rows - 1;
+            *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) =
+                *reinterpret_cast<const uint4*>(xs + (int64_t)rc * a.O + 8 * c);
+        }
+    }
+    // fragment addresses: row 32 i + lr, chunk (8 s + 4 lg + jj) ^ (lr & 15)
+    const int x = lr & 15;
+    const unsigned char* arow = dlds + lr * 1024;
+    uint32_t aoff[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) aoff[jj] = (uint32_t)(((4 * lg + jj) ^ (x & 7)) * 16);
+    const int sflip = x >> 3;
+
+    // one unit: 16 products; HALF = u & 1 picks the chunks 2 HALF, 2 HALF + 1 of the super-step
+    auto unit = [&](const uint4 (&wf)[2][2], int u, auto half_tag) {
+        constexpr int HALF = decltype(half_tag)::value;
+        const unsigned char* as = arow + ((u >> 1) ^ sflip) * 128;
+        uint4 fa[2][4];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fa[jj][i] = *reinterpret_cast<const uint4*>(as + i * 32768 + aoff[2 * HALF + jj]);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(wf[j][jj], fa[jj][i], acc[i][j]);
+    };
+    // lane n of `bias` holds b_l[wn + n]; every accumulator of a lane's octet o starts from its feature's bias
+    auto init_acc = [&](float bias) {
+#pragma unroll
+        for (int o = 0; o < 4; ++o)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float b = __shfl(bias, 16 * o + 8 * lg + u, 64);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i][o >> 1][8 * (o & 1) + u] = b;
+            }
+    };
+    auto load_bias = [&](int l) { return bp[a.vec_off[l] + wn + lane]; };
+
+    init_acc(load_bias(0));
+    __syncthreads();
+    for (int l = 0; l < a.L; ++l) {
+        const bool more = l + 1 < a.L;
+        // the last request of a layer fetches the first unit of the next one (of this one again after the last
+        // layer: a harmless, valid load), so that every pass through the loop has the same loads in flight
+        const char* wq[2];
+        w_rows(more ? l + 1 : l, wq);
+        const int nU = l == 0 ? a.O >> 5 : FF_W / 32;
+        for (int u = 0; u < nU; u += 2) {
+            load_w(wfb, wp[0], wp[1], u + 1);
+            __builtin_amdgcn_sched_barrier(0);  // the requests stay ahead of the products they overlap with
+            unit(wfa, u, std::integral_constant<int, 0>{});
+            const bool last = u + 2 == nU;
+            load_w(wfa, last ? wq[0] : wp[0], last ? wq[1] : wp[1], last ? 0 : u + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            unit(wfb, u + 1, std::integral_constant<int, 1>{});
+        }
+        wp[0] = wq[0];
+        wp[1] = wq[1];
+        __syncthreads();  // every wave has read the layer's input for the last time
+        const float bnext = load_bias(more ? l + 1 : l);
+        {
+            const int ol = opaque(lane), olr = ol & 31, olg = ol >> 5, ox = ol & 15;
+            unsigned char* hrow = dlds + olr * 1024;
+            unsigned char* patch = dlds + FF_ACT_BYTES + wave * 4096;
+            gfix16_t* Gl = SAVE ? a.G + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint4 gq[4];
+#pragma unroll
+                for (int o = 0; o < 4; ++o) {
+                    const int j = o >> 1, h = o & 1;
+                    float v[8], g[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) act_pair<ACT>(acc[i][j][8 * h + u], v[u], g[u]);
+                    const int cc = 8 * wave + 4 * j + 2 * h + olg;
+                    *reinterpret_cast<uint4*>(hrow + i * 32768 + ((cc ^ ox) * 16)) = pack_chunk<bf16_t>(v);
+                    if (SAVE) gq[o] = pack8(g, (const gfix16_t*)nullptr).lo;
+                }
+                if (SAVE) {  // act'(z) leaves through the wave's patch as whole 128-byte row segments
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        const int cch = 4 * (o >> 1) + 2 * (o & 1) + olg;
+                        *reinterpret_cast<uint4*>(patch + olr * 128 + ((cch ^ (olr & 7)) * 16)) = gq[o];
+                    }
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int prow = it * 8 + (ol >> 3), pc = ol & 7;
+                        const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
+                        const int gr = 32 * i + prow;
+                        if (gr < rows) *reinterpret_cast<uint4*>(Gl + (int64_t)gr * FF_W + pc * 8) = u;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+        __syncthreads();  // the layer's output is complete in LDS
+        if (SAVE) {  // h to memory, one whole row per wave and store
+            const int ol = opaque(lane);
+            bf16_t* Hl = a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + 8 * ol;
+            uint4 hv[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int r = 8 * q + wave;
+                hv[q] = *reinterpret_cast<const uint4*>(dlds + r * 1024 + ((ol ^ (r & 15)) * 16));
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int r = 8 * q + wave;
+                if (r < rows) *reinterpret_cast<uint4*>(Hl + (int64_t)r * FF_W) = hv[q];
+            }
+        }
+        if (more) init_acc(bnext);
+    }
+
+    // output layer: wave w takes rows 16 w .. 16 w + 15 of the tile with 16x16x32 products; lane (hl, hg)
+    // supplies row hl / output hl at contraction chunk 4 u + hg and receives output hl of rows 4 hg + e
+    {
+        const int hl = lane & 15, hg = lane >> 4;
+        const int r = 16 * wave + hl;
+        const unsigned char* hrow = dlds + r * 1024;
+        const bf16_t* wrow = Wp + a.head_mat_off + (int64_t)hl * FF_W;
+        const bool b_ok = hl < a.out_dim;
+        float4_t c = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            uint4 fa[8], fb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int ch = 32 * half + 4 * u + hg;
+                fa[u] = *reinterpret_cast<const uint4*>(hrow + ((ch ^ (r & 15)) * 16));
+                fb[u] = make_uint4(0, 0, 0, 0);
+                if (b_ok) fb[u] = *reinterpret_cast<const uint4*>(wrow + 8 * ch);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) {
+                Mma16<bf16_t>::run(fa[u], fb[u], c);
+                Mma16<bf16_t>::run(fa[u + 1], fb[u + 1], c2);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] += c2[e];
+        const float bias = b_ok ? bp[a.head_vec_off + hl] : 0.f;
+        float ls = 0.f, sg = 0.f;
+        if (a.eps && b_ok) {
+            ls = bp[a.logsig_off + hl];
+            sg = expf(ls);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int tr = 16 * wave + 4 * hg + e, m = m0 + tr;
+            const bool ok = (tr < rows) && b_ok;
+            const float z = c[e] + bias;
+            const float o = a.tanh_head ? tanhf(z) : z;
+            int64_t row = 0;
+            if (tr < rows) row = a.rm.row(p, m);
+            float term = 0.f;
+            if (ok) {
+                a.out[row * a.out_dim + hl] = o;
+                if (SAVE) a.saved_out[((int64_t)p * a.M + m) * OUT_PITCH + hl] = o;
+                if (a.eps) {
+                    const float ep = a.eps[row * a.out_dim + hl];
+                    a.act[row * a.out_dim + hl] = o + sg * ep;
+                    term = -0.5f * ep * ep - ls;
+                }
+            }
+            if (a.eps) {
+                term += __shfl_xor(term, 8, 64);
+                term += __shfl_xor(term, 4, 64);
+                term += __shfl_xor(term, 2, 64);
+                term += __shfl_xor(term, 1, 64);
+                if (tr < rows && hl == 0) a.logp[row] = term - 0.918938533204672742f * (float)a.out_dim;
+            }
+        }
+    }
+}
+
 // ---- optional event timing of the GEMM launches ------------------------------------------------
 #include <vector>
 struct GemmProf {
@@ -1330,24 +1613,6 @@ static void run_gemm(const morlax_ctx* c, int kind, GemmArgs<T, KA, KB, Epi, FAS
 }
 
 // ---- output layer ------------------------------------------------------------------------------
-template <typename T> struct Mma16;
-template <> struct Mma16<bf16_t> {
-    static __device__ inline void run(const uint4& a, const uint4& b, float4_t& c) {
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
-                                                    0, 0, 0);
-    }
-};
-template <> struct Mma16<float> {
-    static __device__ inline void run(const uint4& a, const uint4& b, float4_t& c) {
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
-    }
-};
-
-// out = head(h W_L(p)^T + b_L(p)); actor: optional sampling a = mu + sigma eps and its log-density.
-// A wave owns 16 rows; lane (row = lane % 16, chunk = lane / 16) feeds 16x16 MFMA tiles from global.
 template <typename T>
 __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, const T* __restrict__ theta_mat,
                                                  const float* __restrict__ theta_vec, int64_t mat_len,
@@ -1701,6 +1966,32 @@ static RowMap make_rowmap(const morlax_ctx* c, const RowSel& rs) {
     return rm;
 }
 
+// The fused forward serves bf16 networks of width 512 whose observation width is a multiple of 64.
+static bool fused_fwd_ok(const morlax_ctx* c, const NetDev& nd, const void* theta_mat) {
+    if (c->d.wdtype != 1 || c->d.width != FF_W || c->d.obs_dim % 64 || c->d.obs_dim > FF_W || c->d.n_hidden < 1)
+        return false;
+    if ((reinterpret_cast<uintptr_t>(theta_mat) & 15) || (nd.mat_len & 7)) return false;
+    for (int l = 0; l <= c->d.n_hidden; ++l)
+        if (nd.layer[l].mat_off & 7) return false;
+    return true;
+}
+
+template <int ACT, bool SAVE>
+static void launch_fused_fwd(const morlax_ctx* c, const FusedFwdArgs& a, hipStream_t s) {
+    constexpr int lds = FF_ACT_BYTES + (SAVE ? 8 * 4096 : 0);
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mlp_fused_fwd<ACT, SAVE>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    const double per_row = 2.0 * FF_W * ((double)a.O + (double)(a.L - 1) * FF_W);
+    GemmProf::Rec* r = prof_take(c, 5, per_row * a.M * c->d.P);
+    if (r) (void)hipEventRecord(r->a, s);
+    k_mlp_fused_fwd<ACT, SAVE><<<a.n_tiles, 512, lds, s>>>(a);
+    if (r) (void)hipEventRecord(r->b, s);
+}
+
 template <typename T>
 static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const float* theta_vec, const float* x,
                          const RowSel& rs, float* out, const float* eps, float* act, float* logp, void* saved,
@@ -1760,7 +2051,38 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             run_gemm(c, 1, g, P, s);
         }
     };
-    for (int l = 0; l < L; ++l) {
+    bool fused = false;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (fused_fwd_ok(c, nd, theta_mat) && !getenv("MORLAX_NO_FUSED")) {
+            T* x0 = sv ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
+                                              align_up((int64_t)P * M * OUT_PITCH * 4, 256))
+                       : reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
+            const int64_t pieces = (int64_t)M * (O / 8);
+            k_gather_x<T><<<dim3((unsigned)((pieces + 255) / 256), P), 256, 0, s>>>(x, x0, O, M, rm);
+            FusedFwdArgs a;
+            a.x0 = x0; a.theta_mat = theta_mat; a.theta_vec = theta_vec;
+            a.mat_len = nd.mat_len; a.vec_len = nd.vec_len;
+            for (int l = 0; l < L; ++l) { a.mat_off[l] = nd.layer[l].mat_off; a.vec_off[l] = nd.layer[l].vec_off; }
+            a.H = sv;
+            a.G = sv ? reinterpret_cast<gfix16_t*>(sv + ae) : nullptr;
+            a.lstride = 2 * ae;
+            a.L = L; a.O = O; a.M = M;
+            a.tiles_m = (M + FF_ROWS - 1) / FF_ROWS;
+            a.n_tiles = a.tiles_m * P;
+            const LayerDev& Lo = nd.layer[L];
+            a.head_mat_off = Lo.mat_off; a.head_vec_off = Lo.vec_off; a.logsig_off = Lo.vec_off + Lo.d_out;
+            a.out_dim = nd.out_dim;
+            a.tanh_head = (net == MORLAX_ACTOR && c->d.mean_tanh) ? 1 : 0;
+            a.rm = rm; a.out = out; a.saved_out = saved_out; a.eps = eps; a.act = act; a.logp = logp;
+            if (c->d.act == 0) {
+                if (sv) launch_fused_fwd<0, true>(c, a, s); else launch_fused_fwd<0, false>(c, a, s);
+            } else {
+                if (sv) launch_fused_fwd<1, true>(c, a, s); else launch_fused_fwd<1, false>(c, a, s);
+            }
+            fused = true;
+        }
+    }
+    for (int l = 0; l < L && !fused; ++l) {
         const bool save = sv != nullptr;
         if (c->d.act == 0) {
             if (save) layer(l, std::integral_constant<int, 0>{}, std::true_type{});
@@ -1770,6 +2092,7 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             else layer(l, std::integral_constant<int, 1>{}, std::false_type{});
         }
     }
+    if (fused) return;  // the fused kernel applies the output layer as well
     const LayerDev& Lh = nd.layer[L];
     const int tanh_head = (net == MORLAX_ACTOR && c->d.mean_tanh) ? 1 : 0;
     const dim3 grid((M + 63) / 64, P);

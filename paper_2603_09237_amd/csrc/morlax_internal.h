@@ -52,7 +52,7 @@ struct morlax_ctx {
     GemmProf* prof;  // NULL unless morlax_profile_begin() was called
 };
 
-#define MORLAX_GEMM_KINDS 5  // fwd first layer, fwd hidden, dX hidden, dW hidden, dW first layer
+#define MORLAX_GEMM_KINDS 6  // fwd first layer, fwd hidden, dX hidden, dW hidden, dW first layer, fused fwd
 int prof_begin(morlax_ctx* c);
 int prof_end(morlax_ctx* c, double* ms, int64_t* launches, double* flops);
 void prof_free(morlax_ctx* c);

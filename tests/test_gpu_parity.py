@@ -56,6 +56,11 @@ RAGGED_BF16 = scaled(RAGGED, name="ragged-bf16", wdtype=1, N=3 * 150, T=5, width
 # last column tile (width 160), and an observation width that takes the gathered first-layer path
 RAGGED_PERS = scaled(RAGGED, name="ragged-persistent-bf16", wdtype=1, P=32, N=32 * 126, T=16, width=160, obs_dim=32,
                      rank=4)
+# the fused forward of all hidden layers (bf16, width 512, observation width a multiple of 64): three row
+# tiles per preference with a cut last one (333 = 2 * 128 + 77 rows), tanh in one variant
+RAGGED_FUSED = scaled(RAGGED, name="ragged-fused-bf16", wdtype=1, P=5, N=5 * 37, T=9, width=512, obs_dim=64, n_hidden=3,
+                      rank=4)
+RAGGED_FUSED_TANH = scaled(RAGGED_FUSED, name="ragged-fused-bf16-tanh", act=0, n_hidden=1, obs_dim=128)
 
 
 def all_cfgs():
@@ -346,7 +351,8 @@ def pref_env_mask(cfg, prefs):
 
 FWD_CASES = [(CONFIGS[1], None), (CONFIGS[1], (3, 9, 5, 7)), (RAGGED, None), (RAGGED, (1, 5, 2, 19)),
              (RAGGED_BF16, None), (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None),
-             (CONFIGS[4], None), (CONFIGS[5], None), (CONFIGS[5], "mb")]
+             (CONFIGS[4], None), (CONFIGS[5], None), (CONFIGS[5], "mb"), (RAGGED_FUSED, None),
+             (RAGGED_FUSED, (2, 5, 3, 30)), (RAGGED_FUSED_TANH, None)]
 
 
 @pytest.mark.parametrize("cfg,rows", FWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -409,7 +415,7 @@ def test_policy_fwd_matches_oracle(cfg, rows, torch, binding):
 
 BWD_CASES = [(CONFIGS[1], None), (RAGGED, None), (RAGGED, (1, 5, 2, 19)), (RAGGED_BF16, None),
              (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None), (CONFIGS[4], None),
-             (CONFIGS[5], "mb")]
+             (CONFIGS[5], "mb"), (RAGGED_FUSED, None), (RAGGED_FUSED_TANH, (1, 6, 0, 37))]
 
 
 @pytest.mark.parametrize("cfg,rows", BWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -577,7 +583,8 @@ def test_update_step_fp32_matches_oracle(cfg, torch, binding):
                 assert_close32(g[o:o + n] / scale, r / scale, f"{key}[{name}] mb {i}", rel=1e-3, abs_=1e-4)
 
 
-@pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), RAGGED_PERS, CONFIGS[3]],
+@pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), RAGGED_PERS, CONFIGS[3],
+                                 scaled(RAGGED_FUSED, name="ragged-fused-step", minibatches=1, epochs=1)],
                          ids=lambda c: c.name)
 def test_update_step_bf16_matches_oracle(cfg, torch, binding):
     say(f"update_step bf16 {cfg.name}")
