@@ -1225,7 +1225,8 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
 #define FF_ACT_BYTES (FF_ROWS * FF_W * 2)
 
 struct FusedFwdArgs {
-    const bf16_t* x0;         // gathered observations, compact [P][M][O]
+    const float* x;           // observations, time-major rows of O values
+    bf16_t* x0;               // saving: receives the gathered observations, compact [P][M][O] bf16
     const bf16_t* theta_mat;  // [P][mat_len]
     const float* theta_vec;   // [P][vec_len]
     int64_t mat_len, vec_len;
@@ -1289,13 +1290,17 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
     w_rows(0, wp);
     load_w(wfa, wp[0], wp[1], 0);
 
-    {  // the tile's observations; rows past the end repeat the last row (their results are never stored)
+    {  // the tile's observations, gathered from the time-major tensor and rounded to bf16; rows past the end
+       // repeat the last row (their results are never stored).  The saving variant keeps the compact copy
+       // that the first layer's dW product reads.
         const int cpr = a.O >> 3;
-        const bf16_t* xs = a.x0 + ((int64_t)p * a.M + m0) * a.O;
         for (int id = threadIdx.x; id < FF_ROWS * cpr; id += 512) {
             const int r = id / cpr, c = id % cpr, rc = r < rows ? r : rows - 1;
-            *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) =
-                *reinterpret_cast<const uint4*>(xs + (int64_t)rc * a.O + 8 * c);
+            float v[8];
+            get8(a.x + a.rm.row(p, m0 + rc) * a.O + 8 * c, v);
+            const uint4 q = pack_chunk<bf16_t>(v);
+            *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) = q;
+            if (SAVE && r < rows) *reinterpret_cast<uint4*>(a.x0 + ((int64_t)p * a.M + m0 + r) * a.O + 8 * c) = q;
         }
     }
     // fragment addresses: row 32 i + lr, chunk (8 s + 4 lg + jj) ^ (lr & 15)
@@ -2054,13 +2059,12 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     bool fused = false;
     if constexpr (std::is_same<T, bf16_t>::value) {
         if (fused_fwd_ok(c, nd, theta_mat) && !getenv("MORLAX_NO_FUSED")) {
-            T* x0 = sv ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
-                                              align_up((int64_t)P * M * OUT_PITCH * 4, 256))
-                       : reinterpret_cast<T*>(reinterpret_cast<float*>(wsT + 2 * ae) + part_elems(c, rs));
-            const int64_t pieces = (int64_t)M * (O / 8);
-            k_gather_x<T><<<dim3((unsigned)((pieces + 255) / 256), P), 256, 0, s>>>(x, x0, O, M, rm);
             FusedFwdArgs a;
-            a.x0 = x0; a.theta_mat = theta_mat; a.theta_vec = theta_vec;
+            a.x = x;
+            a.x0 = sv ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
+                                             align_up((int64_t)P * M * OUT_PITCH * 4, 256))
+                      : nullptr;
+            a.theta_mat = theta_mat; a.theta_vec = theta_vec;
             a.mat_len = nd.mat_len; a.vec_len = nd.vec_len;
             for (int l = 0; l < L; ++l) { a.mat_off[l] = nd.layer[l].mat_off; a.vec_off[l] = nd.layer[l].vec_off; }
             a.H = sv;
