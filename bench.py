@@ -34,8 +34,8 @@ KERNEL_OF_KIND = {
 }
 
 # HBM bytes per launch of a GEMM launch kind, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script scaled by
-# a copy of known size (profiles/grouped_gemm_cfg5_hbm_traffic.txt); workloads without such a run report null
-MEASURED_TRAFFIC_BYTES = {("cfg5-largest-K6-P128-N16384-T64-4x512-silu-bf16-4mbx2ep", "fwd_hidden"): 1033.5e6}
+# a copy of known size (profiles/fused_fwd_grouped_gemm_cfg5_hbm_traffic.txt); workloads without such a run report null
+MEASURED_TRAFFIC_BYTES = {("cfg5-largest-K6-P128-N16384-T64-4x512-silu-bf16-4mbx2ep", "fwd_fused"): 2291.4e6}
 
 
 def cpu_baseline(cfg_full):

@@ -12,7 +12,6 @@
 // axis in memory (W in the dX product, both operands of the dW product) are transposed on the way
 // into LDS.  The skinny output layer (<= 16 columns) uses 16x16 MFMA tiles straight from global
 // memory in the forward pass and plain vector code in the backward pass.
-#include <cstdlib>
 #include <type_traits>
 
 #include "morlax_internal.h"
@@ -1210,16 +1209,24 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
     }
 }
 
-// ---- fused forward of all hidden layers (bf16, width 512) ----------------------------------------
-// One workgroup of eight waves carries 128 rows of one preference through every hidden layer.  The
-// activations of the tile live in LDS (128 rows x 1 KB, 16-byte chunks XOR-swizzled by the row) and are
-// rewritten in place layer after layer; HBM sees the gathered observations once and, in the saving
-// variant, the stores of h and act'(z) that the backward pass reads -- never a load of an activation.
+// ---- fused forward: observations -> every hidden layer -> output layer (bf16, width 512) --------------
+// (paper Sec. III-C: the target network of a preference applied to that preference's environments, in the
+// rollout and in the update.)  One workgroup of eight waves carries 128 rows of one preference through the
+// whole network.  The activations of the tile live in LDS (128 rows x 1 KB, 16-byte chunks XOR-swizzled by
+// the row) and are rewritten in place layer after layer; HBM sees the observations once, the outputs once
+// and, in the saving variant, the stores of h and act'(z) that the backward pass reads -- never a load of
+// an activation.
 // Wave w owns output features [64 w, 64 w + 64) of every layer for all 128 rows: its slice of W_l(p) is
-// used by no other wave, so the W fragments go from global memory (L2) straight into registers, 64
-// contiguous bytes per lane and 64 contraction steps ("super-step"), one super-step ahead of their use.
-// Inside a super-step lane group g of product jj covers contraction indices 64 s + 32 g + 8 jj .. + 8 for
-// both operands.  The bias enters as the initial value of the accumulators.
+// used by no other wave, so the W fragments go from global memory (they sit in L2: 64 tiles share one
+// W(p)) straight into registers, 64 contiguous bytes per lane and 64 contraction indices ("super-step"),
+// requested half a super-step ("unit": 16 products) ahead of their use.  Inside a super-step lane group g
+// of product jj covers contraction indices 64 s + 32 g + 8 jj .. + 8 for both operands.  The bias enters
+// as the initial value of the accumulators.  A layer ends with a barrier, the epilogue (activation, its
+// derivative, the in-place rewrite of the tile, the stores of the saving variant) and a second barrier;
+// the products and the epilogue of a workgroup do not overlap, and with 128 KB of LDS for the tile there is
+// one workgroup per CU.  Measured on workload 5 the time of a launch splits, additively, into the W
+// requests (a third: 32 cache lines per load instruction, each used for 32 bytes), the products, the
+// epilogue arithmetic and a fixed part per tile (observation gather, first requests, barriers).
 #define FF_ROWS 128
 #define FF_W 512
 #define FF_ACT_BYTES (FF_ROWS * FF_W * 2)
@@ -2058,7 +2065,7 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     };
     bool fused = false;
     if constexpr (std::is_same<T, bf16_t>::value) {
-        if (fused_fwd_ok(c, nd, theta_mat) && !getenv("MORLAX_NO_FUSED")) {
+        if (fused_fwd_ok(c, nd, theta_mat)) {
             FusedFwdArgs a;
             a.x = x;
             a.x0 = sv ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
