@@ -416,6 +416,29 @@ def adv_norm_stats(adv_s, mask):
     return m, s
 
 
+def scalarize_normalized(d, rows, adv_vec, w):
+    """Per-objective normalisation before scalarisation -- the other reading of "normalised across the
+    batch" in the update phase (Sec. III-C): every objective's advantages are standardised over the
+    selected cells on their own (mean, population standard deviation, + 1e-8), and only then combined
+    with the trade-off vector of the environment:
+      Ahat[t, n] = sum_k w[g(n), k] (A_k[t, n] - mean_k) / (std_k + 1e-8).
+    Objectives with very different reward scales then weigh in by w alone.  adv_vec [T, N, K],
+    w [P, K]; returns [T, N] with zeros outside the selection."""
+    a = np.asarray(adv_vec, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    T, N, K = a.shape
+    mask = row_mask(d, rows, T)
+    g = env_pref_index(N, w.shape[0])
+    out = np.zeros((T, N))
+    for k in range(K):
+        sel = a[:, :, k][mask]
+        mean = sel.mean()
+        std = math.sqrt(((sel - mean) ** 2).mean())
+        out += w[g, k][None, :] * (a[:, :, k] - mean) / (std + 1e-8)
+    out[~mask] = 0.0
+    return out
+
+
 # --------------------------------------------------------------------------- losses
 
 def ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv=True):
@@ -497,7 +520,8 @@ def minibatch_rows(d, T, b, MB):
 
 
 def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rewards, dones, eps,
-                gamma, lam, clip_eps, minibatches=1, epochs=1, emulate_bf16=False, keep=False, optimizer=None):
+                gamma, lam, clip_eps, minibatches=1, epochs=1, emulate_bf16=False, keep=False, optimizer=None,
+                adv_norm="scalar"):
     """One MORLAX iteration after the trade-offs are drawn (Sec. III-C): rollout forward of the
     actor family (sampling actions and their log-density) and of the critic family at every state,
     vector GAE, then for every epoch and minibatch the losses and their gradients with respect to
@@ -506,7 +530,8 @@ def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rew
     minibatch is evaluated at the same update-time parameters.  With optimizer = dict(lr_actor,
     lr_critic, beta1, beta2, eps) each minibatch is followed by one Adam step on either hypernet with
     its own learning rate (moments start at zero, step counter t = 1, 2, ...), and the result holds
-    the final parameters and moments.  Returns a dict; with keep=True it also holds the intermediate
+    the final parameters and moments.  adv_norm = "scalar": the scalarised advantage is normalised over
+    the minibatch; "per_objective": scalarize_normalized() instead.  Returns a dict; with keep=True it also holds the intermediate
     tensors of the first minibatch."""
     T = rewards.shape[0]
     wq = (lambda m: round_bf16(m)) if (emulate_bf16 and d.wdtype == 1) else (lambda m: m)
@@ -534,8 +559,13 @@ def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rew
             mu, _, _ = policy_fwd(d, ACTOR, tm_a, tv_a, obs[:T], rows, emulate_bf16=emu)
             vv, _, _ = policy_fwd(d, CRITIC, tm_c, tv_c, obs[:T], rows, emulate_bf16=emu)
             logsig = tv_a[:, -d.act_dim:]
-            dmu, dlogsig, dv, stats = ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, vv,
-                                                    vtarg, clip_eps, True)
+            if adv_norm == "per_objective":
+                dmu, dlogsig, dv, stats = ppo_loss_grad(d, rows, mu, logsig, act, logp_old,
+                                                        scalarize_normalized(d, rows, adv_vec, w), vv, vtarg,
+                                                        clip_eps, False)
+            else:
+                dmu, dlogsig, dv, stats = ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, vv,
+                                                        vtarg, clip_eps, True)
             dm_a, dvec_a = policy_bwd(d, ACTOR, tm_a, tv_a, obs[:T], rows, dmu, dlogsig, emulate_bf16=emu)
             dm_c, dvec_c = policy_bwd(d, CRITIC, tm_c, tv_c, obs[:T], rows, dv, None, emulate_bf16=emu)
             g_a = hypernet_bwd(d, ACTOR, hp_actor, w, dm_a, dvec_a)

@@ -185,3 +185,103 @@ def test_update_step_with_optimizer_equals_manual_adam_on_its_gradients():
     hp2, _, _ = orc.adam_step(hp1, ref2["grads"][1]["dhp_actor"], m1, v1, 3e-3, 0.9, 0.999, 1e-8, 2)
     assert np.allclose(res["hp_actor"], hp2, rtol=1e-12, atol=1e-15)
     assert not np.allclose(res["hp_actor"], d["hparams_actor"])
+
+
+# ---- per-objective advantage normalisation before scalarisation ------------------------------------
+def _tiny_cfg(K=3, P=2, N=6, T=5):
+    from paper_2603_09237_amd.configs import CONFIGS, scaled
+    return scaled(CONFIGS[1], name="advk", K=K, P=P, N=N, T=T)
+
+
+def test_per_objective_normalisation_brute_force():
+    """The definition written out with loops over cells and objectives, on a partial selection."""
+    cfg = _tiny_cfg()
+    rng = np.random.default_rng(3)
+    adv = rng.standard_normal((cfg.T, cfg.N, cfg.K)) * np.array([1.0, 0.1, 10.0]) + np.array([0.5, -2.0, 7.0])
+    w = rng.dirichlet(np.ones(cfg.K), size=cfg.P)
+    rows = (1, 3, 1, 2)                       # t in 1..3, local environments 1..2 of every preference
+    n_g = cfg.N // cfg.P
+    cells = [(t, p * n_g + j) for t in range(1, 4) for p in range(cfg.P) for j in range(1, 3)]
+    want = np.zeros((cfg.T, cfg.N))
+    for k in range(cfg.K):
+        vals = [adv[t, n, k] for t, n in cells]
+        mean = sum(vals) / len(vals)
+        std = (sum((x - mean) ** 2 for x in vals) / len(vals)) ** 0.5
+        for t, n in cells:
+            want[t, n] += w[n // n_g, k] * (adv[t, n, k] - mean) / (std + 1e-8)
+    got = orc.scalarize_normalized(cfg, rows, adv, w)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-14)
+    outside = np.ones((cfg.T, cfg.N), bool)
+    for t, n in cells:
+        outside[t, n] = False
+    assert np.all(got[outside] == 0.0)
+
+
+def test_per_objective_normalisation_ignores_scale_and_offset_of_an_objective():
+    """What the variant is for: an objective measured in other units (x c_k + b_k, c_k > 0) counts the same."""
+    cfg = _tiny_cfg(K=3, P=3, N=12, T=7)
+    rng = np.random.default_rng(4)
+    adv = rng.standard_normal((cfg.T, cfg.N, cfg.K))
+    w = rng.dirichlet(np.ones(cfg.K), size=cfg.P)
+    rows = orc.full_rows(cfg, cfg.T)
+    a = orc.scalarize_normalized(cfg, rows, adv, w)
+    b = orc.scalarize_normalized(cfg, rows, adv * np.array([1.0, 0.1, 10.0]) + np.array([0.0, 3.0, -50.0]), w)
+    assert np.allclose(a, b, rtol=0, atol=1e-6)
+    # the scalarise-then-normalise reading does depend on the units
+    s1 = orc.vec_gae(adv, np.zeros((cfg.T + 1, cfg.N, cfg.K)), np.ones((cfg.T, cfg.N)), w, 0.0, 0.0)[2]
+    s2 = orc.vec_gae(adv * np.array([1.0, 0.1, 10.0]), np.zeros((cfg.T + 1, cfg.N, cfg.K)), np.ones((cfg.T, cfg.N)),
+                     w, 0.0, 0.0)[2]
+    m = np.ones((cfg.T, cfg.N), bool)
+    n1 = (s1 - orc.adv_norm_stats(s1, m)[0]) / orc.adv_norm_stats(s1, m)[1]
+    n2 = (s2 - orc.adv_norm_stats(s2, m)[0]) / orc.adv_norm_stats(s2, m)[1]
+    assert not np.allclose(n1, n2, atol=1e-2)
+
+
+def test_per_objective_normalisation_single_objective_is_the_scalar_normalisation():
+    cfg = _tiny_cfg(K=1, P=2, N=8, T=6)
+    rng = np.random.default_rng(5)
+    adv = rng.standard_normal((cfg.T, cfg.N, 1)) * 3.0 + 1.0
+    w = np.ones((cfg.P, 1))
+    rows = (0, cfg.T, 0, 2)
+    mask = orc.row_mask(cfg, rows, cfg.T)
+    mean, std = orc.adv_norm_stats(adv[:, :, 0], mask)
+    got = orc.scalarize_normalized(cfg, rows, adv, w)
+    assert np.allclose(got[mask], (adv[:, :, 0][mask] - mean) / (std + 1e-8), rtol=1e-12, atol=0)
+
+
+def test_per_objective_normalisation_vertex_gives_unit_variance_and_is_linear_in_w():
+    cfg = _tiny_cfg(K=3, P=2, N=10, T=9)
+    rng = np.random.default_rng(6)
+    adv = rng.standard_normal((cfg.T, cfg.N, cfg.K)) * np.array([2.0, 30.0, 0.01])
+    rows = orc.full_rows(cfg, cfg.T)
+    parts = []
+    for k in range(cfg.K):
+        e = np.zeros((2, cfg.K)); e[:, k] = 1.0     # both preferences at vertex k
+        z = orc.scalarize_normalized(cfg, rows, adv, e)
+        std_k = adv[:, :, k].std()
+        assert abs(z.mean()) < 1e-12 and abs(z.var() - (std_k / (std_k + 1e-8)) ** 2) < 1e-12
+        parts.append(z)
+    w = np.repeat(rng.dirichlet(np.ones(cfg.K), size=1), 2, axis=0)
+    mix = orc.scalarize_normalized(cfg, rows, adv, w)
+    assert np.allclose(mix, sum(w[0, k] * parts[k] for k in range(cfg.K)), rtol=1e-12, atol=1e-14)
+
+
+def test_update_step_per_objective_uses_the_prenormalised_advantage():
+    """The update step's variant = the plain loss (no further normalisation) on scalarize_normalized()."""
+    from paper_2603_09237_amd import inputs
+    from paper_2603_09237_amd.configs import CONFIGS, scaled
+    cfg = scaled(CONFIGS[1], name="advk-step", minibatches=2, epochs=1)
+    d = inputs.make_all(cfg)
+    args = (cfg, d["w"], d["hparams_actor_old"], d["hparams_critic_old"], d["hparams_actor"], d["hparams_critic"],
+            d["obs"], d["rewards"], d["dones"], d["eps"], cfg.gamma, cfg.lam, cfg.clip_eps)
+    a = orc.update_step(*args, minibatches=2, epochs=1, adv_norm="per_objective", keep=True)
+    b = orc.update_step(*args, minibatches=2, epochs=1, keep=True)
+    # the critic's loss does not see the advantage; the actor's does
+    assert np.array_equal(a["grads"][0]["dhp_critic"], b["grads"][0]["dhp_critic"])
+    assert not np.allclose(a["grads"][0]["dhp_actor"], b["grads"][0]["dhp_actor"], rtol=1e-3)
+    rows = orc.minibatch_rows(cfg, cfg.T, 0, 2)
+    adv_b = orc.scalarize_normalized(cfg, rows, a["adv_vec"], d["w"])
+    logsig = a["theta_vec_actor"][:, -cfg.act_dim:]
+    dmu, dls, dv, st = orc.ppo_loss_grad(cfg, rows, a["mu"], logsig, a["act"], a["logp_old"], adv_b, a["v"],
+                                         a["vtarg"], cfg.clip_eps, False)
+    assert np.array_equal(dmu, a["dmu"]) and np.array_equal(dls, a["dlogsig"])
