@@ -88,6 +88,17 @@ def bench_kernel(a, cfg):
                 ctx.adam_step(net, th[net], g[net], m[net], v[net], 3e-4, 0.9, 0.999, 1e-8, step[0])
         units, unit_name, bytes_per_launch = sum(n), "parameters/s", 28.0 * sum(n)   # 4 arrays read, 3 written
         metric = "adam_step_params_per_sec"
+    elif a.row == "scalarize_normalized":
+        rows = (0, T, 0, cfg.n_g // cfg.minibatches)          # one minibatch, as in the update step
+        adv = torch.randn(T, N, K, device="cuda")
+        w = dev(inputs.make_preferences(cfg))
+        out = torch.empty(T, N, device="cuda")
+        ws = torch.empty(ctx.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
+        launch = lambda: ctx.scalarize_normalized(rows, adv, w, out, ws)
+        cells = T * N // cfg.minibatches
+        # the vector advantage is read twice (statistics, then the combination), the result written once
+        units, unit_name, bytes_per_launch = cells, "env-steps/s", (8.0 * K + 4.0) * cells
+        metric = "scalarize_normalized_env_steps_per_sec"
     else:
         r, vv, w = dev(inputs.make_rewards(cfg)), dev(inputs.make_values(cfg)), dev(inputs.make_preferences(cfg))
         rng = np.random.default_rng(3)
@@ -135,7 +146,7 @@ def main():
                          "in flight stretch each other's event-timed durations)")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
-    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc"), default="update_step",
+    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "scalarize_normalized"), default="update_step",
                     help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")

@@ -172,6 +172,18 @@ int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const float* dhpa
                      float* v, float lr, float beta1, float beta2, float eps, int32_t step,
                      void* stream);
 
+/* Per-objective advantage normalisation before scalarisation: the alternative reading of the update
+ * phase's "normalised across the batch" (Sec. III-C).  Over the selected cells every objective k of the
+ * vector advantage is standardised on its own (mean_k, population std_k) and the results are combined
+ * with the trade-off vector of the environment:
+ *   adv_out[t, n] = sum_k w[g(n), k] (adv_vec[t, n, k] - mean_k) / (std_k + 1e-8).
+ * Feed adv_out to morlax_ppo_loss_grad with norm_adv = 0.  All pointers are DEVICE pointers:
+ * adv_vec [T, N, K] (as written by morlax_vec_gae), w [P, K], adv_out [T, N] (only the selected cells are
+ * written), ws >= morlax_workspace_bytes(ctx, rows).  rows selects t in [0, T).  Sums in fp64 in a fixed
+ * order: results are repeatable.  Errors: NULL arguments, invalid rows. */
+int morlax_scalarize_normalized(morlax_ctx* ctx, const morlax_rows* rows, const float* adv_vec,
+                                const float* w, float* adv_out, void* ws, void* stream);
+
 /* Clipped PPO surrogate and vector value loss with their gradients on one minibatch (Sec. III-C,
  * update phase).  B = selected cells.  Ahat = (adv_s - mean) / (std + 1e-8) over the selection
  * (population std) when norm_adv != 0, else adv_s.  logp = Gaussian log-density of act under

@@ -37,7 +37,8 @@ EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hpara
            "morlax_theta_mat_len", "morlax_theta_vec_len", "morlax_saved_bytes", "morlax_workspace_bytes",
            "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
            "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
-           "morlax_sample_preferences", "morlax_ppo_loss_grad", "morlax_profile_begin", "morlax_profile_end")
+           "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad", "morlax_profile_begin",
+           "morlax_profile_end")
 
 GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first", "fwd_fused")
 
@@ -77,6 +78,7 @@ def load():
     lib.morlax_vec_gae_trunc.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
     lib.morlax_adam_step.argtypes = [vp, C.c_int, vp, vp, vp, vp, f32, f32, f32, f32, i32, vp]
     lib.morlax_sample_preferences.argtypes = [vp, vp, i32, vp, vp]
+    lib.morlax_scalarize_normalized.argtypes = [vp, C.POINTER(Rows), vp, vp, vp, vp, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
                                          vp, vp, vp, vp, vp, vp]
     lib.morlax_profile_begin.argtypes = [vp]
@@ -85,7 +87,7 @@ def load():
     lib.morlax_profile_end.restype = C.c_int
     for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
                  "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
-                 "morlax_sample_preferences", "morlax_ppo_loss_grad"):
+                 "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -214,6 +216,10 @@ class Context:
         self._check(self.lib.morlax_adam_step(self.h, net, _ptr(hparams), _ptr(dhparams), _ptr(m), _ptr(v),
                                               float(lr), float(beta1), float(beta2), float(eps), int(step),
                                               stream if stream is not None else _stream()))
+
+    def scalarize_normalized(self, rows, adv_vec, w, adv_out, ws, stream=None):
+        self._check(self.lib.morlax_scalarize_normalized(self.h, _rows(rows), _ptr(adv_vec), _ptr(w), _ptr(adv_out),
+                                                         _ptr(ws), stream if stream is not None else _stream()))
 
     def ppo_loss_grad(self, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv,
                       dmu, dlogsig, dv, stats, ws, stream=None):

@@ -296,6 +296,79 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
 }
 
 // ------------------------------------------------------------------------------------------------
+// Per-objective advantage normalisation before scalarisation (the other reading of "normalised across
+// the batch" in the update phase, Sec. III-C): every objective is standardised over the selected cells
+// on its own, then the objectives are combined with the trade-off vector of the environment.
+// Workspace: [nblk][2K] partial sums, then [2K] (mean_k, std_k), all fp64; fixed summation order.
+int64_t advnorm_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
+    const int64_t nblk = (int64_t)((rs.M + 255) / 256) * c->d.P;
+    return align_up((nblk * 2 * c->d.K + 2 * c->d.K) * 8, 256);
+}
+
+__global__ __launch_bounds__(256) void k_advk_partial(RowSel rs, const float* __restrict__ adv_vec,
+                                                     double* __restrict__ part, int N, int n_g, int K) {
+    __shared__ double sh[4];
+    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
+    const float* a = (m < rs.M) ? adv_vec + cell_row(rs, p, m, N, n_g) * K : nullptr;
+    const int64_t b = (int64_t)p * gridDim.x + blockIdx.x;
+    for (int k = 0; k < K; ++k) {
+        const double x = a ? (double)a[k] : 0.0;
+        const double s1 = block_sum(x, sh);
+        const double s2 = block_sum(x * x, sh);
+        if (threadIdx.x == 0) {
+            part[(b * K + k) * 2] = s1;
+            part[(b * K + k) * 2 + 1] = s2;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_advk_final(const double* __restrict__ part, int64_t nblk, int K, double cnt,
+                                                   double* __restrict__ stat) {
+    __shared__ double sh[4];
+    const int k = blockIdx.x;
+    double s1 = 0.0, s2 = 0.0;
+    for (int64_t b = threadIdx.x; b < nblk; b += 256) {
+        s1 += part[(b * K + k) * 2];
+        s2 += part[(b * K + k) * 2 + 1];
+    }
+    s1 = block_sum(s1, sh);
+    s2 = block_sum(s2, sh);
+    if (threadIdx.x == 0) {
+        const double mean = s1 / cnt;
+        double var = s2 / cnt - mean * mean;
+        if (var < 0.0) var = 0.0;
+        stat[2 * k] = mean;
+        stat[2 * k + 1] = sqrt(var);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_advk_apply(RowSel rs, const float* __restrict__ adv_vec,
+                                                   const float* __restrict__ w, const double* __restrict__ stat,
+                                                   float* __restrict__ out, int N, int n_g, int K) {
+    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= rs.M) return;
+    const int64_t row = cell_row(rs, p, m, N, n_g);
+    const float* a = adv_vec + row * K;
+    double acc = 0.0;
+    for (int k = 0; k < K; ++k)
+        acc += (double)w[(int64_t)p * K + k] * (((double)a[k] - stat[2 * k]) / (stat[2 * k + 1] + 1e-8));
+    out[row] = (float)acc;
+}
+
+void launch_scalarize_normalized(const morlax_ctx* c, const RowSel& rs, const float* adv_vec, const float* w,
+                                 float* adv_out, void* ws, hipStream_t s) {
+    const int P = c->d.P, N = c->d.N, K = c->d.K;
+    const int nbm = (rs.M + 255) / 256;
+    const int64_t nblk = (int64_t)nbm * P;
+    double* part = reinterpret_cast<double*>(ws);
+    double* stat = part + nblk * 2 * K;
+    const dim3 grid(nbm, P);
+    k_advk_partial<<<grid, 256, 0, s>>>(rs, adv_vec, part, N, c->n_g, K);
+    k_advk_final<<<K, 256, 0, s>>>(part, nblk, K, (double)rs.M * P, stat);
+    k_advk_apply<<<grid, 256, 0, s>>>(rs, adv_vec, w, stat, adv_out, N, c->n_g, K);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Adam step on a flat parameter vector (optimiser of the decoupled hypernet updates, Sec. III-C):
 //   m <- b1 m + (1 - b1) g,  v <- b2 v + (1 - b2) g^2,
 //   theta <- theta - lr (m c1) / (sqrt(v c2) + eps),  c1 = 1 / (1 - b1^t), c2 = 1 / (1 - b2^t)

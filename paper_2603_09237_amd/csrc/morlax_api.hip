@@ -187,8 +187,10 @@ extern "C" int64_t morlax_workspace_bytes(const morlax_ctx* c, const morlax_rows
     int64_t b = hyper_ws_bytes(c);
     int64_t m = mlp_ws_bytes(c, rs);
     int64_t l = loss_ws_bytes(c, rs);
+    int64_t n = advnorm_ws_bytes(c, rs);
     if (m > b) b = m;
     if (l > b) b = l;
+    if (n > b) b = n;
     return b;
 }
 
@@ -327,6 +329,19 @@ extern "C" int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const 
     const double c2 = 1.0 / (1.0 - std::pow((double)beta2, (double)step));
     launch_adam_step(hparams, dhparams, m, v, morlax_hparam_count(ctx, net), lr, beta1, beta2, eps, (float)c1,
                      (float)c2, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_scalarize_normalized(morlax_ctx* ctx, const morlax_rows* rows, const float* adv_vec,
+                                           const float* w, float* adv_out, void* ws, void* stream) {
+    const char* who = "morlax_scalarize_normalized";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
+    REQ(adv_vec, who); REQ(w, who); REQ(adv_out, who); REQ(ws, who);
+    RowSel rs;
+    int rc = resolve_rows(ctx, rows, ctx->d.T, rs, who);
+    if (rc != MORLAX_OK) return rc;
+    launch_scalarize_normalized(ctx, rs, adv_vec, w, adv_out, ws, (hipStream_t)stream);
     return finish(who);
 }
 

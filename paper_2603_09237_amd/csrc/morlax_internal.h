@@ -79,6 +79,10 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
                           int norm_adv, float* dmu, float* dlogsig, float* dv, float* stats,
                           void* ws, hipStream_t s);
 
+int64_t advnorm_ws_bytes(const morlax_ctx* c, const RowSel& rs);
+void launch_scalarize_normalized(const morlax_ctx* c, const RowSel& rs, const float* adv_vec, const float* w,
+                                 float* adv_out, void* ws, hipStream_t s);
+
 int64_t hyper_ws_bytes(const morlax_ctx* c);
 void launch_hypernet_fwd(const morlax_ctx* c, int net, const float* hparams, const float* w,
                          void* theta_mat, float* theta_vec, void* ws, hipStream_t s);

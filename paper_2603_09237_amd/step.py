@@ -17,12 +17,15 @@ from .configs import Config, WDTYPE_BF16
 
 class UpdateStep:
     def __init__(self, cfg: Config, device: str = "cuda:0", keep_adv_vec: bool = False, two_streams: bool = False,
-                 optimizer: dict | None = None, side_hypernet: bool = False):
+                 optimizer: dict | None = None, side_hypernet: bool = False, adv_norm: str = "scalar"):
         """optimizer = dict(lr_actor, lr_critic, beta1, beta2, eps): take one Adam step on either hypernet
         after every minibatch (a true PPO update); None: gradients only, parameters stay fixed.
         side_hypernet: the hypernet calls (backward, optimiser step, the next minibatch's forward) run on a second
         stream next to the grouped GEMMs of the other network / the next minibatch; the GEMM chain stays on the
-        caller's stream.  two_streams: the older split, one stream per network family."""
+        caller's stream.  two_streams: the older split, one stream per network family.
+        adv_norm: "scalar" = the scalarised advantage is normalised over the minibatch (inside the loss call);
+        "per_objective" = every objective is standardised over the minibatch before scalarisation
+        (scalarize_normalized, then the loss without further normalisation)."""
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -55,7 +58,10 @@ class UpdateStep:
         self.v_roll = torch.empty(T + 1, N, K, **f32)
         self.vtarg = torch.empty(T, N, K, **f32)
         self.adv_s = torch.empty(T, N, **f32)
-        self.adv_vec = torch.empty(T, N, K, **f32) if keep_adv_vec else None
+        assert adv_norm in ("scalar", "per_objective")
+        self.adv_norm = adv_norm
+        self.adv_vec = torch.empty(T, N, K, **f32) if (keep_adv_vec or adv_norm == "per_objective") else None
+        self.adv_mb = torch.empty(T, N, **f32) if adv_norm == "per_objective" else None
         self.mu = torch.zeros(T, N, A, **f32)
         self.v = torch.zeros(T, N, K, **f32)
         self.dmu = torch.zeros(T, N, A, **f32)
@@ -151,9 +157,17 @@ class UpdateStep:
 
         self._per_net(fwd)
         logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
-        ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, self.adv_s,
-                          self.v, self.vtarg, c.clip_eps, 1, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
+        self._loss(rows, logsig)
         self._per_net(bwd)
+
+    def _loss(self, rows, logsig):
+        c, ctx = self.cfg, self.ctx
+        adv, norm = self.adv_s, 1
+        if self.adv_norm == "per_objective":
+            ctx.scalarize_normalized(rows, self.adv_vec, self.w, self.adv_mb, self.ws)
+            adv, norm = self.adv_mb, 0
+        ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, adv,
+                          self.v, self.vtarg, c.clip_eps, norm, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
 
     def run(self, on_minibatch=None):
         """One whole update step.  `on_minibatch(e, b)` (optional) is called after each minibatch."""
@@ -211,8 +225,7 @@ class UpdateStep:
                 ctx.policy_fwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, out[net],
                                saved=self.saved[net], ws=self.ws)
             logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
-            ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, self.adv_s,
-                              self.v, self.vtarg, c.clip_eps, 1, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
+            self._loss(rows, logsig)
             for net in nets:
                 if dtheta_free[net] is not None:
                     main.wait_event(dtheta_free[net])

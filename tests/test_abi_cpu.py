@@ -114,6 +114,12 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
     with pytest.raises(binding.MorlaxError) as e:      # more extreme trade-offs than objectives
         ctx.sample_preferences(good, cfg.K + 1, good, stream=0)
     assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:      # the vector advantage has T rows, not T + 1
+        ctx.scalarize_normalized((0, cfg.T + 1, 0, cfg.n_g), good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.scalarize_normalized((0, 1, 0, 1), good, None, good, good, stream=0)
+    assert e.value.code == binding.ERR_NULL
     with pytest.raises(binding.MorlaxError) as e:      # the truncation mask is not optional here
         ctx.vec_gae_trunc(good, good, good, None, good, 0.99, 0.95, None, good, good, stream=0)
     assert e.value.code == binding.ERR_NULL

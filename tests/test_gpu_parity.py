@@ -535,6 +535,68 @@ def test_update_step_with_optimizer_matches_oracle(schedule, torch, binding):
         assert (~small).mean() > 0.5, float((~small).mean())
 
 
+@pytest.mark.parametrize("cfg,rows", [(CONFIGS[1], None), (RAGGED, (1, 5, 2, 19)), (CONFIGS[3], None), (CONFIGS[5], "mb"),
+                                      (scaled(RAGGED, name="ragged-K16", K=16, T=19), None)],
+                         ids=lambda x: getattr(x, "name", str(x)))
+def test_scalarize_normalized_matches_oracle(cfg, rows, torch, binding):
+    """Per-objective standardisation + scalarisation of a vector advantage whose objectives differ in scale."""
+    ctx = binding.Context.from_config(cfg)
+    if rows == "mb":
+        rows = (0, cfg.T, cfg.n_g // cfg.minibatches, cfg.n_g // cfg.minibatches)
+    if rows is None:
+        rows = (0, cfg.T, 0, cfg.n_g)
+    say(f"scalarize_normalized {cfg.name} rows={rows}")
+    rng = np.random.default_rng([11, cfg.K, cfg.N])
+    scale = 10.0 ** rng.uniform(-1, 1, size=cfg.K)
+    adv = (rng.standard_normal((cfg.T, cfg.N, cfg.K)) * scale + rng.standard_normal(cfg.K) * scale).astype(np.float32)
+    w = inputs.make_all(cfg)["w"]
+    SENT = -7.5
+    out = torch.full((cfg.T, cfg.N), SENT, device="cuda")
+    ws = torch.empty(ctx.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
+    ctx.scalarize_normalized(rows, dev(adv), dev(w), out, ws)
+    torch.cuda.synchronize()
+    ref = orc.scalarize_normalized(cfg, rows, adv, w)
+    mask = orc.row_mask(cfg, rows, cfg.T)
+    got = to_np(out)
+    assert np.all(got[~mask] == SENT)                      # cells outside the selection are not written
+    assert_close32(got, ref, "adv_out", mask=mask)
+    assert np.abs(ref[mask]).max() > 0.5
+
+
+def test_update_step_per_objective_normalisation_matches_oracle(torch, binding):
+    from paper_2603_09237_amd.step import UpdateStep
+    cfg = scaled(CONFIGS[1], name="cfg1-advk", minibatches=2, epochs=1)
+    say(f"update_step per-objective normalisation {cfg.name}")
+    st = UpdateStep(cfg, adv_norm="per_objective")
+    d = inputs.make_all(cfg)
+    st.load_inputs(d)
+    grads = []
+
+    def grab(e, b):
+        torch.cuda.synchronize()
+        grads.append((to_np(st.dhp[ACTOR]).copy(), to_np(st.dhp[CRITIC]).copy()))
+
+    st.run(on_minibatch=grab)
+    torch.cuda.synchronize()
+    res = orc.update_step(cfg, d["w"], d["hparams_actor_old"], d["hparams_critic_old"], d["hparams_actor"],
+                          d["hparams_critic"], d["obs"], d["rewards"], d["dones"], d["eps"], cfg.gamma, cfg.lam,
+                          cfg.clip_eps, cfg.minibatches, cfg.epochs, adv_norm="per_objective")
+    plain = orc.update_step(cfg, d["w"], d["hparams_actor_old"], d["hparams_critic_old"], d["hparams_actor"],
+                            d["hparams_critic"], d["obs"], d["rewards"], d["dones"], d["eps"], cfg.gamma, cfg.lam,
+                            cfg.clip_eps, cfg.minibatches, cfg.epochs)
+    for i, (ga, gc) in enumerate(grads):
+        for net, got, key in ((ACTOR, ga, "dhp_actor"), (CRITIC, gc, "dhp_critic")):
+            ref = res["grads"][i][key]
+            for name, (o, shp) in orc.hparam_layout(cfg, net).items():
+                if name == "_total":
+                    continue
+                sl = slice(o, o + int(np.prod(shp)))
+                sc = max(float(np.abs(ref[sl]).max()), 1e-30)
+                assert np.abs(got[sl] - ref[sl]).max() <= 1e-3 * sc + 1e-7, (i, key, name)
+        # and it is not the other reading
+        assert np.abs(ga - plain["grads"][i]["dhp_actor"]).max() > 1e-2 * np.abs(ga).max()
+
+
 def run_step(cfg, torch, keep_adv_vec=True):
     from paper_2603_09237_amd.step import UpdateStep
     st = UpdateStep(cfg, keep_adv_vec=keep_adv_vec)
