@@ -18,61 +18,121 @@ void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Vector GAE.  One lane per (environment, objective): a wave holds G = 64 / K environments with
-// their K objectives in adjacent lanes, so every load of r[t] and v[t] is one contiguous run of
-// G*K floats and the scalarisation sum_k w_k A_k is a K-lane shuffle reduction.  The scan over t
-// is sequential per lane; loads of U steps are issued before the U dependent updates.
-template <int U>
-__global__ __launch_bounds__(256) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
+// Vector GAE (Sec. III-C, update phase: the estimator applied to every objective on its own, then
+// scalarised).  One lane per (environment, objective): a wave holds G = 64 / K environments with their
+// K objectives in adjacent lanes, so every load of r[t] and v[t] is one contiguous run of G*K floats and
+// the scalarisation sum_k w_k A_k is a K-lane shuffle reduction.
+//
+// The recursion over t, A_t = cut_t ? a_t : a_t + gl A_{t+1} (a_t = r_t - V_t at an episode end, else the
+// TD error; cut_t = episode end or time limit), is a chain of affine maps, so the time axis is split as
+// well: the four waves of a workgroup take four consecutive chunks of up to GAE_CH steps of the same
+// lanes.  A wave requests all loads of its chunk at once, runs the recursion from zero (A'_t), and posts
+// the value at its first step and whether its chunk holds a cut.  After a barrier it folds the posts of
+// the later chunks into the advantage that enters its own chunk, x, and finishes
+// A_t = (a cut between t and the chunk's end) ? A'_t : A'_t + gl^(steps to the chunk's end) x.
+// Cuts stay selects throughout, so nothing behind an episode end -- NaN and Inf included -- reaches the
+// steps before it.  Horizons above 4 * GAE_CH are walked in groups of four chunks, last group first.
+template <int GAE_CH, int NW, int OCC>
+__global__ __launch_bounds__(64 * NW, OCC) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
                                                 const uint8_t* __restrict__ done,
                                                 const uint8_t* __restrict__ trunc, const float* __restrict__ w,
                                                 float gamma, float gl, float* __restrict__ adv_vec,
                                                 float* __restrict__ vtarg, float* __restrict__ adv_s,
-                                                int T, int N, int K, int n_g) {
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+                                                int T, int N, int K, int n_g, int ch) {
+    __shared__ float post_a[2][NW][WAVE];
+    __shared__ uint8_t post_cut[2][NW][WAVE];
+    __shared__ float carry[2][WAVE];
+    // cw: chunk within the group; made visibly wave-uniform so that the step offsets stay in scalar registers
+    const int lane = threadIdx.x & (WAVE - 1), cw = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int G = WAVE / K;
     const int e = lane / K, k = lane - e * K;
-    const int n = wave * G + e;
+    const int n = blockIdx.x * G + e;
     const bool live = (e < G) && (n < N);
     const int64_t NK = (int64_t)N * K;
     const int64_t idx = (int64_t)n * K + k;
     const float wk = live ? w[(n / n_g) * K + k] : 0.f;
-    float vn = live ? v[(int64_t)T * NK + idx] : 0.f;
-    float acc = 0.f;
-    int t = T - 1;
-    while (t >= 0) {
-        float rt[U], vt[U];
-        uint8_t dn[U], tr[U];
+    float gl_ch = 1.f;  // gl^ch: what a whole chunk without a cut multiplies the entering advantage by
+    for (int m = 0; m < ch; ++m) gl_ch *= gl;
+
+    const int n_chunks = (T + ch - 1) / ch, n_groups = (n_chunks + NW - 1) / NW;
+    for (int g = n_groups - 1, it = 0; g >= 0; --g, ++it) {
+        const int buf = it & 1;  // posts and carries alternate between two slots: one barrier per group
+        const int c = NW * g + cw;
+        const int t0 = c * ch;
+        int len = T - t0;
+        len = len < 0 ? 0 : (len > ch ? ch : len);
+        // loads of the whole chunk
+        float rt[GAE_CH], vt[GAE_CH + 1];
+        uint32_t cutm = 0, donem = 0;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int tt = t - u;
-            const bool ok = live && tt >= 0;
-            rt[u] = ok ? r[(int64_t)tt * NK + idx] : 0.f;
-            vt[u] = ok ? v[(int64_t)tt * NK + idx] : 0.f;
-            dn[u] = ok ? done[(int64_t)tt * N + n] : (uint8_t)0;
-            tr[u] = (ok && trunc) ? trunc[(int64_t)tt * N + n] : (uint8_t)0;
+        for (int u = 0; u < GAE_CH; ++u) {
+            const bool ok = live && u < len;
+            const int64_t o = (int64_t)(t0 + u) * NK + idx;
+            rt[u] = ok ? r[o] : 0.f;
+            vt[u] = ok ? v[o] : 0.f;
+            const uint32_t dn = ok ? done[(int64_t)(t0 + u) * N + n] : 0u;
+            const uint32_t tr = (ok && trunc) ? trunc[(int64_t)(t0 + u) * N + n] : 0u;
+            donem |= ((dn && !tr) ? 1u : 0u) << u;  // a time limit keeps the bootstrap whatever `done` says
+            cutm |= ((dn | tr) ? 1u : 0u) << u;
         }
+        // V after the chunk's last step (exists up to t = T)
+        float vnext = (live && len > 0) ? v[(int64_t)(t0 + len) * NK + idx] : 0.f;
+        // chunk-local recursion from zero, last step first
+        float ap[GAE_CH];
+        float acc = 0.f;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int tt = t - u;
-            if (tt < 0) break;  // uniform across the wave
-            const float d_done = rt[u] - vt[u];
-            const float d_live = rt[u] + gamma * vn - vt[u];
-            acc = dn[u] ? d_done : (d_live + gl * acc);
-            acc = tr[u] ? d_live : acc;  // a time limit keeps the bootstrap and restarts the sum
-            float s = wk * acc;
-            float tot = s;
-            for (int j = 1; j < K; ++j) tot += __shfl_down(s, j, WAVE);
-            if (live) {
-                const int64_t o = (int64_t)tt * NK + idx;
-                if (adv_vec) adv_vec[o] = acc;
-                vtarg[o] = acc + vt[u];
-                if (k == 0) adv_s[(int64_t)tt * N + n] = tot;
+        for (int u = GAE_CH - 1; u >= 0; --u) {
+            if (u < len) {
+                const float vn = (u + 1 < len) ? vt[(u + 1) & (GAE_CH - 1)] : vnext;
+                const float d_done = rt[u] - vt[u];
+                const float d_live = rt[u] + gamma * vn - vt[u];
+                const bool dn = (donem >> u) & 1u, ct = (cutm >> u) & 1u;
+                acc = dn ? d_done : (ct ? d_live : d_live + gl * acc);
             }
-            vn = vt[u];
+            ap[u] = acc;
         }
-        t -= U;
+        post_a[buf][cw][lane] = ap[0];
+        post_cut[buf][cw][lane] = (uint8_t)(cutm != 0);
+        __syncthreads();
+        // advantage entering this chunk: later chunks of the group folded onto the group's carry-in
+        float x = (it == 0) ? 0.f : carry[buf ^ 1][lane];
+        for (int j = NW - 1; j > cw; --j) {
+            int lj = T - (NW * g + j) * ch;
+            lj = lj < 0 ? 0 : (lj > ch ? ch : lj);
+            float f = gl_ch;
+            if (lj < ch) {  // the last chunk of the horizon may be short (uniform)
+                f = 1.f;
+                for (int m = 0; m < lj; ++m) f *= gl;
+            }
+            if (lj > 0) x = post_cut[buf][j][lane] ? post_a[buf][j][lane] : post_a[buf][j][lane] + f * x;
+        }
+        // finish the chunk and write it out
+        uint32_t cut_after = 0;  // a cut at or after step u, within the chunk
+        float f = gl;            // gl^(steps from u to the chunk's end)
+#pragma unroll
+        for (int u = GAE_CH - 1; u >= 0; --u) {
+            if (u < len) {
+                cut_after |= (cutm >> u) & 1u;
+                ap[u] = cut_after ? ap[u] : ap[u] + f * x;
+                f *= gl;
+            }
+        }
+        if (cw == 0) carry[buf][lane] = ap[0];  // read by every wave after the next group's barrier
+#pragma unroll
+        for (int u = 0; u < GAE_CH; ++u) {
+            if (u < len) {  // uniform across the wave
+                const float a = ap[u];
+                const float sc = wk * a;
+                float tot = sc;
+                for (int j = 1; j < K; ++j) tot += __shfl_down(sc, j, WAVE);
+                if (live) {
+                    const int64_t o = (int64_t)(t0 + u) * NK + idx;
+                    if (adv_vec) adv_vec[o] = a;
+                    vtarg[o] = a + vt[u];
+                    if (k == 0) adv_s[(int64_t)(t0 + u) * N + n] = tot;
+                }
+            }
+        }
     }
 }
 
@@ -81,10 +141,15 @@ void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const u
                     float* vtarg, float* adv_s, hipStream_t s) {
     const int K = c->d.K, N = c->d.N, T = c->d.T;
     const int G = WAVE / K;
-    const int waves = (N + G - 1) / G;
-    const int blocks = (waves + 3) / 4;
-    k_vec_gae<8><<<blocks, 256, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s, T, N, K,
-                                        c->n_g);
+    const int blocks = (N + G - 1) / G;
+    // the chunks of one group cover the horizon when it is short; CH steps each, in several groups, when it is long
+    // eight chunks of up to eight steps, at most 64 registers per lane (eight waves per SIMD): the fastest of the
+    // shapes tried at T = 64 (16 x 4: 36 us, 8 x 8: 30 us, 4 x 16: 33 us for 81 MB)
+    constexpr int CH = 8, NW = 8;
+    int ch = (T + NW - 1) / NW;
+    ch = ch > CH ? CH : ch;
+    k_vec_gae<CH, NW, 8><<<blocks, 64 * NW, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s,
+                                                   T, N, K, c->n_g, ch);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -112,7 +112,9 @@ def run_gae(cfg, torch, binding, r, v, done, w, want_vec=True):
 
 
 @pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, scaled(RAGGED, name="ragged-K16", K=16, T=19),
-                                              scaled(RAGGED, name="ragged-K1", K=1, T=1)],
+                                              scaled(RAGGED, name="ragged-K1", K=1, T=1),
+                                              # a horizon of several groups of chunks, the last chunk cut short
+                                              scaled(RAGGED, name="ragged-T150", K=5, T=150)],
                          ids=lambda c: c.name)
 def test_vec_gae_matches_oracle(cfg, torch, binding):
     say(f"vec_gae {cfg.name}")
@@ -137,7 +139,8 @@ def test_vec_gae_matches_oracle(cfg, torch, binding):
     assert np.array_equal(vt2, vtarg) and np.array_equal(as2, adv_s)
 
 
-@pytest.mark.parametrize("cfg", [CONFIGS[1], RAGGED, CONFIGS[5]], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [CONFIGS[1], RAGGED, CONFIGS[5], scaled(RAGGED, name="ragged-T150", K=5, T=150)],
+                         ids=lambda c: c.name)
 def test_vec_gae_trunc_matches_oracle(cfg, torch, binding):
     """Time limits keep the bootstrap and restart the sum; without any the plain scan is reproduced bit for bit."""
     say(f"vec_gae_trunc {cfg.name}")
