@@ -88,6 +88,24 @@ def bench_kernel(a, cfg):
                 ctx.adam_step(net, th[net], g[net], m[net], v[net], 3e-4, 0.9, 0.999, 1e-8, step[0])
         units, unit_name, bytes_per_launch = sum(n), "parameters/s", 28.0 * sum(n)   # 4 arrays read, 3 written
         metric = "adam_step_params_per_sec"
+    elif a.row == "ppo_loss_grad":
+        rows = (0, T, 0, cfg.n_g // cfg.minibatches)          # one minibatch, as in the update step
+        A, P = cfg.act_dim, cfg.P
+        mu = torch.tanh(torch.randn(T, N, A, device="cuda"))
+        act = mu + 0.6 * torch.randn(T, N, A, device="cuda")
+        logsig = torch.full((P, A), -0.5, device="cuda")
+        logp_old = -0.5 * (((act - mu) / 0.6065) ** 2).sum(-1) + 0.5 * A - 0.9189 * A + 0.02 * torch.randn(T, N, device="cuda")
+        adv_s = torch.randn(T, N, device="cuda")
+        v, vt = torch.randn(T, N, K, device="cuda"), torch.randn(T, N, K, device="cuda")
+        dmu, dv = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, K, device="cuda")
+        dls, stats = torch.empty(P, A, device="cuda"), torch.empty(8, device="cuda")
+        ws = torch.empty(ctx.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
+        launch = lambda: ctx.ppo_loss_grad(rows, mu, logsig, A, act, logp_old, adv_s, v, vt, cfg.clip_eps, 1, dmu, dls,
+                                           dv, stats, ws)
+        cells = T * N // cfg.minibatches
+        # mu, act (A each), logp_old, adv_s (twice: statistics, then the loss), v, vtarg (K each) read; dmu, dv written
+        units, unit_name, bytes_per_launch = cells, "env-steps/s", 4.0 * (2 * A + 3 + 2 * K + A + K) * cells
+        metric = "ppo_loss_grad_env_steps_per_sec"
     elif a.row == "scalarize_normalized":
         rows = (0, T, 0, cfg.n_g // cfg.minibatches)          # one minibatch, as in the update step
         adv = torch.randn(T, N, K, device="cuda")
@@ -146,7 +164,7 @@ def main():
                          "in flight stretch each other's event-timed durations)")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
-    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "scalarize_normalized"), default="update_step",
+    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "ppo_loss_grad", "scalarize_normalized"), default="update_step",
                     help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")

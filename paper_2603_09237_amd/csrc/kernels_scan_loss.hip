@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void k_ppo_loss_grad(
     const float* __restrict__ v, const float* __restrict__ vtarg, const double* __restrict__ adv_stat,
     float clip_eps, int norm_adv, float inv_B, float* __restrict__ dmu, float* __restrict__ dv,
     double* __restrict__ stat_part, double* __restrict__ dls_part, int N, int n_g, int A, int K) {
-    __shared__ double sh[4];
+    __shared__ float red[5 + A_MAX][256 + 16];
     __shared__ float s_ls[A_MAX], s_isig[A_MAX];
     const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
     if (threadIdx.x < A) {
@@ -288,19 +288,29 @@ __global__ __launch_bounds__(256) void k_ppo_loss_grad(
             dv[row * K + k] = 2.f * dd * inv_B;
         }
     }
+    // block sums of the 5 statistics and the A log-sigma terms: the per-cell values go to LDS (one padded row
+    // per quantity), then 16 lanes add up each row in fp64 -- 16 values each in ascending order, then four
+    // exchange steps -- so the whole reduction costs two barriers and has a fixed order
     const int64_t b = (int64_t)p * gridDim.x + blockIdx.x;
-    const double r0 = block_sum((double)l_pi, sh), r1 = block_sum((double)l_v, sh),
-                 r2 = block_sum((double)clipped, sh), r3 = block_sum((double)kl, sh),
-                 r4 = block_sum((double)rho_s, sh);
-    if (threadIdx.x == 0) {
-        stat_part[b * 5 + 0] = r0; stat_part[b * 5 + 1] = r1; stat_part[b * 5 + 2] = r2;
-        stat_part[b * 5 + 3] = r3; stat_part[b * 5 + 4] = r4;
-    }
+    const int nq = 5 + A;
+    red[0][threadIdx.x] = l_pi; red[1][threadIdx.x] = l_v; red[2][threadIdx.x] = clipped;
+    red[3][threadIdx.x] = kl; red[4][threadIdx.x] = rho_s;
 #pragma unroll
-    for (int a = 0; a < A_MAX; ++a) {
-        if (a < A) {
-            const double t = block_sum((double)dls[a], sh);
-            if (threadIdx.x == 0) dls_part[b * A + a] = t;
+    for (int a = 0; a < A_MAX; ++a)
+        if (a < A) red[5 + a][threadIdx.x] = dls[a];
+    __syncthreads();
+    const int qi = threadIdx.x >> 4, li = threadIdx.x & 15;
+    for (int q = qi; q < nq; q += 16) {  // (a wave's four groups of 16 lanes take the same number of turns)
+        double t = 0.0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) t += (double)red[q][16 * j + li];
+        t += __shfl_xor(t, 8, WAVE);
+        t += __shfl_xor(t, 4, WAVE);
+        t += __shfl_xor(t, 2, WAVE);
+        t += __shfl_xor(t, 1, WAVE);
+        if (li == 0) {
+            if (q < 5) stat_part[b * 5 + q] = t;
+            else dls_part[b * A + (q - 5)] = t;
         }
     }
 }
