@@ -77,8 +77,11 @@ def hparam_layout(d, net):
     add("Wh1", (F, K)); add("bh1", (F,)); add("Wh2", (F, F)); add("bh2", (F,))
     for l, (do, di) in enumerate(layer_shapes(d, net)):
         add(f"W0_{l}", (do, di)); add(f"b0_{l}", (do,))
-        add(f"MA_{l}", (do * r, F)); add(f"cA_{l}", (do * r,))
-        add(f"MB_{l}", (r * di, F)); add(f"cB_{l}", (r * di,))
+        if r < 0:       # strictly affine: one row of M per weight
+            add(f"MW_{l}", (do * di, F))
+        else:
+            add(f"MA_{l}", (do * r, F)); add(f"cA_{l}", (do * r,))
+            add(f"MB_{l}", (r * di, F)); add(f"cB_{l}", (r * di,))
         add(f"Mb_{l}", (do, F))
     if net == ACTOR:
         add("logsig0", (d.act_dim,)); add("Msig", (d.act_dim, F))
@@ -169,15 +172,20 @@ def hypernet_fwd(d, net, hparams, w):
     """H(w) = M f(w) + b (Sec. III-B), read as: f a two-layer tanh MLP K -> F -> F; the affine map
     emits, per target layer l, factors A_l [d_out, r] and B_l [r, d_in] and a bias delta, and the
     layer's weights are W_l = W0_l + A_l B_l, b_l = b0_l + Mb_l f; the actor also gets
-    log sigma = logsig0 + Msig f.  Returns theta_mat [P, mat_len] (layers concatenated, each
-    [d_out, d_in] row-major) and theta_vec [P, vec_len] (biases, then the actor's log sigma)."""
+    log sigma = logsig0 + Msig f.  With d.rank < 0 the map is the strictly affine one of the section's
+    equation, every weight its own row of M: W_l = W0_l + (MW_l f) reshaped to [d_out, d_in].
+    Returns theta_mat [P, mat_len] (layers concatenated, each [d_out, d_in] row-major) and
+    theta_vec [P, vec_len] (biases, then the actor's log sigma)."""
     hp, w, h1, f = _hyper_cache(d, net, hparams, w)
     P, r = w.shape[0], d.rank
     mats, vecs = [], []
     for l, (do, di) in enumerate(layer_shapes(d, net)):
-        A = (f @ hp[f"MA_{l}"].T + hp[f"cA_{l}"]).reshape(P, do, r)
-        B = (f @ hp[f"MB_{l}"].T + hp[f"cB_{l}"]).reshape(P, r, di)
-        W = hp[f"W0_{l}"][None] + np.einsum("pok,pki->poi", A, B)
+        if r < 0:
+            W = hp[f"W0_{l}"][None] + (f @ hp[f"MW_{l}"].T).reshape(P, do, di)
+        else:
+            A = (f @ hp[f"MA_{l}"].T + hp[f"cA_{l}"]).reshape(P, do, r)
+            B = (f @ hp[f"MB_{l}"].T + hp[f"cB_{l}"]).reshape(P, r, di)
+            W = hp[f"W0_{l}"][None] + np.einsum("pok,pki->poi", A, B)
         mats.append(W.reshape(P, do * di))
         vecs.append(hp[f"b0_{l}"][None] + f @ hp[f"Mb_{l}"].T)
     if net == ACTOR:
@@ -203,20 +211,26 @@ def hypernet_bwd(d, net, hparams, w, dtheta_mat, dtheta_vec):
     df = np.zeros_like(f)
     moff = voff = 0
     for l, (do, di) in enumerate(layer_shapes(d, net)):
-        A = (f @ hp[f"MA_{l}"].T + hp[f"cA_{l}"]).reshape(P, do, r)
-        B = (f @ hp[f"MB_{l}"].T + hp[f"cB_{l}"]).reshape(P, r, di)
         dW = dtheta_mat[:, moff:moff + do * di].reshape(P, do, di)
         db = dtheta_vec[:, voff:voff + do]
         moff += do * di
         voff += do
         put(f"W0_{l}", dW.sum(axis=0))
         put(f"b0_{l}", db.sum(axis=0))
-        dA = np.einsum("poi,pki->pok", dW, B).reshape(P, do * r)
-        dB = np.einsum("pok,poi->pki", A, dW).reshape(P, r * di)
-        put(f"MA_{l}", dA.T @ f); put(f"cA_{l}", dA.sum(axis=0))
-        put(f"MB_{l}", dB.T @ f); put(f"cB_{l}", dB.sum(axis=0))
+        if r < 0:
+            dWf = dW.reshape(P, do * di)
+            put(f"MW_{l}", dWf.T @ f)
+            df += dWf @ hp[f"MW_{l}"]
+        else:
+            A = (f @ hp[f"MA_{l}"].T + hp[f"cA_{l}"]).reshape(P, do, r)
+            B = (f @ hp[f"MB_{l}"].T + hp[f"cB_{l}"]).reshape(P, r, di)
+            dA = np.einsum("poi,pki->pok", dW, B).reshape(P, do * r)
+            dB = np.einsum("pok,poi->pki", A, dW).reshape(P, r * di)
+            put(f"MA_{l}", dA.T @ f); put(f"cA_{l}", dA.sum(axis=0))
+            put(f"MB_{l}", dB.T @ f); put(f"cB_{l}", dB.sum(axis=0))
+            df += dA @ hp[f"MA_{l}"] + dB @ hp[f"MB_{l}"]
         put(f"Mb_{l}", db.T @ f)
-        df += dA @ hp[f"MA_{l}"] + dB @ hp[f"MB_{l}"] + db @ hp[f"Mb_{l}"]
+        df += db @ hp[f"Mb_{l}"]
     if net == ACTOR:
         dls = dtheta_vec[:, voff:voff + d.act_dim]
         put("logsig0", dls.sum(axis=0)); put("Msig", dls.T @ f)

@@ -36,7 +36,7 @@ def hparam_blocks(cfg: Config, net: int):
     """Flat order of a hypernetwork's parameter blocks: (name, shape, kind, scale).
 
     Order: trunk (Wh1, bh1, Wh2, bh2); per target layer (W0, b0, MA, cA, MB, cB,
-    Mb); for the actor finally (logsig0, Msig).  All blocks row-major.
+    Mb) -- with rank < 0 (W0, b0, MW, Mb) --; for the actor finally (logsig0, Msig).  All blocks row-major.
     """
     K, F, r = cfg.K, cfg.hyper_width, cfg.rank
     blocks = [("Wh1", (F, K), "normal", K ** -0.5), ("bh1", (F,), "const", 0.0),
@@ -44,12 +44,15 @@ def hparam_blocks(cfg: Config, net: int):
     for l, (do, di) in enumerate(layer_shapes(cfg, net)):
         s = 0.3 * (max(r, 1) * di) ** -0.25
         blocks += [(f"W0_{l}", (do, di), "normal", di ** -0.5),
-                   (f"b0_{l}", (do,), "const", 0.0),
-                   (f"MA_{l}", (do * r, F), "normal", s * F ** -0.5),
-                   (f"cA_{l}", (do * r,), "normal", s),
-                   (f"MB_{l}", (r * di, F), "normal", s * F ** -0.5),
-                   (f"cB_{l}", (r * di,), "normal", s),
-                   (f"Mb_{l}", (do, F), "normal", 0.1 * F ** -0.5)]
+                   (f"b0_{l}", (do,), "const", 0.0)]
+        if r < 0:   # strictly affine hypernetwork: a row of M per weight, sized so that |M f| ~ 0.13 |W0|
+            blocks += [(f"MW_{l}", (do * di, F), "normal", 0.26 * di ** -0.5 * F ** -0.5)]
+        else:
+            blocks += [(f"MA_{l}", (do * r, F), "normal", s * F ** -0.5),
+                       (f"cA_{l}", (do * r,), "normal", s),
+                       (f"MB_{l}", (r * di, F), "normal", s * F ** -0.5),
+                       (f"cB_{l}", (r * di,), "normal", s)]
+        blocks += [(f"Mb_{l}", (do, F), "normal", 0.1 * F ** -0.5)]
     if net == NET_ACTOR:
         blocks += [("logsig0", (cfg.act_dim,), "const", -0.5),
                    ("Msig", (cfg.act_dim, F), "normal", 0.1 * F ** -0.5)]

@@ -136,9 +136,12 @@ def t_hypernet(d, net, hp_t, w_t):
     P = w_t.shape[0]
     Ws, bs = [], []
     for l, (do, di) in enumerate(orc.layer_shapes(d, net)):
-        A = F.linear(f, get(f"MA_{l}"), get(f"cA_{l}")).reshape(P, do, d.rank)
-        B = F.linear(f, get(f"MB_{l}"), get(f"cB_{l}")).reshape(P, d.rank, di)
-        Ws.append(get(f"W0_{l}")[None] + torch.bmm(A, B))
+        if d.rank < 0:
+            Ws.append(get(f"W0_{l}")[None] + F.linear(f, get(f"MW_{l}")).reshape(P, do, di))
+        else:
+            A = F.linear(f, get(f"MA_{l}"), get(f"cA_{l}")).reshape(P, do, d.rank)
+            B = F.linear(f, get(f"MB_{l}"), get(f"cB_{l}")).reshape(P, d.rank, di)
+            Ws.append(get(f"W0_{l}")[None] + torch.bmm(A, B))
         bs.append(get(f"b0_{l}")[None] + F.linear(f, get(f"Mb_{l}")))
     logsig = get("logsig0")[None] + F.linear(f, get("Msig")) if net == orc.ACTOR else None
     return Ws, bs, logsig
@@ -160,8 +163,48 @@ def t_mlp(d, net, Ws, bs, x_t, rows):
     return torch.stack(outs)
 
 
-def test_hypernet_fwd_and_bwd_match_torch_autograd():
-    d = tiny()
+def test_strictly_affine_hypernet_is_one_matrix_product():
+    """rank < 0: the section's equation as it stands -- theta = M f(w) + b with one stacked M and b over all
+    parameters of the target network, rows in the order theta_mat | theta_vec."""
+    d = tiny(rank=-1)
+    for net in (orc.ACTOR, orc.CRITIC):
+        hp = rand_hparams(d, net, 7)
+        w = rand_w(d, 8)
+        lay = orc.hparam_layout(d, net)
+        blk = lambda n: hp[lay[n][0]:lay[n][0] + int(np.prod(lay[n][1]))].reshape(lay[n][1])
+        shapes = orc.layer_shapes(d, net)
+        M = [blk(f"MW_{l}") for l in range(len(shapes))] + [blk(f"Mb_{l}") for l in range(len(shapes))]
+        b = [blk(f"W0_{l}").reshape(-1) for l in range(len(shapes))] + [blk(f"b0_{l}") for l in range(len(shapes))]
+        if net == orc.ACTOR:
+            M.append(blk("Msig")); b.append(blk("logsig0"))
+        M, b = np.concatenate(M, axis=0), np.concatenate(b)
+        assert M.shape == (orc.theta_mat_len(d, net) + orc.theta_vec_len(d, net), d.hyper_width)
+        f = np.tanh(np.tanh(w @ blk("Wh1").T + blk("bh1")) @ blk("Wh2").T + blk("bh2"))
+        theta = f @ M.T + b
+        tm, tv = orc.hypernet_fwd(d, net, hp, w)
+        assert np.allclose(np.concatenate([tm, tv], axis=1), theta, rtol=1e-13, atol=1e-14)
+        # every block of the flat vector is accounted for: trunk + M + b
+        assert lay["_total"][0] == M.size + b.size + d.hyper_width * (d.K + d.hyper_width + 2)
+
+
+def test_strictly_affine_hypernet_with_zero_matrix_is_the_rank_zero_net():
+    d_aff, d_r0 = tiny(rank=-1), tiny(rank=0)
+    for net in (orc.ACTOR, orc.CRITIC):
+        hp0 = rand_hparams(d_r0, net, 9)
+        lay0, lay1 = orc.hparam_layout(d_r0, net), orc.hparam_layout(d_aff, net)
+        hp1 = np.zeros(lay1["_total"][0])
+        for name, (o, shp) in lay0.items():
+            if name != "_total" and int(np.prod(shp)) > 0:
+                o1 = lay1[name][0]
+                hp1[o1:o1 + int(np.prod(shp))] = hp0[o:o + int(np.prod(shp))]
+        w = rand_w(d_r0, 10)
+        a, b = orc.hypernet_fwd(d_r0, net, hp0, w), orc.hypernet_fwd(d_aff, net, hp1, w)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("rank", [2, -1])
+def test_hypernet_fwd_and_bwd_match_torch_autograd(rank):
+    d = tiny(rank=rank)
     for net in (orc.ACTOR, orc.CRITIC):
         hp = rand_hparams(d, net, 4)
         w = rand_w(d, 5)
@@ -257,10 +300,10 @@ def make_case(d, seed=0, pert=0.15):
     return w, hp_a0, hp_c0, hp_a, hp_c, obs, rew, done, eps
 
 
-@pytest.mark.parametrize("act,mb", [(orc.ACT_TANH, 1), (orc.ACT_SILU, 2)])
-def test_update_step_gradients_match_torch_autograd(act, mb):
+@pytest.mark.parametrize("act,mb,rank", [(orc.ACT_TANH, 1, 2), (orc.ACT_SILU, 2, 2), (orc.ACT_SILU, 1, -1)])
+def test_update_step_gradients_match_torch_autograd(act, mb, rank):
     """The whole hand-derived reverse pass (loss -> target nets -> hypernets) against autograd."""
-    d = tiny(act=act, N=12, P=3)
+    d = tiny(act=act, N=12, P=3, rank=rank)
     w, hp_a0, hp_c0, hp_a, hp_c, obs, rew, done, eps = make_case(d, 20)
     res = orc.update_step(d, w, hp_a0, hp_c0, hp_a, hp_c, obs, rew, done, eps, 0.99, 0.95, 0.2,
                           minibatches=mb, epochs=1, keep=True)
