@@ -88,6 +88,31 @@ def bench_kernel(a, cfg):
                 ctx.adam_step(net, th[net], g[net], m[net], v[net], 3e-4, 0.9, 0.999, 1e-8, step[0])
         units, unit_name, bytes_per_launch = sum(n), "parameters/s", 28.0 * sum(n)   # 4 arrays read, 3 written
         metric = "adam_step_params_per_sec"
+    elif a.row == "hypernet_affine":
+        # the strictly affine hypernetwork (rank = -1) at the workload's shapes: forward and backward of both networks
+        from paper_2603_09237_amd.configs import scaled
+        cfg = scaled(cfg, name=cfg.name + "-affine", rank=-1)
+        ctx = binding.Context.from_config(cfg)
+        P, F = cfg.P, cfg.hyper_width
+        wdt = torch.bfloat16 if cfg.wdtype == 1 else torch.float32
+        w = dev(inputs.make_preferences(cfg))
+        ws = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device="cuda")
+        nets = []
+        for net in (0, 1):
+            ml, vl, nh = ctx.theta_mat_len(net), ctx.theta_vec_len(net), ctx.hparam_count(net)
+            nets.append(dict(hp=torch.randn(nh, device="cuda") * 0.05, tm=torch.empty(P, ml, dtype=wdt, device="cuda"),
+                             tv=torch.empty(P, vl, device="cuda"), dtm=torch.randn(P, ml, device="cuda") * 1e-3,
+                             dtv=torch.randn(P, vl, device="cuda") * 1e-3, dhp=torch.empty(nh, device="cuda"), ml=ml))
+
+        def launch():
+            for net, d in enumerate(nets):
+                ctx.hypernet_fwd(net, d["hp"], w, d["tm"], d["tv"], ws)
+                ctx.hypernet_bwd(net, d["hp"], w, d["dtm"], d["dtv"], d["dhp"], ws)
+        esz = 2 if cfg.wdtype == 1 else 4
+        # forward: M read, theta written; backward: dtheta read twice (dM, df), M read once, dM written
+        per_el = (4.0 * F + esz * P) + (2 * 4.0 * P + 2 * 4.0 * F)
+        units = sum(d["ml"] for d in nets)
+        unit_name, bytes_per_launch, metric = "weights/s", per_el * units, "hypernet_affine_weights_per_sec"
     elif a.row == "ppo_loss_grad":
         rows = (0, T, 0, cfg.n_g // cfg.minibatches)          # one minibatch, as in the update step
         A, P = cfg.act_dim, cfg.P
@@ -164,7 +189,8 @@ def main():
                          "in flight stretch each other's event-timed durations)")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
-    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "ppo_loss_grad", "scalarize_normalized"), default="update_step",
+    ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "ppo_loss_grad", "scalarize_normalized",
+                                     "hypernet_affine"), default="update_step",
                     help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")

@@ -57,7 +57,7 @@ typedef struct {
     int32_t obs_dim, act_dim;
     int32_t n_hidden, width;
     int32_t act;         /* hidden activation: 0 tanh, 1 SiLU */
-    int32_t rank;        /* r >= 0 */
+    int32_t rank;        /* r >= 0: rank of the per-preference weight delta; -1: strictly affine hypernetwork */
     int32_t hyper_width; /* F */
     int32_t wdtype;      /* 0: fp32 weights and GEMM inputs; 1: bf16 weights and GEMM inputs, fp32 accumulate */
     int32_t mean_tanh;   /* 1: actor mean = tanh(z) (Sec. III-E); 0: mean = z */
@@ -69,7 +69,7 @@ typedef struct {
 } morlax_rows;
 
 /* Limits: 1 <= K <= 16, 1 <= act_dim <= 16, 1 <= obs_dim <= 1024, 1 <= n_hidden <= 8,
- * width a multiple of 16 in [16, 2048], 0 <= rank <= 32, 1 <= hyper_width <= 64, P >= 2, P | N. */
+ * width a multiple of 16 in [16, 2048], -1 <= rank <= 32, 1 <= hyper_width <= 64, P >= 2, P | N. */
 int morlax_create(const morlax_dims* dims, morlax_ctx** out);
 void morlax_destroy(morlax_ctx* ctx);
 const char* morlax_last_error(void); /* thread-local, never NULL */
@@ -90,8 +90,10 @@ int morlax_env_pref_index(const morlax_ctx* ctx, int32_t* out, void* stream);
 /* Hypernetwork forward H(w) = M f(w) + b (Sec. III-B) for all P trade-offs: f is a two-layer tanh
  * MLP K -> F -> F; the affine map emits per target layer the factors A_l [d_out, r], B_l [r, d_in]
  * and a bias delta; W_l(p) = W0_l + A_l(p) B_l(p), b_l(p) = b0_l + Mb_l f(p); actor:
- * log sigma(p) = logsig0 + Msig f(p).  All arithmetic fp32; theta_mat rounded once (nearest even)
- * when dims.wdtype is bf16.
+ * log sigma(p) = logsig0 + Msig f(p).  With dims.rank = -1 the map is the section's equation as it
+ * stands: every weight has its own row of M, W_l(p) = W0_l + reshape(MW_l f(p)), MW_l [d_out * d_in, F]
+ * stored in hparams where the factor maps would be (block order per layer: W0, b0, MW, Mb).
+ * All arithmetic fp32; theta_mat rounded once (nearest even) when dims.wdtype is bf16.
  *   hparams [hparam_count] fp32, w [P, K] fp32 (rows on the simplex; not checked on the device)
  *   -> theta_mat [P, theta_mat_len] (wdtype), theta_vec [P, theta_vec_len] fp32. */
 int morlax_hypernet_fwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,

@@ -1,10 +1,11 @@
 // Hypernetwork forward and backward (paper Sec. III-B: H(w) = M f(w) + b, read as rank-r factors on
-// shared base weights).  fp32 arithmetic; theta_mat is rounded to bf16 (nearest even) on store when
+// shared base weights; with rank < 0 the strictly affine form, every weight its own row of M, which runs
+// entirely through the stacked affine map below).  fp32 arithmetic; theta_mat is rounded to bf16 (nearest even) on store when
 // the target networks run in bf16.  Every reduction is fixed-order.
 #include "morlax_internal.h"
 #include "numeric.h"
 
-#define QW 64  // stacked-affine rows per wave of the df partial kernel
+#define QW 64  // stacked-affine rows per wave of the df partial kernel (at least)
 #define DAB_COLS 128  // columns of dW one block of the fused dA/dB kernel walks
 #define DAB_NCT (DAB_COLS / 64)
 #define DAB_MAX_CS (2048 / DAB_COLS)  // column runs of the widest layer
@@ -15,9 +16,18 @@ struct HyperWs {
     int n_chunk, n_cs;
 };
 
+// stacked-affine rows per wave of the df partial kernel: QW, more when there are very many rows (strictly
+// affine hypernetwork), so that the partials stay a few thousand chunks
+static int df_chunk_rows(int64_t q_total) {
+    int qw = QW;
+    while ((q_total + qw - 1) / qw > 4096) qw *= 2;
+    return qw;
+}
+
 static HyperWs hyper_ws_layout(const morlax_ctx* c, void* ws, int64_t* total) {
     const int64_t P = c->d.P, F = c->d.hyper_width;
-    int64_t fac = c->net[0].fac_len > c->net[1].fac_len ? c->net[0].fac_len : c->net[1].fac_len;
+    const bool affine = c->d.rank < 0;  // no factor vector: the leading stacked rows are theta_mat itself
+    int64_t fac = affine ? 0 : (c->net[0].fac_len > c->net[1].fac_len ? c->net[0].fac_len : c->net[1].fac_len);
     int64_t q = c->aff[0].q_total > c->aff[1].q_total ? c->aff[0].q_total : c->aff[1].q_total;
     HyperWs L;
     float* p = reinterpret_cast<float*>(ws);
@@ -33,7 +43,15 @@ static HyperWs hyper_ws_layout(const morlax_ctx* c, void* ws, int64_t* total) {
     }
     L.fac = take(P * fac);
     L.dfac = take(P * fac);
-    L.n_chunk = (int)((q + QW - 1) / QW);
+    {  // chunks of the df partials: each network with its own rows per chunk
+        L.n_chunk = 0;
+        for (int n = 0; n < 2; ++n) {
+            const int64_t qn = c->aff[n].q_total;
+            const int qw = df_chunk_rows(qn);
+            const int nc = (int)((qn + qw - 1) / qw);
+            L.n_chunk = nc > L.n_chunk ? nc : L.n_chunk;
+        }
+    }
     L.df_part = take((int64_t)L.n_chunk * P * F);
     L.mrow = reinterpret_cast<int32_t*>(take(q));
     {
@@ -81,8 +99,9 @@ __device__ inline int find_seg(const AffineTable& at, int q) {
 
 // Stacked affine map: row q for every preference.  Thread per row with its M row in registers; f[p, :]
 // is read through wave-uniform addresses (scalar loads), so the inner product costs no LDS traffic.
+template <typename TF>  // type of the leading rows' destination: float factors, or theta_mat (strictly affine form)
 __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const float* __restrict__ hp,
-                                                     const float* __restrict__ f, float* __restrict__ fac,
+                                                     const float* __restrict__ f, TF* __restrict__ fac,
                                                      float* __restrict__ theta_vec, int P, int F,
                                                      int64_t fac_len, int64_t vec_len) {
     const int q = blockIdx.x * 256 + threadIdx.x;
@@ -94,8 +113,13 @@ __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const floa
     const float* mr = hp + at.hp_m[s] + loc * F;
 #pragma unroll
     for (int j = 0; j < MORLAX_MAX_F; ++j) m[j] = (j < F) ? mr[j] : 0.f;
-    float* dst = (q < fac_len) ? (fac + q) : (theta_vec + (q - fac_len));
-    const int64_t stride = (q < fac_len) ? fac_len : vec_len;
+    const bool lead = q < fac_len;
+    TF* dst_f = fac + q;
+    float* dst_v = theta_vec + (q - fac_len);
+    auto put = [&](int p, float a) {
+        if (lead) dst_f[(int64_t)p * fac_len] = cvt<TF>(a);
+        else dst_v[(int64_t)p * vec_len] = a;
+    };
     // blockIdx.y takes a run of preferences (one run: more did not pay, the per-thread row of M is reloaded)
     const int per = (P + gridDim.y - 1) / gridDim.y;
     const int p_lo = blockIdx.y * per, p_hi = (p_lo + per < P) ? (p_lo + per) : P;
@@ -111,14 +135,14 @@ __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const floa
                 for (int j = 0; j < 32; ++j) a[u] += m[j] * fp[j];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) dst[(int64_t)(p + u) * stride] = a[u];
+            for (int u = 0; u < 4; ++u) put(p + u, a[u]);
         }
         for (; p < p_hi; ++p) {
             const float* fp = f + (int64_t)p * 32;
             float a = c;
 #pragma unroll
             for (int j = 0; j < 32; ++j) a += m[j] * fp[j];
-            dst[(int64_t)p * stride] = a;
+            put(p, a);
         }
     } else {
         for (int p = p_lo; p < p_hi; ++p) {
@@ -127,7 +151,7 @@ __global__ __launch_bounds__(256) void k_hyper_affine(AffineTable at, const floa
 #pragma unroll
             for (int j = 0; j < MORLAX_MAX_F; ++j)
                 if (j < F) a += m[j] * fp[j];
-            dst[(int64_t)p * stride] = a;
+            put(p, a);
         }
     }
 }
@@ -206,7 +230,8 @@ static void run_trunk_and_affine(const morlax_ctx* c, int net, const float* hp, 
     const int P = c->d.P, F = c->d.hyper_width;
     k_hyper_trunk<<<P, 64, 0, s>>>(hp, w, L.h1, L.f, c->d.K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
     float* tv = theta_vec_or_null ? theta_vec_or_null : vec_scratch;
-    k_hyper_affine<<<dim3((at.q_total + 255) / 256, 1), 256, 0, s>>>(at, hp, L.f, L.fac, tv, P, F, nd.fac_len, nd.vec_len);
+    k_hyper_affine<float><<<dim3((at.q_total + 255) / 256, 1), 256, 0, s>>>(at, hp, L.f, L.fac, tv, P, F, nd.fac_len,
+                                                                            nd.vec_len);
 }
 
 static MatTiles mat_tiles(const NetDev& nd) {
@@ -225,6 +250,20 @@ void launch_hypernet_fwd(const morlax_ctx* c, int net, const float* hparams, con
                          void* theta_mat, float* theta_vec, void* ws, hipStream_t s) {
     const NetDev& nd = c->net[net];
     HyperWs L = hyper_ws_layout(c, ws, nullptr);
+    if (c->d.rank < 0) {
+        // strictly affine form (Sec. III-B as written): the stacked map writes theta_mat and theta_vec directly
+        const AffineTable& at = c->aff[net];
+        const int P = c->d.P, F = c->d.hyper_width;
+        k_hyper_trunk<<<P, 64, 0, s>>>(hparams, w, L.h1, L.f, c->d.K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
+        const dim3 grid((at.q_total + 255) / 256, 1);
+        if (c->d.wdtype == 1)
+            k_hyper_affine<bf16_t><<<grid, 256, 0, s>>>(at, hparams, L.f, (bf16_t*)theta_mat, theta_vec, P, F, nd.fac_len,
+                                                        nd.vec_len);
+        else
+            k_hyper_affine<float><<<grid, 256, 0, s>>>(at, hparams, L.f, (float*)theta_mat, theta_vec, P, F, nd.fac_len,
+                                                       nd.vec_len);
+        return;
+    }
     run_trunk_and_affine(c, net, hparams, w, L, theta_vec, nullptr, s);
     MatTiles mt = mat_tiles(nd);
     const dim3 grid(mt.tile0[nd.n_layers], c->d.P);
@@ -464,7 +503,7 @@ __global__ __launch_bounds__(256) void k_hyper_mrow(AffineTable at, int32_t* __r
     mrow[q] = (int32_t)(at.hp_m[s] + (int64_t)(q - at.q0[s]) * F);
 }
 
-// df partials on fp32 MFMA: part[chunk, p, j] = sum over the chunk's QW stacked rows q of g[p, q] M[q, j].
+// df partials on fp32 MFMA: part[chunk, p, j] = sum over the chunk's qw stacked rows q of g[p, q] M[q, j].
 // One wave per chunk; lane (ln, kg) feeds rows p = 16 pt + ln of g and columns j = 16 jt + ln of M for the
 // contraction indices q0 + 4 kg + e, e = 0..3 (one MFMA per e).
 template <int JT>
@@ -472,12 +511,12 @@ __global__ __launch_bounds__(256) void k_hyper_df_part(const float* __restrict__
                                                       const float* __restrict__ dfac,
                                                       const float* __restrict__ dvec, float* __restrict__ part,
                                                       int P, int F, int64_t fac_len, int64_t vec_len, int q_total,
-                                                      int n_chunk) {
+                                                      int n_chunk, int qw) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ln = lane & 15, kg = lane >> 4;
     const int chunk = blockIdx.x * 4 + wave;
     if (chunk >= n_chunk) return;
-    const int qa = chunk * QW;
-    const int qb = (qa + QW < q_total) ? (qa + QW) : q_total;
+    const int qa = chunk * qw;
+    const int qb = (qa + qw < q_total) ? (qa + qw) : q_total;
     for (int p0 = 0; p0 < P; p0 += 128) {
         float4_t acc[8][JT];
 #pragma unroll
@@ -645,9 +684,17 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
     const AffineTable& at = c->aff[net];
     const int P = c->d.P, F = c->d.hyper_width, r = c->d.rank, K = c->d.K;
     HyperWs L = hyper_ws_layout(c, ws, nullptr);
-    // recompute f and the factors; the theta_vec rows of the affine map land in a scratch nobody reads
-    run_trunk_and_affine(c, net, hparams, w, L, nullptr, L.vecs, s);
-    k_hyper_dbase<<<(int)((nd.mat_len / 4 + 255) / 256), 256, 0, s>>>(nd, dtheta_mat, dhparams, P);
+    const bool affine = r < 0;
+    // the gradient of the leading stacked rows: of the factor vector, or (strictly affine form) of theta_mat itself
+    const float* dlead = affine ? dtheta_mat : L.dfac;
+    if (affine) {
+        // only f is needed again; dW0 and dMW come out of k_hyper_dM below (W0 is the constant term of those rows)
+        k_hyper_trunk<<<P, 64, 0, s>>>(hparams, w, L.h1, L.f, K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
+    } else {
+        // recompute f and the factors; the theta_vec rows of the affine map land in a scratch nobody reads
+        run_trunk_and_affine(c, net, hparams, w, L, nullptr, L.vecs, s);
+        k_hyper_dbase<<<(int)((nd.mat_len / 4 + 255) / 256), 256, 0, s>>>(nd, dtheta_mat, dhparams, P);
+    }
     if (r > 0) {
         DabWork wk;
         wk.n = 0;
@@ -666,16 +713,17 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
         if (split)
             k_hyper_dA_merge<<<dim3((int)((nd.fac_len + 255) / 256), P), 256, 0, s>>>(nd, L.da_part, L.dfac, r, P);
     }
-    k_hyper_dM<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.f, L.dfac, dtheta_vec, dhparams, P, F, nd.fac_len,
+    k_hyper_dM<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.f, dlead, dtheta_vec, dhparams, P, F, nd.fac_len,
                                                        nd.vec_len);
     k_hyper_mrow<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.mrow, F);
-    const int n_chunk = (at.q_total + QW - 1) / QW;
+    const int qw = df_chunk_rows(at.q_total);
+    const int n_chunk = (at.q_total + qw - 1) / qw;
     if (F <= 32)
-        k_hyper_df_part<2><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, L.dfac, dtheta_vec, L.df_part, P, F,
-                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk);
+        k_hyper_df_part<2><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, dlead, dtheta_vec, L.df_part, P, F,
+                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk, qw);
     else
-        k_hyper_df_part<4><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, L.dfac, dtheta_vec, L.df_part, P, F,
-                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk);
+        k_hyper_df_part<4><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, dlead, dtheta_vec, L.df_part, P, F,
+                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk, qw);
     k_hyper_df_final<<<(P * F + 63) / 64, 256, 0, s>>>(L.df_part, n_chunk, L.f, L.dz2, P * F);
     k_hyper_trunk_bwd_a<<<(F * F + F + P * F + 255) / 256, 256, 0, s>>>(hparams, L.h1, L.dz2, L.dz1, dhparams, P, F,
                                                                        nd.hp_wh2, nd.hp_bh2);

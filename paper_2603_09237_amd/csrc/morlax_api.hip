@@ -24,7 +24,10 @@ extern "C" const char* morlax_last_error(void) { return g_err; }
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at) {
-    const int64_t F = d.hyper_width, r = d.rank, K = d.K;
+    // rank < 0: strictly affine hypernetwork -- every weight has its own row of M (stored where the factor maps
+    // of the low-rank form would be) and W0 is its constant term; there are no factors
+    const bool affine = d.rank < 0;
+    const int64_t F = d.hyper_width, r = affine ? 0 : d.rank, K = d.K;
     const int out = (net == MORLAX_ACTOR) ? d.act_dim : d.K;
     nd.n_layers = d.n_hidden + 1;
     nd.out_dim = out;
@@ -43,7 +46,7 @@ static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at
         L.fac_b = fac; fac += r * (int64_t)L.d_in;
         L.hp_w0 = hp; hp += (int64_t)L.d_out * L.d_in;
         L.hp_b0 = hp; hp += L.d_out;
-        L.hp_ma = hp; hp += (int64_t)L.d_out * r * F;
+        L.hp_ma = hp; hp += affine ? (int64_t)L.d_out * L.d_in * F : (int64_t)L.d_out * r * F;
         L.hp_ca = hp; hp += (int64_t)L.d_out * r;
         L.hp_mb = hp; hp += r * (int64_t)L.d_in * F;
         L.hp_cb = hp; hp += r * (int64_t)L.d_in;
@@ -66,6 +69,9 @@ static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at
         q += rows;
         at.q0[s + 1] = q;
     };
+    if (affine)
+        for (int l = 0; l < nd.n_layers; ++l)  // the rows of theta_mat, in its own order
+            seg(nd.layer[l].hp_ma, nd.layer[l].hp_w0, (int32_t)(nd.layer[l].d_out * nd.layer[l].d_in));
     if (r > 0)
         for (int l = 0; l < nd.n_layers; ++l) {
             const LayerDev& L = nd.layer[l];
@@ -77,7 +83,7 @@ static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at
     at.q_total = q;
     nd.mat_len = mat;
     nd.vec_len = vec;
-    nd.fac_len = fac;
+    nd.fac_len = affine ? mat : fac;  // the leading rows of the stacked map: factor vector, or theta_mat itself
     nd.hp_count = hp;
 }
 
@@ -86,8 +92,8 @@ extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
     *out = nullptr;
     const morlax_dims& d = *dims;
     if (d.K < 1 || d.T < 1 || d.N < 1 || d.obs_dim < 1 || d.act_dim < 1 || d.n_hidden < 1 ||
-        d.width < 1 || d.rank < 0 || d.hyper_width < 1)
-        return fail(MORLAX_ERR_SHAPE, "morlax_create: K, T, N, obs_dim, act_dim, n_hidden, width, hyper_width must be >= 1 and rank >= 0");
+        d.width < 1 || d.rank < -1 || d.hyper_width < 1)
+        return fail(MORLAX_ERR_SHAPE, "morlax_create: K, T, N, obs_dim, act_dim, n_hidden, width, hyper_width must be >= 1 and rank >= -1");
     if (d.P < 2) return fail(MORLAX_ERR_SHAPE, "morlax_create: need P > 1 trade-off vectors (got %d)", d.P);
     if (d.N % d.P != 0)
         return fail(MORLAX_ERR_SHAPE, "morlax_create: P = %d must divide N = %d", d.P, d.N);
@@ -123,6 +129,10 @@ extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
     c->n_g = d.N / d.P;
     build_net(d, MORLAX_ACTOR, c->net[0], c->aff[0]);
     build_net(d, MORLAX_CRITIC, c->net[1], c->aff[1]);
+    if (c->net[0].hp_count >= ((int64_t)1 << 31) || c->net[1].hp_count >= ((int64_t)1 << 31)) {
+        delete c;  // rows of the stacked affine matrix are addressed with 32-bit offsets into hparams
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: a hypernetwork with 2^31 or more parameters");
+    }
     *out = c;
     return MORLAX_OK;
 }

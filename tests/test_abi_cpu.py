@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_layout_queries_match_oracle_and_generator(lib):
-    for cid, cfg in configs.CONFIGS.items():
+    affine = [configs.scaled(configs.CONFIGS[i], name=f"cfg{i}-affine", rank=-1) for i in (1, 5)]
+    for cfg in list(configs.CONFIGS.values()) + affine:
         ctx = binding.Context.from_config(cfg)
         for net in (0, 1):
             assert ctx.hparam_count(net) == orc.hparam_count(cfg, net) == inputs.hparam_count(cfg, net)
@@ -45,7 +46,7 @@ def test_layout_queries_match_oracle_and_generator(lib):
 
 @pytest.mark.parametrize("over,code", [
     (dict(P=1), binding.ERR_SHAPE), (dict(P=3), binding.ERR_SHAPE), (dict(K=0), binding.ERR_SHAPE),
-    (dict(T=0), binding.ERR_SHAPE), (dict(rank=-1), binding.ERR_SHAPE), (dict(K=17), binding.ERR_UNSUPPORTED),
+    (dict(T=0), binding.ERR_SHAPE), (dict(rank=-2), binding.ERR_SHAPE), (dict(K=17), binding.ERR_UNSUPPORTED),
     (dict(width=40), binding.ERR_UNSUPPORTED), (dict(act=2), binding.ERR_UNSUPPORTED),
     (dict(wdtype=3), binding.ERR_UNSUPPORTED), (dict(rank=64), binding.ERR_UNSUPPORTED),
     (dict(hyper_width=128), binding.ERR_UNSUPPORTED), (dict(n_hidden=9), binding.ERR_UNSUPPORTED),

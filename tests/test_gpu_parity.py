@@ -276,7 +276,12 @@ def hyper_case(cfg, net):
     return inputs.make_hparams(cfg, net), inputs.make_preferences(cfg)
 
 
-@pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, RAGGED_BF16, scaled(RAGGED, name="rank0", rank=0)],
+# the strictly affine hypernetwork (rank = -1): a ragged fp32 case, a bf16 case, and workload 3's shapes
+AFFINE_CASES = [scaled(RAGGED, name="ragged-affine", rank=-1), scaled(RAGGED_BF16, name="ragged-bf16-affine", rank=-1),
+                scaled(CONFIGS[3], name="cfg3-affine", rank=-1)]
+
+
+@pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, RAGGED_BF16, scaled(RAGGED, name="rank0", rank=0)] + AFFINE_CASES,
                          ids=lambda c: c.name)
 def test_hypernet_fwd_matches_oracle(cfg, torch, binding):
     ctx = binding.Context.from_config(cfg)
@@ -303,7 +308,8 @@ def test_hypernet_fwd_matches_oracle(cfg, torch, binding):
             assert same > 0.999, same
 
 
-@pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, scaled(RAGGED, name="rank0", rank=0)], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, scaled(RAGGED, name="rank0", rank=0)] + AFFINE_CASES,
+                         ids=lambda c: c.name)
 def test_hypernet_bwd_matches_oracle(cfg, torch, binding):
     ctx = binding.Context.from_config(cfg)
     ws = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device="cuda")
@@ -617,7 +623,8 @@ def run_step(cfg, torch, keep_adv_vec=True):
 
 
 @pytest.mark.parametrize("cfg", [CONFIGS[1], scaled(CONFIGS[1], name="cfg1-mb2x2", minibatches=2, epochs=2),
-                                 scaled(RAGGED, name="ragged-step", minibatches=1), CONFIGS[2]],
+                                 scaled(RAGGED, name="ragged-step", minibatches=1), CONFIGS[2],
+                                 scaled(CONFIGS[1], name="cfg1-affine-step", rank=-1, minibatches=2, epochs=1)],
                          ids=lambda c: c.name)
 def test_update_step_fp32_matches_oracle(cfg, torch, binding):
     say(f"update_step fp32 {cfg.name}")
