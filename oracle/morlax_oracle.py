@@ -48,9 +48,22 @@ ACT_TANH, ACT_SILU = 0, 1
 
 # --------------------------------------------------------------------------- shapes
 
+def sigma_state(d):
+    """True when the actor's standard deviation is an output of the network (state dependent) instead of
+    a per-preference vector from the hypernetwork."""
+    return bool(getattr(d, "sigma_state", 0))
+
+
+def head_dim(d, net):
+    """Width of a network's output layer: K values, or A means (+ A log sigmas when state dependent)."""
+    if net != ACTOR:
+        return d.K
+    return 2 * d.act_dim if sigma_state(d) else d.act_dim
+
+
 def layer_shapes(d, net):
-    """(d_out, d_in) per dense layer: O -> W, (W -> W) x (L-1), W -> A (actor) or K (critic)."""
-    out = d.act_dim if net == ACTOR else d.K
+    """(d_out, d_in) per dense layer: O -> W, (W -> W) x (L-1), W -> A or 2A (actor) or K (critic)."""
+    out = head_dim(d, net)
     widths = [d.obs_dim] + [d.width] * d.n_hidden + [out]
     return [(widths[i + 1], widths[i]) for i in range(len(widths) - 1)]
 
@@ -61,7 +74,7 @@ def theta_mat_len(d, net):
 
 def theta_vec_len(d, net):
     n = sum(do for do, _ in layer_shapes(d, net))
-    return n + (d.act_dim if net == ACTOR else 0)
+    return n + (d.act_dim if (net == ACTOR and not sigma_state(d)) else 0)
 
 
 def hparam_layout(d, net):
@@ -83,7 +96,7 @@ def hparam_layout(d, net):
             add(f"MA_{l}", (do * r, F)); add(f"cA_{l}", (do * r,))
             add(f"MB_{l}", (r * di, F)); add(f"cB_{l}", (r * di,))
         add(f"Mb_{l}", (do, F))
-    if net == ACTOR:
+    if net == ACTOR and not sigma_state(d):
         add("logsig0", (d.act_dim,)); add("Msig", (d.act_dim, F))
     lay["_total"] = (off, ())
     return lay
@@ -188,7 +201,7 @@ def hypernet_fwd(d, net, hparams, w):
             W = hp[f"W0_{l}"][None] + np.einsum("pok,pki->poi", A, B)
         mats.append(W.reshape(P, do * di))
         vecs.append(hp[f"b0_{l}"][None] + f @ hp[f"Mb_{l}"].T)
-    if net == ACTOR:
+    if net == ACTOR and not sigma_state(d):
         vecs.append(hp["logsig0"][None] + f @ hp["Msig"].T)
     return np.concatenate(mats, axis=1), np.concatenate(vecs, axis=1)
 
@@ -231,7 +244,7 @@ def hypernet_bwd(d, net, hparams, w, dtheta_mat, dtheta_vec):
             df += dA @ hp[f"MA_{l}"] + dB @ hp[f"MB_{l}"]
         put(f"Mb_{l}", db.T @ f)
         df += db @ hp[f"Mb_{l}"]
-    if net == ACTOR:
+    if net == ACTOR and not sigma_state(d):
         dls = dtheta_vec[:, voff:voff + d.act_dim]
         put("logsig0", dls.sum(axis=0)); put("Msig", dls.T @ f)
         df += dls @ hp["Msig"]
@@ -267,7 +280,9 @@ def _split_theta(d, net, theta_mat, theta_vec, p):
         bs.append(np.asarray(theta_vec[p, voff:voff + do], dtype=np.float64))
         moff += do * di
         voff += do
-    logsig = np.asarray(theta_vec[p, voff:voff + d.act_dim], dtype=np.float64) if net == ACTOR else None
+    logsig = None
+    if net == ACTOR and not sigma_state(d):
+        logsig = np.asarray(theta_vec[p, voff:voff + d.act_dim], dtype=np.float64)
     return Ws, bs, logsig
 
 
@@ -290,13 +305,17 @@ def _mlp_forward(d, net, Ws, bs, X, emulate_bf16):
         if l < nl - 1:
             hs.append(_act(z, d.act))
     z = zs[-1]
-    out = np.tanh(z) if (net == ACTOR and d.mean_tanh) else z
+    out = z
+    if net == ACTOR and d.mean_tanh:     # only the means are squashed, a state-dependent log sigma is not
+        out = z.copy()
+        out[:, :d.act_dim] = np.tanh(z[:, :d.act_dim])
     return hs, zs, out
 
 
 def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=False, prefs=None):
     """Rollout-phase forward of the family {pi_i} or {V_i} (Sec. III-C): environment n is served by
-    the network of preference g(n).  x is [Tx, N, O]; returns `out` [Tx, N, A or K] and, when the
+    the network of preference g(n).  x is [Tx, N, O]; returns `out` [Tx, N, A or K] (with a state-
+    dependent standard deviation the actor's `out` is [Tx, N, 2A]: means, then log sigmas) and, when the
     Gaussian noise eps [Tx, N, A] is given (actor only), the sampled action a = mu + sigma * eps
     and its log-density log p = sum_j [ -((a_j - mu_j)/sigma_j)^2 / 2 - log sigma_j ] - (A/2) log 2 pi.
     Cells outside `rows` stay zero.  `prefs` (optional) restricts the work to those preference
@@ -304,7 +323,7 @@ def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=Fal
     x = np.asarray(x, dtype=np.float64)
     Tx = x.shape[0]
     t0, tc, j0, jc = rows
-    odim = d.act_dim if net == ACTOR else d.K
+    odim = head_dim(d, net)
     out = np.zeros((Tx, d.N, odim))
     act = logp = None
     if eps is not None:
@@ -320,11 +339,12 @@ def policy_fwd(d, net, theta_mat, theta_vec, x, rows, eps=None, emulate_bf16=Fal
         o = o.reshape(tc, jc, odim)
         out[t0:t0 + tc, idx[0]:idx[0] + jc, :] = o
         if eps is not None:
-            sig = np.exp(logsig)
+            mu = o[..., :d.act_dim]
+            ls = o[..., d.act_dim:] if sigma_state(d) else logsig   # per state, or per preference
             e = eps[t0:t0 + tc, idx[0]:idx[0] + jc, :]
-            a = o + sig * e
+            a = mu + np.exp(ls) * e
             act[t0:t0 + tc, idx[0]:idx[0] + jc, :] = a
-            logp[t0:t0 + tc, idx[0]:idx[0] + jc] = gaussian_logp(a, o, logsig)
+            logp[t0:t0 + tc, idx[0]:idx[0] + jc] = gaussian_logp(a, mu, ls)
     return out, act, logp
 
 
@@ -347,7 +367,7 @@ def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulat
     x = np.asarray(x, dtype=np.float64)
     dout = np.asarray(dout, dtype=np.float64)
     t0, tc, j0, jc = rows
-    odim = d.act_dim if net == ACTOR else d.K
+    odim = head_dim(d, net)
     dmat = np.zeros((d.P, theta_mat_len(d, net)))
     dvec = np.zeros((d.P, theta_vec_len(d, net)))
     dx = np.zeros_like(x) if want_dx else None
@@ -359,7 +379,8 @@ def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulat
         hs, zs, o = _mlp_forward(d, net, Ws, bs, X, emulate_bf16)
         dz = dout[t0:t0 + tc][:, idx, :].reshape(tc * jc, odim)
         if net == ACTOR and d.mean_tanh:
-            dz = dz * (1.0 - o * o)
+            dz = dz.copy()
+            dz[:, :d.act_dim] *= 1.0 - o[:, :d.act_dim] ** 2
         gW, gb = [None] * len(Ws), [None] * len(Ws)
         for l in range(len(Ws) - 1, -1, -1):
             gW[l] = rb(dz).T @ rb(hs[l])
@@ -374,6 +395,7 @@ def policy_bwd(d, net, theta_mat, theta_vec, x, rows, dout, dlogsig=None, emulat
         vec = np.concatenate(gb)
         dvec[p, :vec.size] = vec
     if net == ACTOR and dlogsig is not None:
+        assert not sigma_state(d), "a state-dependent log sigma is part of dout"
         dvec[:, -d.act_dim:] = np.asarray(dlogsig, dtype=np.float64)
     if want_dx:
         return dmat, dvec, dx
@@ -467,16 +489,21 @@ def ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, v, vtarg, clip_eps,
     else 0; dlogp/dmu_j = (a_j - mu_j)/sigma_j^2; dlogp/dlogsig_j = ((a_j-mu_j)/sigma_j)^2 - 1,
     summed over the rows of each preference; dL_V/dV_k = 2 (V_k - Vhat_k) / B.
     Returns dmu [Tx,N,A], dlogsig [P,A], dv [Tx,N,K] (zero outside the rows) and
-    stats = [L_pi, L_V, clip fraction, mean(logp_old - logp), adv mean, adv std, mean rho, B]."""
+    stats = [L_pi, L_V, clip fraction, mean(logp_old - logp), adv mean, adv std, mean rho, B].
+    With a state-dependent standard deviation `mu` is the actor's whole output [Tx,N,2A] (means, then
+    log sigmas), `logsig` is ignored, the first return value is the gradient of that output
+    [Tx,N,2A] (the log-sigma gradients stay per cell) and the second is None."""
     mu = np.asarray(mu, dtype=np.float64); act = np.asarray(act, dtype=np.float64)
     logp_old = np.asarray(logp_old, dtype=np.float64); adv_s = np.asarray(adv_s, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64); vtarg = np.asarray(vtarg, dtype=np.float64)
-    logsig = np.asarray(logsig, dtype=np.float64)
     Tx = mu.shape[0]
     mask = row_mask(d, rows, Tx)
     B = int(mask.sum())
     g = env_pref_index(d.N, d.P)
-    ls = logsig[g][None, :, :]                                  # [1, N, A]
+    if sigma_state(d):
+        mu, ls = mu[..., :d.act_dim], mu[..., d.act_dim:]           # [Tx, N, A] each
+    else:
+        ls = np.asarray(logsig, dtype=np.float64)[g][None, :, :]    # [1, N, A]
     sig = np.exp(ls)
     if norm_adv:
         m, s = adv_norm_stats(adv_s[:Tx], mask)
@@ -495,10 +522,14 @@ def ppo_loss_grad(d, rows, mu, logsig, act, logp_old, adv_s, v, vtarg, clip_eps,
     dlogp = np.where(live & mask, -ahat * rho / B, 0.0)       # [Tx, N]
     dmu = np.where(mask[..., None], dlogp[..., None] * q / sig, 0.0)
     dls_rows = np.where(mask[..., None], dlogp[..., None] * (q * q - 1.0), 0.0)   # [Tx, N, A]
-    dlogsig = np.zeros((d.P, d.act_dim))
-    for p in range(d.P):
-        sel = (g == p)
-        dlogsig[p] = dls_rows[:, sel, :].sum(axis=(0, 1))
+    if sigma_state(d):
+        dmu = np.concatenate([dmu, dls_rows], axis=-1)
+        dlogsig = None
+    else:
+        dlogsig = np.zeros((d.P, d.act_dim))
+        for p in range(d.P):
+            sel = (g == p)
+            dlogsig[p] = dls_rows[:, sel, :].sum(axis=(0, 1))
     dv = np.where(mask[..., None], 2.0 * dv_all / B, 0.0)
     clipped = (np.abs(rho - 1.0) > clip_eps)
     stats = np.array([L_pi, L_V, clipped[mask].mean(), (logp_old[:Tx] - logp)[mask].mean(),
@@ -572,7 +603,7 @@ def update_step(d, w, hp_actor_old, hp_critic_old, hp_actor, hp_critic, obs, rew
             tm_a, tm_c = wq(tm_a), wq(tm_c)
             mu, _, _ = policy_fwd(d, ACTOR, tm_a, tv_a, obs[:T], rows, emulate_bf16=emu)
             vv, _, _ = policy_fwd(d, CRITIC, tm_c, tv_c, obs[:T], rows, emulate_bf16=emu)
-            logsig = tv_a[:, -d.act_dim:]
+            logsig = None if sigma_state(d) else tv_a[:, -d.act_dim:]
             if adv_norm == "per_objective":
                 dmu, dlogsig, dv, stats = ppo_loss_grad(d, rows, mu, logsig, act, logp_old,
                                                         scalarize_normalized(d, rows, adv_vec, w), vv, vtarg,

@@ -143,7 +143,9 @@ def t_hypernet(d, net, hp_t, w_t):
             B = F.linear(f, get(f"MB_{l}"), get(f"cB_{l}")).reshape(P, d.rank, di)
             Ws.append(get(f"W0_{l}")[None] + torch.bmm(A, B))
         bs.append(get(f"b0_{l}")[None] + F.linear(f, get(f"Mb_{l}")))
-    logsig = get("logsig0")[None] + F.linear(f, get("Msig")) if net == orc.ACTOR else None
+    logsig = None
+    if net == orc.ACTOR and not getattr(d, "sigma_state", 0):
+        logsig = get("logsig0")[None] + F.linear(f, get("Msig"))
     return Ws, bs, logsig
 
 
@@ -159,7 +161,9 @@ def t_mlp(d, net, Ws, bs, x_t, rows):
             z = F.linear(h, Ws[l][p], bs[l][p])
             if l < len(Ws) - 1:
                 h = torch.tanh(z) if d.act == orc.ACT_TANH else F.silu(z)
-        outs.append(torch.tanh(z) if (net == orc.ACTOR and d.mean_tanh) else z)
+        if net == orc.ACTOR and d.mean_tanh:    # the means are squashed, a state-dependent log sigma is not
+            z = torch.cat([torch.tanh(z[:, :d.act_dim]), z[:, d.act_dim:]], dim=1)
+        outs.append(z)
     return torch.stack(outs)
 
 
@@ -268,6 +272,55 @@ def test_sampling_logp_closed_form_and_torch_normal():
     assert np.all(np.abs(mu) <= 1.0)
 
 
+def test_state_dependent_sigma_sampling_and_reduction_to_the_constant_case():
+    """sigma from the network's own output: closed form of the rollout log-density, and with the log-sigma
+    rows of the output layer zeroed (weights) and set to a constant (bias) the policy is exactly the one with
+    that constant per-preference log sigma."""
+    d1 = tiny(sigma_state=1)
+    A = d1.act_dim
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((d1.T, d1.N, d1.obs_dim))
+    eps = rng.standard_normal((d1.T, d1.N, A))
+    tm, tv = orc.hypernet_fwd(d1, orc.ACTOR, rand_hparams(d1, orc.ACTOR, 13), rand_w(d1))
+    assert tv.shape[1] == orc.theta_vec_len(d1, orc.ACTOR) == 2 * d1.width + 2 * A     # no log-sigma tail
+    out, act, logp = orc.policy_fwd(d1, orc.ACTOR, tm, tv, x, orc.full_rows(d1, d1.T), eps=eps)
+    assert out.shape[-1] == 2 * A
+    mu, ls = out[..., :A], out[..., A:]
+    assert np.all(np.abs(mu) <= 1.0)
+    closed = -0.5 * (eps ** 2).sum(-1) - ls.sum(-1) - 0.5 * A * math.log(2 * math.pi)
+    assert np.allclose(logp, closed, atol=1e-12)
+    assert np.allclose(act, mu + np.exp(ls) * eps, atol=1e-14)
+    # constant log sigma through the output layer = the per-preference vector of the other parametrisation
+    d0 = tiny(sigma_state=0)
+    shapes = orc.layer_shapes(d1, orc.ACTOR)
+    moff = sum(do * di for do, di in shapes[:-1])
+    voff = sum(do for do, _ in shapes[:-1])
+    do, di = shapes[-1]
+    tm1, tv1 = tm.copy(), tv.copy()
+    Wh = tm1[:, moff:].reshape(d1.P, do, di)
+    Wh[:, A:, :] = 0.0
+    c = rng.standard_normal((d1.P, A)) * 0.3
+    tv1[:, voff + A:voff + 2 * A] = c
+    tm0 = np.concatenate([tm1[:, :moff], Wh[:, :A, :].reshape(d1.P, -1)], axis=1)
+    tv0 = np.concatenate([tv1[:, :voff + A], c], axis=1)
+    o1, a1, l1 = orc.policy_fwd(d1, orc.ACTOR, tm1, tv1, x, orc.full_rows(d1, d1.T), eps=eps)
+    o0, a0, l0 = orc.policy_fwd(d0, orc.ACTOR, tm0, tv0, x, orc.full_rows(d0, d0.T), eps=eps)
+    assert np.allclose(o1[..., :A], o0, atol=1e-14) and np.allclose(a1, a0, atol=1e-14)
+    assert np.allclose(l1, l0, atol=1e-12)
+    # and the loss gradients agree: per-cell log-sigma gradients sum to the per-preference one
+    adv = rng.standard_normal((d1.T, d1.N))
+    v = rng.standard_normal((d1.T, d1.N, d1.K)); vt = rng.standard_normal((d1.T, d1.N, d1.K))
+    rows = orc.full_rows(d1, d1.T)
+    act_new = a1 + 0.1 * rng.standard_normal(a1.shape)
+    g1 = orc.ppo_loss_grad(d1, rows, o1, None, act_new, l1, adv, v, vt, 0.2)
+    g0 = orc.ppo_loss_grad(d0, rows, o0, c, act_new, l0, adv, v, vt, 0.2)
+    assert g1[1] is None and np.allclose(g1[0][..., :A], g0[0], atol=1e-14)
+    gidx = orc.env_pref_index(d1.N, d1.P)
+    per_pref = np.stack([g1[0][:, gidx == p, A:].sum(axis=(0, 1)) for p in range(d1.P)])
+    assert np.allclose(per_pref, g0[1], atol=1e-12)
+    assert np.allclose(g1[3], g0[3], atol=1e-12)
+
+
 def t_loss(d, rows, mu_t, logsig_t, act, logp_old, adv_s, v_t, vtarg, clip_eps, Tx):
     """float64 torch graph of the two losses on [P, M, .] tensors (selected rows only)."""
     t0, tc, j0, jc = rows
@@ -279,7 +332,10 @@ def t_loss(d, rows, mu_t, logsig_t, act, logp_old, adv_s, v_t, vtarg, clip_eps, 
                             for p in range(d.P)])
     a_s = sel(adv_s)
     ahat = (a_s - a_s.mean()) / (a_s.std(unbiased=False) + 1e-8)
-    ls = logsig_t[:, None, :]
+    if getattr(d, "sigma_state", 0):           # the network's own output: means, then log sigmas per state
+        mu_t, ls = mu_t[..., :d.act_dim], mu_t[..., d.act_dim:]
+    else:
+        ls = logsig_t[:, None, :]
     logp = torch.distributions.Normal(mu_t, torch.exp(ls)).log_prob(sel(act)).sum(-1)
     rho = torch.exp(logp - sel(logp_old))
     L_pi = -torch.minimum(rho * ahat, torch.clamp(rho, 1 - clip_eps, 1 + clip_eps) * ahat).mean()
@@ -300,10 +356,11 @@ def make_case(d, seed=0, pert=0.15):
     return w, hp_a0, hp_c0, hp_a, hp_c, obs, rew, done, eps
 
 
-@pytest.mark.parametrize("act,mb,rank", [(orc.ACT_TANH, 1, 2), (orc.ACT_SILU, 2, 2), (orc.ACT_SILU, 1, -1)])
-def test_update_step_gradients_match_torch_autograd(act, mb, rank):
+@pytest.mark.parametrize("act,mb,rank,sig", [(orc.ACT_TANH, 1, 2, 0), (orc.ACT_SILU, 2, 2, 0), (orc.ACT_SILU, 1, -1, 0),
+                                             (orc.ACT_SILU, 2, 2, 1), (orc.ACT_TANH, 1, -1, 1)])
+def test_update_step_gradients_match_torch_autograd(act, mb, rank, sig):
     """The whole hand-derived reverse pass (loss -> target nets -> hypernets) against autograd."""
-    d = tiny(act=act, N=12, P=3, rank=rank)
+    d = tiny(act=act, N=12, P=3, rank=rank, sigma_state=sig)
     w, hp_a0, hp_c0, hp_a, hp_c, obs, rew, done, eps = make_case(d, 20)
     res = orc.update_step(d, w, hp_a0, hp_c0, hp_a, hp_c, obs, rew, done, eps, 0.99, 0.95, 0.2,
                           minibatches=mb, epochs=1, keep=True)
