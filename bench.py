@@ -192,6 +192,8 @@ def main():
     ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "ppo_loss_grad", "scalarize_normalized",
                                      "hypernet_affine"), default="update_step",
                     help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
+    ap.add_argument("--sigma-state", action="store_true",
+                    help="variant: the actor network outputs its own log sigma (needs 2 * act_dim <= 16: configs 1-3)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")
     a = ap.parse_args()
@@ -209,6 +211,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     cfg = CONFIGS[a.config]
+    if a.sigma_state:
+        from paper_2603_09237_amd.configs import scaled
+        cfg = scaled(cfg, name=cfg.name + "-sigma", sigma_state=1)
     if a.row != "update_step":
         bench_kernel(a, cfg)
         return

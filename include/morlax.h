@@ -61,6 +61,8 @@ typedef struct {
     int32_t hyper_width; /* F */
     int32_t wdtype;      /* 0: fp32 weights and GEMM inputs; 1: bf16 weights and GEMM inputs, fp32 accumulate */
     int32_t mean_tanh;   /* 1: actor mean = tanh(z) (Sec. III-E); 0: mean = z */
+    int32_t sigma_state; /* 0: log sigma [P, A] comes from the actor hypernetwork (theta_vec tail); 1: it is an output of
+                            the actor network -- its output layer is 2A wide (means, then log sigmas), 2A <= 16 */
 } morlax_dims;
 
 typedef struct {

@@ -18,7 +18,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3
 
 class Dims(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("K", "P", "N", "T", "obs_dim", "act_dim", "n_hidden", "width",
-                                         "act", "rank", "hyper_width", "wdtype", "mean_tanh")]
+                                         "act", "rank", "hyper_width", "wdtype", "mean_tanh", "sigma_state")]
 
 
 class Rows(C.Structure):

@@ -46,6 +46,7 @@ class Config:
     lam: float = 0.95
     clip_eps: float = 0.2
     seed: int = 0
+    sigma_state: int = 0   # 1: the actor network outputs its own log sigma (2A output columns)
 
     @property
     def n_g(self) -> int:
@@ -53,7 +54,7 @@ class Config:
 
     def dims_dict(self) -> dict:
         keys = ("K", "P", "N", "T", "obs_dim", "act_dim", "n_hidden", "width", "act",
-                "rank", "hyper_width", "wdtype", "mean_tanh")
+                "rank", "hyper_width", "wdtype", "mean_tanh", "sigma_state")
         d = asdict(self)
         return {k: d[k] for k in keys}
 

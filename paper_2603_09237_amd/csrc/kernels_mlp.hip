@@ -1244,7 +1244,8 @@ struct FusedFwdArgs {
     int32_t L, O, M, tiles_m, n_tiles;
     // output layer (applied to the tile's last hidden activations while they are still in LDS)
     int64_t head_mat_off, head_vec_off, logsig_off;
-    int32_t out_dim, tanh_head;
+    int32_t out_dim, tanh_cols;  // leading output columns that are squashed by tanh (the actor's means)
+    int32_t adim, sig_state;     // action width; 1: log sigma = output columns [adim, 2 adim) of the same row
     RowMap rm;
     float* out;        // time-major [.., N, out_dim]
     float* saved_out;  // saving: compact [P][M][OUT_PITCH]
@@ -1452,26 +1453,27 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) c[e] += c2[e];
         const float bias = b_ok ? bp[a.head_vec_off + hl] : 0.f;
-        float ls = 0.f, sg = 0.f;
-        if (a.eps && b_ok) {
-            ls = bp[a.logsig_off + hl];
-            sg = expf(ls);
-        }
+        const bool a_ok = hl < a.adim;  // lanes that hold an action mean
+        float ls_p = 0.f;
+        if (a.eps && a_ok && !a.sig_state) ls_p = bp[a.logsig_off + hl];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int tr = 16 * wave + 4 * hg + e, m = m0 + tr;
             const bool ok = (tr < rows) && b_ok;
             const float z = c[e] + bias;
-            const float o = a.tanh_head ? tanhf(z) : z;
+            const float o = (hl < a.tanh_cols) ? tanhf(z) : z;
             int64_t row = 0;
             if (tr < rows) row = a.rm.row(p, m);
             float term = 0.f;
+            // a state-dependent log sigma sits adim columns to the right, in the same group of 16 lanes
+            const float ls_s = __shfl(o, (lane & 48) | ((hl + a.adim) & 15), 64);
             if (ok) {
                 a.out[row * a.out_dim + hl] = o;
                 if (SAVE) a.saved_out[((int64_t)p * a.M + m) * OUT_PITCH + hl] = o;
-                if (a.eps) {
-                    const float ep = a.eps[row * a.out_dim + hl];
-                    a.act[row * a.out_dim + hl] = o + sg * ep;
+                if (a.eps && a_ok) {
+                    const float ls = a.sig_state ? ls_s : ls_p;
+                    const float ep = a.eps[row * a.adim + hl];
+                    a.act[row * a.adim + hl] = o + expf(ls) * ep;
                     term = -0.5f * ep * ep - ls;
                 }
             }
@@ -1480,7 +1482,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
                 term += __shfl_xor(term, 4, 64);
                 term += __shfl_xor(term, 2, 64);
                 term += __shfl_xor(term, 1, 64);
-                if (tr < rows && hl == 0) a.logp[row] = term - 0.918938533204672742f * (float)a.out_dim;
+                if (tr < rows && hl == 0) a.logp[row] = term - 0.918938533204672742f * (float)a.adim;
             }
         }
     }
@@ -1629,10 +1631,11 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, const T* __restrict__ theta_mat,
                                                  const float* __restrict__ theta_vec, int64_t mat_len,
                                                  int64_t vec_len, int64_t mat_off, int64_t vec_off, int W,
-                                                 int out_dim, int M, RowMap rm, int tanh_head,
+                                                 int out_dim, int M, RowMap rm, int tanh_cols,
                                                  float* __restrict__ out, float* __restrict__ saved_out,
                                                  const float* __restrict__ eps, float* __restrict__ act,
-                                                 float* __restrict__ logp, int64_t logsig_off) {
+                                                 float* __restrict__ logp, int64_t logsig_off, int adim,
+                                                 int sig_state) {
     constexpr int VE = Elems<T>::VE;
     const int p = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1665,26 +1668,27 @@ __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, con
     for (int e = 0; e < 4; ++e) c[e] += c2[e];
     // lane holds column lr of rows m0 + 4*lg + e
     const float bias = b_ok ? theta_vec[(int64_t)p * vec_len + vec_off + lr] : 0.f;
-    float ls = 0.f, sg = 0.f;
-    if (eps && b_ok) {
-        ls = theta_vec[(int64_t)p * vec_len + logsig_off + lr];
-        sg = expf(ls);
-    }
+    const bool mean_lane = lr < adim;  // lanes that hold an action mean
+    float ls_p = 0.f;
+    if (eps && mean_lane && !sig_state) ls_p = theta_vec[(int64_t)p * vec_len + logsig_off + lr];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const int m = m0 + 4 * lg + e;
         const bool ok = (m < M) && b_ok;
         const float z = c[e] + bias;
-        const float o = tanh_head ? tanhf(z) : z;
+        const float o = (lr < tanh_cols) ? tanhf(z) : z;
         int64_t row = 0;
         if (m < M) row = rm.row(p, m);
         float term = 0.f;
+        // a state-dependent log sigma sits adim columns to the right, in the same group of 16 lanes
+        const float ls_s = __shfl(o, (lane & 48) | ((lr + adim) & 15), 64);
         if (ok) {
             out[row * out_dim + lr] = o;
             if (saved_out) saved_out[((int64_t)p * M + m) * OUT_PITCH + lr] = o;
-            if (eps) {
-                const float ep = eps[row * out_dim + lr];
-                act[row * out_dim + lr] = o + sg * ep;
+            if (eps && mean_lane) {
+                const float ls = sig_state ? ls_s : ls_p;
+                const float ep = eps[row * adim + lr];
+                act[row * adim + lr] = o + expf(ls) * ep;
                 term = -0.5f * ep * ep - ls;
             }
         }
@@ -1693,7 +1697,7 @@ __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, con
             term += __shfl_xor(term, 4, 64);
             term += __shfl_xor(term, 2, 64);
             term += __shfl_xor(term, 1, 64);
-            if (m < M && lr == 0) logp[row] = term - 0.918938533204672742f * (float)out_dim;
+            if (m < M && lr == 0) logp[row] = term - 0.918938533204672742f * (float)adim;
         }
     }
 }
@@ -1705,7 +1709,7 @@ __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ Hin, con
 template <typename T>
 __global__ __launch_bounds__(256) void k_head_dzh(const float* __restrict__ dout, const float* __restrict__ saved_out,
                                                  float* __restrict__ dzh, float* __restrict__ pb, int out_dim, int M,
-                                                 RowMap rm, int tanh_head) {
+                                                 RowMap rm, int tanh_cols) {
     __shared__ float red[4][MORLAX_MAX_OUT];
     const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
     float d[MORLAX_MAX_OUT];
@@ -1717,7 +1721,7 @@ __global__ __launch_bounds__(256) void k_head_dzh(const float* __restrict__ dout
         for (int j = 0; j < MORLAX_MAX_OUT; ++j) {
             if (j < out_dim) {
                 d[j] = dout[row * out_dim + j];
-                if (tanh_head) {
+                if (j < tanh_cols) {
                     const float mu = saved_out[((int64_t)p * M + m) * OUT_PITCH + j];
                     d[j] *= (1.f - mu * mu);
                 }
@@ -2083,7 +2087,9 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             const LayerDev& Lo = nd.layer[L];
             a.head_mat_off = Lo.mat_off; a.head_vec_off = Lo.vec_off; a.logsig_off = Lo.vec_off + Lo.d_out;
             a.out_dim = nd.out_dim;
-            a.tanh_head = (net == MORLAX_ACTOR && c->d.mean_tanh) ? 1 : 0;
+            a.tanh_cols = (net == MORLAX_ACTOR && c->d.mean_tanh) ? c->d.act_dim : 0;
+            a.adim = c->d.act_dim;
+            a.sig_state = (net == MORLAX_ACTOR && c->d.sigma_state) ? 1 : 0;
             a.rm = rm; a.out = out; a.saved_out = saved_out; a.eps = eps; a.act = act; a.logp = logp;
             if (c->d.act == 0) {
                 if (sv) launch_fused_fwd<0, true>(c, a, s); else launch_fused_fwd<0, false>(c, a, s);
@@ -2105,11 +2111,12 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     }
     if (fused) return;  // the fused kernel applies the output layer as well
     const LayerDev& Lh = nd.layer[L];
-    const int tanh_head = (net == MORLAX_ACTOR && c->d.mean_tanh) ? 1 : 0;
+    const int tanh_cols = (net == MORLAX_ACTOR && c->d.mean_tanh) ? c->d.act_dim : 0;
     const dim3 grid((M + 63) / 64, P);
     k_head_fwd<T><<<grid, 256, 0, s>>>(Hbuf(L - 1), theta_mat, theta_vec, nd.mat_len, nd.vec_len, Lh.mat_off,
-                                       Lh.vec_off, W, nd.out_dim, M, rm, tanh_head, out, saved_out, eps, act, logp,
-                                       Lh.vec_off + Lh.d_out);
+                                       Lh.vec_off, W, nd.out_dim, M, rm, tanh_cols, out, saved_out, eps, act, logp,
+                                       Lh.vec_off + Lh.d_out, c->d.act_dim,
+                                       (net == MORLAX_ACTOR && c->d.sigma_state) ? 1 : 0);
 }
 
 template <typename T>
@@ -2130,7 +2137,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     float* part = reinterpret_cast<float*>(wsT + 2 * ae);
     int n_part = (M + 63) / 64;  // row blocks of whichever kernel produced the current dZ
     const float* saved_out = reinterpret_cast<const float*>(sv + (int64_t)2 * L * ae);
-    const int tanh_head = (net == MORLAX_ACTOR && c->d.mean_tanh) ? 1 : 0;
+    const int tanh_cols = (net == MORLAX_ACTOR && c->d.mean_tanh) ? c->d.act_dim : 0;
     constexpr int VE = Elems<T>::VE;
     const LayerDev& Lh = nd.layer[L];
     // output layer
@@ -2139,7 +2146,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         float* pw = part;
         float* pb = part + head_pw_elems(c);
         float* dzh = part + head_lo_elems(c, rs);
-        k_head_dzh<T><<<dim3(n_chunk_b, P), 256, 0, s>>>(dout, saved_out, dzh, pb, nd.out_dim, M, rm, tanh_head);
+        k_head_dzh<T><<<dim3(n_chunk_b, P), 256, 0, s>>>(dout, saved_out, dzh, pb, nd.out_dim, M, rm, tanh_cols);
         k_head_bwd_dw<T><<<dim3((W + 127) / 128, HB_SPLIT, P), 256, 0, s>>>(dzh, Hbuf(L - 1), pw, W, M);
         k_head_bwd_dw_final<<<dim3((nd.out_dim * W + 255) / 256, P), 256, 0, s>>>(
             pw, pb, HB_SPLIT, n_chunk_b, dtheta_mat, dtheta_vec, nd.mat_len, nd.vec_len, Lh.mat_off, Lh.vec_off, W,
@@ -2194,7 +2201,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         }
     }
     (void)VE;
-    if (net == MORLAX_ACTOR) {
+    if (net == MORLAX_ACTOR && !c->d.sigma_state) {  // (a state-dependent log sigma is part of dout)
         const int n = P * c->d.act_dim;
         k_copy_dlogsig<<<(n + 255) / 256, 256, 0, s>>>(dlogsig, dtheta_vec, nd.vec_len, Lh.vec_off + Lh.d_out, P,
                                                       c->d.act_dim);

@@ -238,11 +238,13 @@ __global__ __launch_bounds__(256) void k_ppo_loss_grad(
     const float* __restrict__ act, const float* __restrict__ logp_old, const float* __restrict__ adv_s,
     const float* __restrict__ v, const float* __restrict__ vtarg, const double* __restrict__ adv_stat,
     float clip_eps, int norm_adv, float inv_B, float* __restrict__ dmu, float* __restrict__ dv,
-    double* __restrict__ stat_part, double* __restrict__ dls_part, int N, int n_g, int A, int K) {
+    double* __restrict__ stat_part, double* __restrict__ dls_part, int N, int n_g, int A, int K, int sig_state) {
+    // sig_state: mu and dmu have 2A columns per cell -- means, then log sigmas (state dependent) / their gradients
     __shared__ float red[5 + A_MAX][256 + 16];
     __shared__ float s_ls[A_MAX], s_isig[A_MAX];
     const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
-    if (threadIdx.x < A) {
+    const int mus = sig_state ? 2 * A : A;  // row stride of mu and dmu
+    if (threadIdx.x < A && !sig_state) {
         const float ls = logsig[(int64_t)p * ls_stride + threadIdx.x];
         s_ls[threadIdx.x] = ls;
         s_isig[threadIdx.x] = expf(-ls);
@@ -257,13 +259,21 @@ __global__ __launch_bounds__(256) void k_ppo_loss_grad(
         const int64_t row = cell_row(rs, p, m, N, n_g);
         float ahat = adv_s[row];
         if (norm_adv) ahat = (float)(((double)ahat - adv_stat[0]) / (adv_stat[1] + 1e-8));
-        float q[A_MAX];
+        float q[A_MAX], isig[A_MAX];
         float logp = -0.918938533204672742f * (float)A;  // -(A/2) log(2 pi)
 #pragma unroll
         for (int a = 0; a < A_MAX; ++a) {
             if (a < A) {
-                q[a] = (act[row * A + a] - mu[row * A + a]) * s_isig[a];
-                logp += -0.5f * q[a] * q[a] - s_ls[a];
+                float ls = 0.f;
+                if (sig_state) {
+                    ls = mu[row * mus + A + a];
+                    isig[a] = expf(-ls);
+                } else {
+                    ls = s_ls[a];
+                    isig[a] = s_isig[a];
+                }
+                q[a] = (act[row * A + a] - mu[row * mus + a]) * isig[a];
+                logp += -0.5f * q[a] * q[a] - ls;
             }
         }
         const float lpo = logp_old[row];
@@ -278,8 +288,10 @@ __global__ __launch_bounds__(256) void k_ppo_loss_grad(
 #pragma unroll
         for (int a = 0; a < A_MAX; ++a) {
             if (a < A) {
-                dmu[row * A + a] = dlogp * q[a] * s_isig[a];
-                dls[a] = dlogp * (q[a] * q[a] - 1.f);
+                dmu[row * mus + a] = dlogp * q[a] * isig[a];
+                const float g = dlogp * (q[a] * q[a] - 1.f);
+                if (sig_state) dmu[row * mus + A + a] = g;  // stays per cell: it flows back through the network
+                else dls[a] = g;
             }
         }
         for (int k = 0; k < K; ++k) {
@@ -324,6 +336,7 @@ __global__ __launch_bounds__(256) void k_loss_final(const double* __restrict__ s
     __shared__ double sh[4];
     const int p = blockIdx.x;
     if (p < P) {
+        if (!dlogsig) return;  // (state-dependent sigma: there is no per-preference log-sigma gradient)
         for (int a = 0; a < A; ++a) {
             double s = 0.0;
             for (int b = threadIdx.x; b < nbm; b += 256) s += dls_part[((int64_t)p * nbm + b) * A + a];
@@ -366,7 +379,7 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
     k_ppo_loss_grad<MORLAX_MAX_OUT><<<grid, 256, 0, s>>>(rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v,
                                                         vtarg, L.adv_stat, clip_eps, norm_adv,
                                                         (float)(1.0 / cnt), dmu, dv, L.stat_part, L.dls_part,
-                                                        N, c->n_g, A, K);
+                                                        N, c->n_g, A, K, c->d.sigma_state);
     k_loss_final<<<P + 1, 256, 0, s>>>(L.stat_part, L.dls_part, L.adv_stat, nbm, P, A, cnt, dlogsig, stats);
 }
 

@@ -28,7 +28,8 @@ static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at
     // of the low-rank form would be) and W0 is its constant term; there are no factors
     const bool affine = d.rank < 0;
     const int64_t F = d.hyper_width, r = affine ? 0 : d.rank, K = d.K;
-    const int out = (net == MORLAX_ACTOR) ? d.act_dim : d.K;
+    // a state-dependent standard deviation doubles the actor's output layer: means, then log sigmas
+    const int out = (net == MORLAX_ACTOR) ? (d.sigma_state ? 2 * d.act_dim : d.act_dim) : d.K;
     nd.n_layers = d.n_hidden + 1;
     nd.out_dim = out;
     int64_t hp = 0, mat = 0, vec = 0, fac = 0;
@@ -53,7 +54,7 @@ static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at
         L.hp_mbias = hp; hp += (int64_t)L.d_out * F;
     }
     nd.hp_logsig0 = nd.hp_msig = -1;
-    if (net == MORLAX_ACTOR) {
+    if (net == MORLAX_ACTOR && !d.sigma_state) {
         nd.hp_logsig0 = hp; hp += d.act_dim;
         nd.hp_msig = hp; hp += (int64_t)d.act_dim * F;
         vec += d.act_dim;
@@ -79,7 +80,7 @@ static void build_net(const morlax_dims& d, int net, NetDev& nd, AffineTable& at
             seg(L.hp_mb, L.hp_cb, (int32_t)(r * L.d_in));
         }
     for (int l = 0; l < nd.n_layers; ++l) seg(nd.layer[l].hp_mbias, nd.layer[l].hp_b0, nd.layer[l].d_out);
-    if (net == MORLAX_ACTOR) seg(nd.hp_msig, nd.hp_logsig0, d.act_dim);
+    if (net == MORLAX_ACTOR && !d.sigma_state) seg(nd.hp_msig, nd.hp_logsig0, d.act_dim);
     at.q_total = q;
     nd.mat_len = mat;
     nd.vec_len = vec;
@@ -99,6 +100,10 @@ extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
         return fail(MORLAX_ERR_SHAPE, "morlax_create: P = %d must divide N = %d", d.P, d.N);
     if (d.K > MORLAX_MAX_OUT || d.act_dim > MORLAX_MAX_OUT)
         return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: K and act_dim must be <= %d", MORLAX_MAX_OUT);
+    if (d.sigma_state != 0 && d.sigma_state != 1)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: sigma_state must be 0 or 1");
+    if (d.sigma_state && 2 * d.act_dim > MORLAX_MAX_OUT)
+        return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: a state-dependent sigma needs 2 * act_dim <= %d", MORLAX_MAX_OUT);
     if (d.obs_dim > 1024) return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: obs_dim must be <= 1024");
     if (d.n_hidden > MORLAX_MAX_LAYERS - 1)
         return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: n_hidden must be <= %d", MORLAX_MAX_LAYERS - 1);
@@ -281,6 +286,8 @@ extern "C" int morlax_policy_bwd(morlax_ctx* ctx, int net, const void* theta_mat
     OPT(dlogsig, who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
     if (dlogsig && net != MORLAX_ACTOR) return fail(MORLAX_ERR_SHAPE, "%s: dlogsig is actor-only", who);
+    if (dlogsig && ctx->d.sigma_state)
+        return fail(MORLAX_ERR_SHAPE, "%s: with a state-dependent sigma the log-sigma gradient is part of dout", who);
     RowSel rs;
     int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
     if (rc != MORLAX_OK) return rc;
@@ -364,12 +371,17 @@ extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, co
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
     REQ(mu, who); REQ(act, who); REQ(logp_old, who); REQ(adv_s, who); REQ(v, who);
-    REQ(vtarg, who); REQ(dmu, who); REQ(dlogsig, who); REQ(dv, who); REQ(stats, who); REQ(ws, who);
-    if (!logsig) return fail(MORLAX_ERR_NULL, "%s: logsig is NULL", who);
-    if ((reinterpret_cast<uintptr_t>(logsig) & 3u) != 0)
-        return fail(MORLAX_ERR_SHAPE, "%s: logsig is not 4-byte aligned", who);
-    if (logsig_stride < ctx->d.act_dim)
-        return fail(MORLAX_ERR_SHAPE, "%s: logsig_stride %d < act_dim %d", who, logsig_stride, ctx->d.act_dim);
+    REQ(vtarg, who); REQ(dmu, who); REQ(dv, who); REQ(stats, who); REQ(ws, who);
+    if (ctx->d.sigma_state) {  // log sigma and its gradient travel inside mu / dmu (2 * act_dim columns)
+        OPT(logsig, who); OPT(dlogsig, who);
+    } else {
+        REQ(dlogsig, who);
+        if (!logsig) return fail(MORLAX_ERR_NULL, "%s: logsig is NULL", who);
+        if ((reinterpret_cast<uintptr_t>(logsig) & 3u) != 0)
+            return fail(MORLAX_ERR_SHAPE, "%s: logsig is not 4-byte aligned", who);
+        if (logsig_stride < ctx->d.act_dim)
+            return fail(MORLAX_ERR_SHAPE, "%s: logsig_stride %d < act_dim %d", who, logsig_stride, ctx->d.act_dim);
+    }
     if (!(clip_eps >= 0.f)) return fail(MORLAX_ERR_SHAPE, "%s: clip_eps must be >= 0", who);
     RowSel rs;
     int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);

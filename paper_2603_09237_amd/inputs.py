@@ -27,7 +27,9 @@ def _rng(seed: int, tid: int) -> np.random.Generator:
 
 def layer_shapes(cfg: Config, net: int):
     """(d_out, d_in) of every dense layer of a target network, input to output."""
-    out = cfg.act_dim if net == NET_ACTOR else cfg.K
+    out = cfg.K
+    if net == NET_ACTOR:    # means, and with a state-dependent standard deviation also the log sigmas
+        out = 2 * cfg.act_dim if cfg.sigma_state else cfg.act_dim
     dims = [cfg.obs_dim] + [cfg.width] * cfg.n_hidden + [out]
     return [(dims[i + 1], dims[i]) for i in range(len(dims) - 1)]
 
@@ -53,7 +55,7 @@ def hparam_blocks(cfg: Config, net: int):
                        (f"MB_{l}", (r * di, F), "normal", s * F ** -0.5),
                        (f"cB_{l}", (r * di,), "normal", s)]
         blocks += [(f"Mb_{l}", (do, F), "normal", 0.1 * F ** -0.5)]
-    if net == NET_ACTOR:
+    if net == NET_ACTOR and not cfg.sigma_state:
         blocks += [("logsig0", (cfg.act_dim,), "const", -0.5),
                    ("Msig", (cfg.act_dim, F), "normal", 0.1 * F ** -0.5)]
     return blocks

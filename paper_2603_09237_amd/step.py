@@ -52,7 +52,8 @@ class UpdateStep:
             self.theta_vec[net] = torch.empty(P, ctx.theta_vec_len(net), **f32)
             self.dtheta_mat[net] = torch.empty(P, ctx.theta_mat_len(net), **f32)
             self.dtheta_vec[net] = torch.empty(P, ctx.theta_vec_len(net), **f32)
-        self.mu_old = torch.empty(T, N, A, **f32)
+        AO = 2 * A if c.sigma_state else A   # actor output columns: means (+ state-dependent log sigmas)
+        self.mu_old = torch.empty(T, N, AO, **f32)
         self.act = torch.empty(T, N, A, **f32)
         self.logp_old = torch.empty(T, N, **f32)
         self.v_roll = torch.empty(T + 1, N, K, **f32)
@@ -62,11 +63,11 @@ class UpdateStep:
         self.adv_norm = adv_norm
         self.adv_vec = torch.empty(T, N, K, **f32) if (keep_adv_vec or adv_norm == "per_objective") else None
         self.adv_mb = torch.empty(T, N, **f32) if adv_norm == "per_objective" else None
-        self.mu = torch.zeros(T, N, A, **f32)
+        self.mu = torch.zeros(T, N, AO, **f32)
         self.v = torch.zeros(T, N, K, **f32)
-        self.dmu = torch.zeros(T, N, A, **f32)
+        self.dmu = torch.zeros(T, N, AO, **f32)
         self.dv = torch.zeros(T, N, K, **f32)
-        self.dlogsig = torch.zeros(P, A, **f32)
+        self.dlogsig = None if c.sigma_state else torch.zeros(P, A, **f32)
         self.stats = torch.zeros(8, **f32)
         if c.n_g % c.minibatches:
             raise ValueError("minibatches must divide n_g")
@@ -156,7 +157,7 @@ class UpdateStep:
                               self.opt_step)
 
         self._per_net(fwd)
-        logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
+        logsig = None if c.sigma_state else self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
         self._loss(rows, logsig)
         self._per_net(bwd)
 
@@ -224,7 +225,7 @@ class UpdateStep:
                 main.wait_event(theta_ready[net])
                 ctx.policy_fwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, out[net],
                                saved=self.saved[net], ws=self.ws)
-            logsig = self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
+            logsig = None if c.sigma_state else self.theta_vec[ACTOR].data_ptr() + 4 * self.logsig_off
             self._loss(rows, logsig)
             for net in nets:
                 if dtheta_free[net] is not None:

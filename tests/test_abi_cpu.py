@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_layout_queries_match_oracle_and_generator(lib):
     affine = [configs.scaled(configs.CONFIGS[i], name=f"cfg{i}-affine", rank=-1) for i in (1, 5)]
-    for cfg in list(configs.CONFIGS.values()) + affine:
+    sigma = [configs.scaled(configs.CONFIGS[i], name=f"cfg{i}-sigma", sigma_state=1) for i in (1, 2)]
+    for cfg in list(configs.CONFIGS.values()) + affine + sigma:
         ctx = binding.Context.from_config(cfg)
         for net in (0, 1):
             assert ctx.hparam_count(net) == orc.hparam_count(cfg, net) == inputs.hparam_count(cfg, net)
@@ -52,6 +53,8 @@ def test_layout_queries_match_oracle_and_generator(lib):
     (dict(hyper_width=128), binding.ERR_UNSUPPORTED), (dict(n_hidden=9), binding.ERR_UNSUPPORTED),
     (dict(N=1 << 20, P=2, T=1023, obs_dim=1024), binding.ERR_UNSUPPORTED),      # observations beyond 32-bit offsets
     (dict(N=1 << 16, P=2, T=16383, width=2048), binding.ERR_UNSUPPORTED),       # one preference's activations too
+    (dict(sigma_state=1, act_dim=9), binding.ERR_UNSUPPORTED),                  # 2A output columns must fit 16
+    (dict(sigma_state=2), binding.ERR_UNSUPPORTED),
 ])
 def test_create_rejects_bad_dims(lib, over, code):
     d = configs.CONFIGS[1].dims_dict()
@@ -115,6 +118,11 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
     with pytest.raises(binding.MorlaxError) as e:      # more extreme trade-offs than objectives
         ctx.sample_preferences(good, cfg.K + 1, good, stream=0)
     assert e.value.code == binding.ERR_SHAPE
+    sctx = binding.Context.from_config(configs.scaled(cfg, name="sigma", sigma_state=1))
+    with pytest.raises(binding.MorlaxError) as e:      # the log-sigma gradient is part of dout in this mode
+        sctx.policy_bwd(0, good, good, good, (0, 1, 0, 1), good, good, good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    sctx.close()
     with pytest.raises(binding.MorlaxError) as e:      # the vector advantage has T rows, not T + 1
         ctx.scalarize_normalized((0, cfg.T + 1, 0, cfg.n_g), good, good, good, good, stream=0)
     assert e.value.code == binding.ERR_SHAPE

@@ -61,6 +61,10 @@ RAGGED_PERS = scaled(RAGGED, name="ragged-persistent-bf16", wdtype=1, P=32, N=32
 RAGGED_FUSED = scaled(RAGGED, name="ragged-fused-bf16", wdtype=1, P=5, N=5 * 37, T=9, width=512, obs_dim=64, n_hidden=3,
                       rank=4)
 RAGGED_FUSED_TANH = scaled(RAGGED_FUSED, name="ragged-fused-bf16-tanh", act=0, n_hidden=1, obs_dim=128)
+# state-dependent standard deviation (the actor's output layer is 2A wide): fp32, the widest allowed (2A = 16),
+# a ragged fp32 case, and the fused bf16 forward
+SIGMA_CASES = [scaled(CONFIGS[1], name="cfg1-sigma", sigma_state=1), scaled(CONFIGS[2], name="cfg2-sigma", sigma_state=1),
+               scaled(RAGGED, name="ragged-sigma", sigma_state=1), scaled(RAGGED_FUSED, name="ragged-fused-sigma", sigma_state=1)]
 
 
 def all_cfgs():
@@ -361,7 +365,8 @@ def pref_env_mask(cfg, prefs):
 FWD_CASES = [(CONFIGS[1], None), (CONFIGS[1], (3, 9, 5, 7)), (RAGGED, None), (RAGGED, (1, 5, 2, 19)),
              (RAGGED_BF16, None), (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None),
              (CONFIGS[4], None), (CONFIGS[5], None), (CONFIGS[5], "mb"), (RAGGED_FUSED, None),
-             (RAGGED_FUSED, (2, 5, 3, 30)), (RAGGED_FUSED_TANH, None)]
+             (RAGGED_FUSED, (2, 5, 3, 30)), (RAGGED_FUSED_TANH, None)] + [(c, None) for c in SIGMA_CASES] + \
+            [(SIGMA_CASES[2], (1, 5, 2, 19))]
 
 
 @pytest.mark.parametrize("cfg,rows", FWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -379,7 +384,7 @@ def test_policy_fwd_matches_oracle(cfg, rows, torch, binding):
         say(f"policy_fwd {cfg.name} net={net} rows={r} prefs={prefs}")
         tm, tv = theta_for(cfg, net, True)
         wdt = torch.bfloat16 if cfg.wdtype == 1 else torch.float32
-        odim = cfg.act_dim if net == ACTOR else cfg.K
+        odim = orc.head_dim(cfg, net)
         SENT = -7.5
         out = torch.full((cfg.T + 1, cfg.N, odim), SENT, device="cuda")
         ws = torch.empty(ctx.workspace_bytes(r), dtype=torch.uint8, device="cuda")
@@ -388,7 +393,7 @@ def test_policy_fwd_matches_oracle(cfg, rows, torch, binding):
         if net == ACTOR:
             eps_pad = np.zeros((cfg.T + 1, cfg.N, cfg.act_dim), dtype=np.float32)
             eps_pad[:cfg.T] = eps
-            act = torch.full((cfg.T + 1, cfg.N, odim), SENT, device="cuda")
+            act = torch.full((cfg.T + 1, cfg.N, cfg.act_dim), SENT, device="cuda")
             logp = torch.full((cfg.T + 1, cfg.N), SENT, device="cuda")
             kw = dict(eps=dev(eps_pad), act=act, logp=logp)
         ctx.policy_fwd(net, d_tm, d_tv, d_x, r, out, ws=ws, **kw)
@@ -406,8 +411,11 @@ def test_policy_fwd_matches_oracle(cfg, rows, torch, binding):
         if net == ACTOR:
             g_act, g_logp = to_np(act), to_np(logp)
             assert np.all(g_act[~mask] == SENT) and np.all(g_logp[~mask] == SENT)
-            close(g_act, o_act, "act", mask=m3)
-            assert_close32(g_logp, o_logp, "logp", mask=cmp)   # depends on eps and log sigma only
+            close(g_act, o_act, "act", mask=cmp[..., None] & np.ones_like(o_act, bool))
+            if cfg.sigma_state:
+                close(g_logp, o_logp, "logp", mask=cmp)        # log sigma is an output of the network here
+            else:
+                assert_close32(g_logp, o_logp, "logp", mask=cmp)   # depends on eps and log sigma only
         if emu and prefs is None:
             # against exact activations (same bf16 weights) the difference is the bf16 rounding noise of
             # the method itself: small in RMS, a few-sigma tail on single elements
@@ -424,7 +432,8 @@ def test_policy_fwd_matches_oracle(cfg, rows, torch, binding):
 
 BWD_CASES = [(CONFIGS[1], None), (RAGGED, None), (RAGGED, (1, 5, 2, 19)), (RAGGED_BF16, None),
              (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None), (CONFIGS[4], None),
-             (CONFIGS[5], "mb"), (RAGGED_FUSED, None), (RAGGED_FUSED_TANH, (1, 6, 0, 37))]
+             (CONFIGS[5], "mb"), (RAGGED_FUSED, None), (RAGGED_FUSED_TANH, (1, 6, 0, 37))] + \
+            [(c, None) for c in SIGMA_CASES]
 
 
 @pytest.mark.parametrize("cfg,rows", BWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -442,10 +451,10 @@ def test_policy_bwd_matches_oracle(cfg, rows, torch, binding):
         say(f"policy_bwd {cfg.name} net={net} rows={rows} prefs={prefs}")
         tm, tv = theta_for(cfg, net, True)
         wdt = torch.bfloat16 if cfg.wdtype == 1 else torch.float32
-        odim = cfg.act_dim if net == ACTOR else cfg.K
+        odim = orc.head_dim(cfg, net)
         rng = np.random.default_rng(80 + net)
         dout = (rng.standard_normal((cfg.T, cfg.N, odim), dtype=np.float32) / np.float32(np.sqrt(rows[1] * rows[3])))
-        dls = rng.standard_normal((cfg.P, cfg.act_dim), dtype=np.float32) if net == ACTOR else None
+        dls = rng.standard_normal((cfg.P, cfg.act_dim), dtype=np.float32) if (net == ACTOR and not cfg.sigma_state) else None
         d_tm, d_tv, d_x = dev(tm, wdt), dev(tv.astype(np.float32)), dev(x)
         ws = torch.empty(ctx.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
         saved = torch.empty(ctx.saved_bytes(net, rows), dtype=torch.uint8, device="cuda")
@@ -467,8 +476,10 @@ def test_policy_bwd_matches_oracle(cfg, rows, torch, binding):
             close(g_dtv[sel, voff:voff + do], o_dtv[sel, voff:voff + do], f"db_{l} net={net}")
             moff += do * di
             voff += do
-        if net == ACTOR:
+        if net == ACTOR and not cfg.sigma_state:
             assert np.array_equal(g_dtv[:, voff:], dls)
+        else:
+            assert voff == g_dtv.shape[1]
         if emu and prefs is None:
             o2, _ = orc.policy_bwd(cfg, net, tm, tv.astype(np.float32), x, rows, dout, dls, emulate_bf16=False)
             e = rel_rms_err(g_dtm, o2)
@@ -606,6 +617,40 @@ def test_update_step_per_objective_normalisation_matches_oracle(torch, binding):
         assert np.abs(ga - plain["grads"][i]["dhp_actor"]).max() > 1e-2 * np.abs(ga).max()
 
 
+@pytest.mark.parametrize("cfg", [SIGMA_CASES[0], SIGMA_CASES[1], SIGMA_CASES[2]], ids=lambda c: c.name)
+def test_ppo_loss_grad_state_sigma_matches_oracle(cfg, torch, binding):
+    """The loss with log sigma per cell (columns A .. 2A of the actor's output); its gradient stays per cell."""
+    say(f"ppo_loss_grad state-dependent sigma {cfg.name}")
+    A = cfg.act_dim
+    mu, logsig, act, logp_old, adv_s, v, vtarg = loss_inputs(cfg)
+    rng = np.random.default_rng(41)
+    gidx = orc.env_pref_index(cfg.N, cfg.P)
+    ls = (logsig[gidx][None] + 0.05 * rng.standard_normal(mu.shape)).astype(np.float32)     # per-cell log sigma
+    out = np.concatenate([mu, ls], axis=-1).astype(np.float32)
+    rows = (0, cfg.T, 0, cfg.n_g)
+    ctx = binding.Context.from_config(cfg)
+    SENT = 3.25
+    dout = torch.full(out.shape, SENT, device="cuda")
+    dv = torch.full(v.shape, SENT, device="cuda")
+    stats = torch.zeros(8, device="cuda")
+    ws = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device="cuda")
+    ctx.ppo_loss_grad(rows, dev(out), None, 0, dev(act), dev(logp_old), dev(adv_s), dev(v), dev(vtarg), cfg.clip_eps, 1,
+                      dout, None, dv, stats, ws)
+    torch.cuda.synchronize()
+    o_d, o_none, o_dv, o_st = orc.ppo_loss_grad(cfg, rows, out, None, act, logp_old, adv_s, v, vtarg, cfg.clip_eps, True)
+    assert o_none is None and o_d.shape[-1] == 2 * A
+    logp = orc.gaussian_logp(act.astype(np.float64), mu.astype(np.float64), ls.astype(np.float64))
+    rho = np.exp(logp - logp_old)
+    kink = (np.abs(rho - (1 + cfg.clip_eps)) < 1e-5) | (np.abs(rho - (1 - cfg.clip_eps)) < 1e-5)
+    B = float(cfg.T * cfg.N)
+    ok = (~kink)[..., None] & np.ones_like(o_d, bool)
+    assert_close32(to_np(dout) * B, o_d * B, "d(out)*B", mask=ok)
+    assert_close32(to_np(dv) * B, o_dv * B, "dv*B")
+    st = to_np(stats)
+    assert_close32(st[[0, 1, 3, 4, 5, 6]], o_st[[0, 1, 3, 4, 5, 6]], "stats", rel=1e-4, abs_=1e-5)
+    assert np.abs(o_d[..., A:]).max() * B > 0.1          # the log-sigma gradient is there
+
+
 def run_step(cfg, torch, keep_adv_vec=True):
     from paper_2603_09237_amd.step import UpdateStep
     st = UpdateStep(cfg, keep_adv_vec=keep_adv_vec)
@@ -624,7 +669,9 @@ def run_step(cfg, torch, keep_adv_vec=True):
 
 @pytest.mark.parametrize("cfg", [CONFIGS[1], scaled(CONFIGS[1], name="cfg1-mb2x2", minibatches=2, epochs=2),
                                  scaled(RAGGED, name="ragged-step", minibatches=1), CONFIGS[2],
-                                 scaled(CONFIGS[1], name="cfg1-affine-step", rank=-1, minibatches=2, epochs=1)],
+                                 scaled(CONFIGS[1], name="cfg1-affine-step", rank=-1, minibatches=2, epochs=1),
+                                 scaled(CONFIGS[1], name="cfg1-sigma-step", sigma_state=1, minibatches=2, epochs=1),
+                                 scaled(RAGGED, name="ragged-sigma-step", sigma_state=1, minibatches=1)],
                          ids=lambda c: c.name)
 def test_update_step_fp32_matches_oracle(cfg, torch, binding):
     say(f"update_step fp32 {cfg.name}")
@@ -656,7 +703,9 @@ def test_update_step_fp32_matches_oracle(cfg, torch, binding):
 
 
 @pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), RAGGED_PERS, CONFIGS[3],
-                                 scaled(RAGGED_FUSED, name="ragged-fused-step", minibatches=1, epochs=1)],
+                                 scaled(RAGGED_FUSED, name="ragged-fused-step", minibatches=1, epochs=1),
+                                 scaled(RAGGED_FUSED, name="ragged-fused-sigma-step", minibatches=1, epochs=1,
+                                        sigma_state=1)],
                          ids=lambda c: c.name)
 def test_update_step_bf16_matches_oracle(cfg, torch, binding):
     say(f"update_step bf16 {cfg.name}")
@@ -666,7 +715,8 @@ def test_update_step_bf16_matches_oracle(cfg, torch, binding):
                           cfg.clip_eps, cfg.minibatches, cfg.epochs, emulate_bf16=True, keep=True)
     assert_close_bf16(to_np(st.mu_old), res["mu_old"], "mu_old")
     assert_close_bf16(to_np(st.act), res["act"], "act")
-    assert_close32(to_np(st.logp_old), res["logp_old"], "logp_old")
+    # (with a state-dependent sigma the log-density depends on a bf16 network output)
+    (assert_close_bf16 if cfg.sigma_state else assert_close32)(to_np(st.logp_old), res["logp_old"], "logp_old")
     assert_close_bf16(to_np(st.v_roll), res["v_roll"], "v_roll")
     assert_close_bf16(to_np(st.vtarg), res["vtarg"], "vtarg")
     assert_close_bf16(to_np(st.adv_s), res["adv_s"], "adv_s")
