@@ -69,6 +69,28 @@ SIGMA_CASES = [scaled(CONFIGS[1], name="cfg1-sigma", sigma_state=1), scaled(CONF
                scaled(RAGGED, name="ragged-sigma", sigma_state=1), scaled(RAGGED_FUSED, name="ragged-fused-sigma", sigma_state=1)]
 
 
+def _random_fused_cases(n, seed):
+    """Seeded random shapes and row selections for the fused forward (bf16, width 512): group sizes, horizons,
+    observation widths 64 .. 512, depths, output widths, both activations, tanh on or off, both sigma forms."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        P, n_g, T = int(rng.integers(2, 5)), int(rng.integers(1, 60)), int(rng.integers(1, 7))
+        O, L = int(rng.choice([64, 128, 192, 256, 320, 384, 448, 512])), int(rng.integers(1, 4))
+        K, A = int(rng.integers(1, 7)), int(rng.integers(1, 9))
+        act, sig, tanh = int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        cfg = scaled(RAGGED, name=f"fused-rand{i}-P{P}-g{n_g}-T{T}-O{O}-L{L}-K{K}-A{A}-a{act}s{sig}t{tanh}", wdtype=1, P=P,
+                     N=P * n_g, T=T, obs_dim=O, n_hidden=L, width=512, K=K, act_dim=A, act=act, sigma_state=sig,
+                     mean_tanh=tanh, rank=2)
+        t0 = int(rng.integers(0, T)); tc = int(rng.integers(1, T - t0 + 1))
+        j0 = int(rng.integers(0, n_g)); jc = int(rng.integers(1, n_g - j0 + 1))
+        cases.append((cfg, (t0, tc, j0, jc)))
+    return cases
+
+
+RANDOM_FUSED = _random_fused_cases(8, 2024)
+
+
 def all_cfgs():
     return [CONFIGS[i] for i in (1, 2, 3, 4, 5)]
 
@@ -368,7 +390,7 @@ FWD_CASES = [(CONFIGS[1], None), (CONFIGS[1], (3, 9, 5, 7)), (RAGGED, None), (RA
              (RAGGED_BF16, None), (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None),
              (CONFIGS[4], None), (CONFIGS[5], None), (CONFIGS[5], "mb"), (RAGGED_FUSED, None),
              (RAGGED_FUSED, (2, 5, 3, 30)), (RAGGED_FUSED_TANH, None)] + [(c, None) for c in SIGMA_CASES] + \
-            [(SIGMA_CASES[2], (1, 5, 2, 19)), (RAGGED_FUSED, (3, 1, 5, 1)), (RAGGED_FUSED_WIDE, None)]   # (one row per preference)
+            [(SIGMA_CASES[2], (1, 5, 2, 19)), (RAGGED_FUSED, (3, 1, 5, 1)), (RAGGED_FUSED_WIDE, None)] + RANDOM_FUSED
 
 
 @pytest.mark.parametrize("cfg,rows", FWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -436,7 +458,8 @@ BWD_CASES = [(CONFIGS[1], None), (RAGGED, None), (RAGGED, (1, 5, 2, 19)), (RAGGE
              (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None), (CONFIGS[4], None),
              (CONFIGS[5], "mb"), (RAGGED_FUSED, None), (RAGGED_FUSED_TANH, (1, 6, 0, 37))] + \
             [(c, None) for c in SIGMA_CASES] + \
-            [(RAGGED_FUSED, (3, 1, 5, 1)), (scaled(RAGGED_FUSED_WIDE, name="ragged-fused-bf16-obs512-3layers", n_hidden=3), None)]
+            [(RAGGED_FUSED, (3, 1, 5, 1)), (scaled(RAGGED_FUSED_WIDE, name="ragged-fused-bf16-obs512-3layers", n_hidden=3), None)] + \
+            RANDOM_FUSED
 # (the backward of the eight-layer network is left out: its bf16 rounding noise, re-rounded at every layer on both
 # sides, passes the 2 % band of single elements without either side being wrong)
 
