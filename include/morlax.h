@@ -109,6 +109,16 @@ int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparams, const fl
                         const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
                         void* ws, void* stream);
 
+/* The same reverse pass for a caller that kept the forward pass's workspace: ws_fwd must be the buffer the
+ * last morlax_hypernet_fwd of this network ran in -- with these hparams and w -- and nothing may have
+ * written to it since (give each network a workspace of its own, used by no other call).  The trunk
+ * features and the factors are then read from it instead of being computed again; the result is bit for
+ * bit that of morlax_hypernet_bwd.  The library cannot check the condition: a stale workspace gives wrong
+ * gradients, not an error. */
+int morlax_hypernet_bwd_kept(morlax_ctx* ctx, int net, const float* hparams, const float* w,
+                             const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
+                             void* ws_fwd, void* stream);
+
 /* Grouped forward of the target-network family {pi_i} or {V_i} (Sec. III-C, rollout phase;
  * Sec. III-E for the tanh on the actor output): every selected (t, n) row of x goes through the
  * network of preference g(n).  Hidden layers h = act(W h + b); actor out = tanh(z) (or z when

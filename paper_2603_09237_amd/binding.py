@@ -35,7 +35,8 @@ _lib = None
 
 EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hparam_count",
            "morlax_theta_mat_len", "morlax_theta_vec_len", "morlax_saved_bytes", "morlax_workspace_bytes",
-           "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
+           "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_hypernet_bwd_kept",
+           "morlax_policy_fwd",
            "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
            "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad", "morlax_profile_begin",
            "morlax_profile_end")
@@ -72,6 +73,7 @@ def load():
     lib.morlax_env_pref_index.argtypes = [vp, vp, vp]
     lib.morlax_hypernet_fwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.morlax_hypernet_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
+    lib.morlax_hypernet_bwd_kept.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
     lib.morlax_policy_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.morlax_policy_bwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.morlax_vec_gae.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
@@ -85,7 +87,8 @@ def load():
     lib.morlax_profile_begin.restype = C.c_int
     lib.morlax_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double)]
     lib.morlax_profile_end.restype = C.c_int
-    for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_policy_fwd",
+    for name in ("morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_hypernet_bwd_kept",
+           "morlax_policy_fwd",
                  "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
                  "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad"):
         getattr(lib, name).restype = C.c_int
@@ -179,6 +182,11 @@ class Context:
         self._check(self.lib.morlax_hypernet_fwd(self.h, net, _ptr(hparams), _ptr(w), _ptr(theta_mat),
                                                  _ptr(theta_vec), _ptr(ws),
                                                  stream if stream is not None else _stream()))
+
+    def hypernet_bwd_kept(self, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws_fwd, stream=None):
+        self._check(self.lib.morlax_hypernet_bwd_kept(self.h, net, _ptr(hparams), _ptr(w), _ptr(dtheta_mat),
+                                                      _ptr(dtheta_vec), _ptr(dhparams), _ptr(ws_fwd),
+                                                      stream if stream is not None else _stream()))
 
     def hypernet_bwd(self, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, stream=None):
         self._check(self.lib.morlax_hypernet_bwd(self.h, net, _ptr(hparams), _ptr(w), _ptr(dtheta_mat),

@@ -679,7 +679,7 @@ __global__ __launch_bounds__(256) void k_hyper_trunk_bwd_b(const float* __restri
 
 void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, const float* w,
                          const float* dtheta_mat, const float* dtheta_vec, float* dhparams, void* ws,
-                         hipStream_t s) {
+                         bool kept, hipStream_t s) {
     const NetDev& nd = c->net[net];
     const AffineTable& at = c->aff[net];
     const int P = c->d.P, F = c->d.hyper_width, r = c->d.rank, K = c->d.K;
@@ -687,12 +687,14 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
     const bool affine = r < 0;
     // the gradient of the leading stacked rows: of the factor vector, or (strictly affine form) of theta_mat itself
     const float* dlead = affine ? dtheta_mat : L.dfac;
+    // kept: the workspace still holds what the forward pass of this network left there (h1, f, the factors)
     if (affine) {
         // only f is needed again; dW0 and dMW come out of k_hyper_dM below (W0 is the constant term of those rows)
-        k_hyper_trunk<<<P, 64, 0, s>>>(hparams, w, L.h1, L.f, K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
+        if (!kept)
+            k_hyper_trunk<<<P, 64, 0, s>>>(hparams, w, L.h1, L.f, K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
     } else {
         // recompute f and the factors; the theta_vec rows of the affine map land in a scratch nobody reads
-        run_trunk_and_affine(c, net, hparams, w, L, nullptr, L.vecs, s);
+        if (!kept) run_trunk_and_affine(c, net, hparams, w, L, nullptr, L.vecs, s);
         k_hyper_dbase<<<(int)((nd.mat_len / 4 + 255) / 256), 256, 0, s>>>(nd, dtheta_mat, dhparams, P);
     }
     if (r > 0) {

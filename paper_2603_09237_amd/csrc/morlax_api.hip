@@ -251,7 +251,19 @@ extern "C" int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparam
     if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
     REQ(hparams, who); REQ(w, who); REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(dhparams, who);
     REQ(ws, who);
-    launch_hypernet_bwd(ctx, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, (hipStream_t)stream);
+    launch_hypernet_bwd(ctx, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, false, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_hypernet_bwd_kept(morlax_ctx* ctx, int net, const float* hparams, const float* w,
+                                        const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
+                                        void* ws_fwd, void* stream) {
+    const char* who = "morlax_hypernet_bwd_kept";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
+    REQ(hparams, who); REQ(w, who); REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(dhparams, who);
+    REQ(ws_fwd, who);
+    launch_hypernet_bwd(ctx, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws_fwd, true, (hipStream_t)stream);
     return finish(who);
 }
 

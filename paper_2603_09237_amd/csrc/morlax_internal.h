@@ -88,7 +88,7 @@ void launch_hypernet_fwd(const morlax_ctx* c, int net, const float* hparams, con
                          void* theta_mat, float* theta_vec, void* ws, hipStream_t s);
 void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, const float* w,
                          const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
-                         void* ws, hipStream_t s);
+                         void* ws, bool kept, hipStream_t s);
 
 int64_t mlp_saved_bytes(const morlax_ctx* c, int net, const RowSel& rs);
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs);

@@ -82,7 +82,10 @@ class UpdateStep:
         self.ws = self.wsn[ACTOR]
         self.streams = {net: torch.cuda.Stream(device=self.dev) for net in (ACTOR, CRITIC)} if two_streams else None
         self.side = torch.cuda.Stream(device=self.dev) if side_hypernet else None
-        self.ws_side = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device=self.dev) if side_hypernet else None
+        # a workspace per hypernetwork, touched by nothing but its forward and backward: the backward pass then
+        # reads the trunk features and factors that the forward pass left there instead of computing them again
+        self.hws = {net: torch.empty(ctx.workspace_bytes((0, 1, 0, 1)), dtype=torch.uint8, device=self.dev)
+                    for net in (ACTOR, CRITIC)}
         self.optimizer = optimizer
         self.opt_step = 0
         if optimizer is not None:
@@ -139,7 +142,7 @@ class UpdateStep:
         dout = {ACTOR: self.dmu, CRITIC: self.dv}
 
         def fwd(net, ws):
-            ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], ws)
+            ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], self.hws[net])
             ctx.policy_fwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, out[net],
                            saved=self.saved[net], ws=ws)
 
@@ -150,7 +153,8 @@ class UpdateStep:
         def bwd(net, ws):
             ctx.policy_bwd(net, self.theta_mat[net], self.theta_vec[net], self.obs, rows, self.saved[net], dout[net],
                            self.dlogsig if net == ACTOR else None, self.dtheta_mat[net], self.dtheta_vec[net], ws)
-            ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net], self.dhp[net], ws)
+            ctx.hypernet_bwd_kept(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net], self.dhp[net],
+                                  self.hws[net])
             if o is not None:
                 ctx.adam_step(net, self.hp[net], self.dhp[net], self.adam_m[net], self.adam_v[net],
                               o["lr_actor"] if net == ACTOR else o["lr_critic"], o["beta1"], o["beta2"], o["eps"],
@@ -210,7 +214,7 @@ class UpdateStep:
         with t.cuda.stream(side):
             for net in nets:
                 side.wait_event(theta_free[net])
-                ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], self.ws_side)
+                ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net], self.hws[net])
                 theta_ready[net].record(side)
         ctx.vec_gae(self.rewards, self.v_roll, self.dones, self.w, c.gamma, c.lam, self.adv_vec, self.vtarg,
                     self.adv_s)
@@ -236,8 +240,8 @@ class UpdateStep:
                 dtheta_ready[net].record(main)
                 with t.cuda.stream(side):
                     side.wait_event(dtheta_ready[net])
-                    ctx.hypernet_bwd(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net],
-                                     self.dhp[net], self.ws_side)
+                    ctx.hypernet_bwd_kept(net, self.hp[net], self.w, self.dtheta_mat[net], self.dtheta_vec[net],
+                                          self.dhp[net], self.hws[net])
                     dtheta_free[net] = t.cuda.Event()
                     dtheta_free[net].record(side)
                     if o is not None:
@@ -246,7 +250,7 @@ class UpdateStep:
                                       o["eps"], self.opt_step)
                     if not last:
                         ctx.hypernet_fwd(net, self.hp[net], self.w, self.theta_mat[net], self.theta_vec[net],
-                                         self.ws_side)
+                                         self.hws[net])
                         theta_ready[net] = t.cuda.Event()
                         theta_ready[net].record(side)
             if on_minibatch is not None:

@@ -84,6 +84,12 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
     with pytest.raises(binding.MorlaxError) as e:
         ctx.hypernet_bwd(0, good, good, None, good, good, good, stream=0)
     assert e.value.code == binding.ERR_NULL
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.hypernet_bwd_kept(0, good, good, good, good, good, None, stream=0)
+    assert e.value.code == binding.ERR_NULL
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.hypernet_bwd_kept(3, good, good, good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
     bad_rows = [(0, cfg.T + 2, 0, cfg.n_g), (0, 0, 0, 1), (0, 1, 0, cfg.n_g + 1), (-1, 1, 0, 1), (0, 1, cfg.n_g, 1)]
     for rows in bad_rows:
         with pytest.raises(binding.MorlaxError) as e:

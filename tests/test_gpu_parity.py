@@ -362,6 +362,33 @@ def test_hypernet_bwd_matches_oracle(cfg, torch, binding):
             assert_close32(got[o:o + n], ref[o:o + n], f"dhparams[{name}]")
 
 
+@pytest.mark.parametrize("cfg", [CONFIGS[1], RAGGED, CONFIGS[3], AFFINE_CASES[0]], ids=lambda c: c.name)
+def test_hypernet_bwd_kept_equals_hypernet_bwd(cfg, torch, binding):
+    """The backward pass that reads the forward pass's workspace gives the gradient of the one that recomputes,
+    bit for bit."""
+    ctx = binding.Context.from_config(cfg)
+    for net in (ACTOR, CRITIC):
+        say(f"hypernet_bwd_kept {cfg.name} net={net}")
+        hp, w = hyper_case(cfg, net)
+        rng = np.random.default_rng(90 + net)
+        ml, vl = ctx.theta_mat_len(net), ctx.theta_vec_len(net)
+        dtm = dev((rng.standard_normal((cfg.P, ml), dtype=np.float32) * 0.01).astype(np.float32))
+        dtv = dev((rng.standard_normal((cfg.P, vl), dtype=np.float32) * 0.01).astype(np.float32))
+        wdt = torch.bfloat16 if cfg.wdtype == 1 else torch.float32
+        tm = torch.zeros(cfg.P, ml, dtype=wdt, device="cuda")
+        tv = torch.zeros(cfg.P, vl, device="cuda")
+        ws_f = torch.empty(ctx.workspace_bytes((0, 1, 0, 1)), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(ctx.workspace_bytes(None), dtype=torch.uint8, device="cuda")
+        d_hp, d_w = dev(hp), dev(w)
+        ctx.hypernet_fwd(net, d_hp, d_w, tm, tv, ws_f)
+        g_kept = torch.full((ctx.hparam_count(net),), 9.0, device="cuda")
+        ctx.hypernet_bwd_kept(net, d_hp, d_w, dtm, dtv, g_kept, ws_f)
+        g_ref = torch.full((ctx.hparam_count(net),), 7.0, device="cuda")
+        ctx.hypernet_bwd(net, d_hp, d_w, dtm, dtv, g_ref, ws_b)
+        torch.cuda.synchronize()
+        assert torch.equal(g_kept, g_ref)
+
+
 # ------------------------------------------------------------------------------------------------
 def theta_for(cfg, net, emulate):
     hp, w = hyper_case(cfg, net)
