@@ -1218,15 +1218,21 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
 // an activation.
 // Wave w owns output features [64 w, 64 w + 64) of every layer for all 128 rows: its slice of W_l(p) is
 // used by no other wave, so the W fragments go from global memory (they sit in L2: 64 tiles share one
-// W(p)) straight into registers, 64 contiguous bytes per lane and 64 contraction indices ("super-step"),
-// requested half a super-step ("unit": 16 products) ahead of their use.  Inside a super-step lane group g
+// W(p)) straight into registers, requested half a super-step ("unit": 16 products, 32 contraction indices
+// per lane group) ahead of their use.  The kernel reads them from a copy of the matrices in fragment order
+// (k_theta_fragment_order, made by the same call): every load instruction then covers 1 KB of consecutive
+// addresses.  Read from the row-major matrices the same stream takes 32 bytes from each of 32 rows per
+// instruction, and the workgroups of a CU, 64 KB of such lines in flight against its vector cache, fetch
+// lines from L2 more than once: streamed alone, without the products, W moved at 9.7 TB/s row-major and
+// 15.3 TB/s in fragment order, and a launch of workload 5 spends most of its time on exactly this stream.
+// Inside a super-step lane group g
 // of product jj covers contraction indices 64 s + 32 g + 8 jj .. + 8 for both operands.  The bias enters
 // as the initial value of the accumulators.  A layer ends with a barrier, the epilogue (activation, its
 // derivative, the in-place rewrite of the tile, the stores of the saving variant) and a second barrier;
 // the products and the epilogue of a workgroup do not overlap, and with 128 KB of LDS for the tile there is
 // one workgroup per CU.  Measured on workload 5 the time of a launch splits, additively, into the W
-// requests (a third: 32 cache lines per load instruction, each used for 32 bytes), the products, the
-// epilogue arithmetic and a fixed part per tile (observation gather, first requests, barriers).
+// requests, the products, the epilogue arithmetic and a fixed part per tile (observation gather, first
+// requests, barriers).
 #define FF_ROWS 128
 #define FF_W 512
 #define FF_ACT_BYTES (FF_ROWS * FF_W * 2)
@@ -1234,7 +1240,8 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
 struct FusedFwdArgs {
     const float* x;           // observations, time-major rows of O values
     bf16_t* x0;               // saving: receives the gathered observations, compact [P][M][O] bf16
-    const bf16_t* theta_mat;  // [P][mat_len]
+    const bf16_t* theta_mat;  // [P][mat_len]: the output layer's matrix is read from here
+    const bf16_t* theta_frag; // [P][mat_len]: the first and the hidden layers' matrices in fragment order
     const float* theta_vec;   // [P][vec_len]
     int64_t mat_len, vec_len;
     int64_t mat_off[MORLAX_MAX_LAYERS], vec_off[MORLAX_MAX_LAYERS];
@@ -1256,6 +1263,39 @@ struct FusedFwdArgs {
 
 __device__ inline int swap_bits23(int i) { return (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
+// Fragment order of a [512][K] bf16 matrix W (K a multiple of 64): the 16-byte pieces of W in the order in
+// which the fused forward requests them, so that each of its load instructions reads 1 KB of consecutive
+// addresses (eight whole cache lines) instead of 32 bytes from each of 32 rows.  Wave v of the forward owns
+// output features [64 v, 64 v + 64); its stream is K / 32 units of 4 KB; unit u holds four 1 KB blocks
+// (j, e), j = feature half, e = which 16 bytes; lane (lg, lr) of a block holds, for feature
+// 64 v + 32 j + swap_bits23(lr), the contraction indices 64 (u / 2) + 32 lg + 16 (u % 2) + 8 e + [0, 8).
+// One workgroup moves a super-step pair of units of one j: 32 rows x 128 bytes, whole lines in and out.
+struct FragOrderArgs {
+    const bf16_t* src;  // [P][mat_len] row-major matrices
+    bf16_t* dst;        // [P][mat_len]
+    int64_t mat_len;
+    int64_t mat_off[MORLAX_MAX_LAYERS];
+    int32_t K[MORLAX_MAX_LAYERS];
+    int32_t g0[MORLAX_MAX_LAYERS + 1];  // first workgroup of layer l; g0[L] = workgroups per preference
+    int32_t L;
+};
+
+__global__ __launch_bounds__(256) void k_theta_fragment_order(FragOrderArgs a) {
+    const int p = blockIdx.y;
+    int l = 0;
+    while (l + 1 < a.L && (int)blockIdx.x >= a.g0[l + 1]) ++l;
+    const int K = a.K[l], g = blockIdx.x - a.g0[l];
+    const int per_wave = 2 * (K >> 6);
+    const int v = g / per_wave, r = g % per_wave, sstep = r >> 1, j = r & 1;
+    const int wq = threadIdx.x >> 6, ln = threadIdx.x & 63, ub = wq >> 1, e = wq & 1, lg = ln >> 5, lr = ln & 31;
+    const int u = 2 * sstep + ub;
+    const char* W = reinterpret_cast<const char*>(a.src + (int64_t)p * a.mat_len + a.mat_off[l]);
+    char* D = reinterpret_cast<char*>(a.dst + (int64_t)p * a.mat_len + a.mat_off[l]);
+    const int f = 64 * v + 32 * j + swap_bits23(lr);
+    const uint4 q = *reinterpret_cast<const uint4*>(W + (int64_t)f * K * 2 + sstep * 128 + ub * 32 + lg * 64 + e * 16);
+    *reinterpret_cast<uint4*>(D + (int64_t)v * (K >> 5) * 4096 + u * 4096 + j * 2048 + e * 1024 + ln * 16) = q;
+}
+
 // a value the compiler can no longer trace back to its source: address arithmetic derived from it stays
 // where it is written instead of being hoisted out of the layer loop into registers held across the products
 __device__ inline int opaque(int v) {
@@ -1272,23 +1312,22 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
     const int rows = a.M - m0 < FF_ROWS ? a.M - m0 : FF_ROWS;
     const int wn = wave * 64;
 
-    const bf16_t* Wp = a.theta_mat + (int64_t)p * a.mat_len;
+    const bf16_t* Wp = a.theta_frag + (int64_t)p * a.mat_len;
     const float* bp = a.theta_vec + (int64_t)p * a.vec_len;
-    const int frow = swap_bits23(lr);
-    auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's two rows of W_l(p), at its contraction offset
+    auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's place in the wave's stream of W_l(p), per feature half
         const int K = l == 0 ? a.O : FF_W;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-            w[j] = reinterpret_cast<const char*>(Wp + a.mat_off[l] + (int64_t)(wn + 32 * j + frow) * K) + lg * 64;
+            w[j] = reinterpret_cast<const char*>(Wp + a.mat_off[l]) + (int64_t)wave * (K >> 5) * 4096 + j * 2048 +
+                   lane * 16;
     };
-    // unit u of a layer = 32 contraction indices per lane group: bytes [32 (u & 1), + 32) of the lane's 64
-    // contiguous bytes of super-step u / 2
+    // unit u of a layer = 32 contraction indices per lane group, 4 KB of the wave's stream (fragment order)
     auto load_w = [&](uint4 (&wf)[2][2], const char* w0, const char* w1, int u) {
-        const int off = (u >> 1) * 128 + (u & 1) * 32;
+        const int off = u * 4096;
         wf[0][0] = *reinterpret_cast<const uint4*>(w0 + off);
-        wf[0][1] = *reinterpret_cast<const uint4*>(w0 + off + 16);
+        wf[0][1] = *reinterpret_cast<const uint4*>(w0 + off + 1024);
         wf[1][0] = *reinterpret_cast<const uint4*>(w1 + off);
-        wf[1][1] = *reinterpret_cast<const uint4*>(w1 + off + 16);
+        wf[1][1] = *reinterpret_cast<const uint4*>(w1 + off + 1024);
     };
     // W fragments: two buffers, a unit's request one unit ahead of its use (a longer distance with four
     // buffers measured slower: the registers it takes spill in the epilogue)
@@ -1431,7 +1470,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
         const int hl = lane & 15, hg = lane >> 4;
         const int r = 16 * wave + hl;
         const unsigned char* hrow = dlds + r * 1024;
-        const bf16_t* wrow = Wp + a.head_mat_off + (int64_t)hl * FF_W;
+        const bf16_t* wrow = a.theta_mat + (int64_t)p * a.mat_len + a.head_mat_off + (int64_t)hl * FF_W;
         const bool b_ok = hl < a.out_dim;
         float4_t c = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -1972,8 +2011,20 @@ static int64_t head_lo_elems(const morlax_ctx* c, const RowSel& rs) {
 static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
     return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64);
 }
+static bool fused_fwd_dims_ok(const morlax_ctx* c) {
+    return c->d.wdtype == 1 && c->d.width == FF_W && c->d.obs_dim % 64 == 0 && c->d.obs_dim <= FF_W &&
+           c->d.n_hidden >= 1;
+}
+
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
-    return 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4 + (use_x0(c) ? x0_elems(c, rs) * esize(c) : 0);
+    int64_t b = 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4 + (use_x0(c) ? x0_elems(c, rs) * esize(c) : 0);
+    if (fused_fwd_dims_ok(c)) {  // the fused forward's copy of the matrices in fragment order
+        for (int net = 0; net < 2; ++net) {
+            const int64_t f = align_up((int64_t)c->d.P * c->net[net].mat_len * 2, 256);
+            if (f > b) b = f;
+        }
+    }
+    return b;
 }
 
 static RowMap make_rowmap(const morlax_ctx* c, const RowSel& rs) {
@@ -1984,8 +2035,7 @@ static RowMap make_rowmap(const morlax_ctx* c, const RowSel& rs) {
 
 // The fused forward serves bf16 networks of width 512 whose observation width is a multiple of 64.
 static bool fused_fwd_ok(const morlax_ctx* c, const NetDev& nd, const void* theta_mat) {
-    if (c->d.wdtype != 1 || c->d.width != FF_W || c->d.obs_dim % 64 || c->d.obs_dim > FF_W || c->d.n_hidden < 1)
-        return false;
+    if (!fused_fwd_dims_ok(c)) return false;
     if ((reinterpret_cast<uintptr_t>(theta_mat) & 15) || (nd.mat_len & 7)) return false;
     for (int l = 0; l <= c->d.n_hidden; ++l)
         if (nd.layer[l].mat_off & 7) return false;
@@ -2078,6 +2128,20 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             a.theta_mat = theta_mat; a.theta_vec = theta_vec;
             a.mat_len = nd.mat_len; a.vec_len = nd.vec_len;
             for (int l = 0; l < L; ++l) { a.mat_off[l] = nd.layer[l].mat_off; a.vec_off[l] = nd.layer[l].vec_off; }
+            {  // the matrices the kernel streams, once more in the order of its requests
+                FragOrderArgs fo;
+                fo.src = theta_mat; fo.dst = reinterpret_cast<bf16_t*>(ws); fo.mat_len = nd.mat_len; fo.L = L;
+                int g = 0;
+                for (int l = 0; l < L; ++l) {
+                    fo.mat_off[l] = nd.layer[l].mat_off;
+                    fo.K[l] = l == 0 ? O : FF_W;
+                    fo.g0[l] = g;
+                    g += 8 * 2 * (fo.K[l] >> 6);
+                }
+                fo.g0[L] = g;
+                k_theta_fragment_order<<<dim3(g, P), 256, 0, s>>>(fo);
+                a.theta_frag = fo.dst;
+            }
             a.H = sv;
             a.G = sv ? reinterpret_cast<gfix16_t*>(sv + ae) : nullptr;
             a.lstride = 2 * ae;
