@@ -142,6 +142,47 @@ def bench_kernel(a, cfg):
         # the vector advantage is read twice (statistics, then the combination), the result written once
         units, unit_name, bytes_per_launch = cells, "env-steps/s", (8.0 * K + 4.0) * cells
         metric = "scalarize_normalized_env_steps_per_sec"
+    elif a.row in ("eval_returns", "pareto_hypervolume"):
+        # evaluation side: return vectors of the roll-out, then their Pareto front and hypervolume
+        r = dev(inputs.make_rewards(cfg))
+        done = dev((np.random.default_rng(3).random((T, N)) < cfg.p_done).astype(np.uint8))
+        J = torch.empty(cfg.P, K, device="cuda")
+        if a.row == "eval_returns":
+            launch = lambda: ctx.eval_returns(r, done, cfg.gamma, J)
+            units, unit_name, bytes_per_launch = T * N, "env-steps/s", (4.0 * K + 1.0) * T * N + 4.0 * cfg.P * K
+            metric = "eval_returns_env_steps_per_sec"
+        else:
+            ctx.eval_returns(r, done, cfg.gamma, J)
+            ref = torch.zeros(16, device="cuda")
+            ref[:K] = J.min(dim=0).values - 1.0
+            front = torch.empty(cfg.P, dtype=torch.uint8, device="cuda")
+            hv = torch.empty(2, dtype=torch.float64, device="cuda")
+            ws = torch.empty(binding.hypervolume_workspace_bytes(cfg.P, K), dtype=torch.uint8, device="cuda")
+            launch = lambda: binding.pareto_hypervolume(J, ref, cfg.P, K, front, hv, ws)
+            tuples = cfg.P ** max(K - 2, 0)
+            # counted work: one fp64 multiply-add per tuple of slabs (thickness product x staircase area); the set
+            # operations and the staircase passes come on top and depend on the data
+            ops = 2.0 * tuples
+            for _ in range(max(a.warmup, 1)):
+                launch()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(a.steps):
+                launch()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / a.steps
+            peak = 78.6                            # fp64 vector TFLOP/s
+            print(json.dumps({
+                "metric": "pareto_hypervolume_slab_tuples_per_sec", "value": tuples / (ms * 1e-3), "unit": "tuples/s",
+                "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+                "config": {"workload": cfg.name, "row": a.row, "points": cfg.P, "objectives": K,
+                           "front_size": int(front.sum().item()), "hypervolume": float(hv[0].item())},
+                "roofline": {"bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                             "frac": ops / (ms * 1e-3) / 1e12 / peak, "traffic": None}}))
+            return
     else:
         r, vv, w = dev(inputs.make_rewards(cfg)), dev(inputs.make_values(cfg)), dev(inputs.make_preferences(cfg))
         rng = np.random.default_rng(3)
@@ -190,7 +231,7 @@ def main():
     ap.add_argument("--with-optimizer", action="store_true",
                     help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
     ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "ppo_loss_grad", "scalarize_normalized",
-                                     "hypernet_affine"), default="update_step",
+                                     "hypernet_affine", "eval_returns", "pareto_hypervolume"), default="update_step",
                     help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
     ap.add_argument("--sigma-state", action="store_true",
                     help="variant: the actor network outputs its own log sigma (needs 2 * act_dim <= 16: configs 1-3)")

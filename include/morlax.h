@@ -214,6 +214,31 @@ int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* 
                          const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
                          float* dlogsig, float* dv, float* stats, void* ws, void* stream);
 
+/* Evaluation side (Fig. 2a: a trade-off is picked, its policy rolled out, and the returns judged).
+ * morlax_eval_returns: the return vector of every trade-off from a finished roll-out (Sec. II-A:
+ * J = expected discounted return from the initial state): J[p, k] = mean over the n_g environments of
+ * group p of sum_t gamma^t r[t, n, k] alive[t, n], alive = 1 up to and including the first done of
+ * environment n and 0 after it.  r [T, N, K] fp32, done [T, N] u8 (device); J [P, K] fp32 (device,
+ * overwritten).  Sums in fp64, fixed order.  MORLAX_ERR_SHAPE unless 0 < gamma <= 1. */
+int morlax_eval_returns(morlax_ctx* ctx, const float* r, const uint8_t* done, float gamma, float* J,
+                        void* stream);
+
+/* Pareto front and hypervolume of n return vectors (Sec. II-A: j dominates i when it is at least as
+ * good in every objective and differs from it; Sec. II-B: hypervolume = volume of objective space
+ * dominated by the set).  The paper names no reference point: ref [K] is an input, and the volume is that
+ * of the union of the boxes [ref, J[i]]; a point that is not above ref in every objective adds nothing.
+ * The result is exact (no sampling): objectives 2 .. K-1 are cut into slabs at the points' coordinates
+ * and every tuple of slabs contributes the area of a two-objective staircase, n^(K-2) tuples in all.
+ *   J [n, K] fp32, ref [K] fp32 (device, read); front [n] u8 (device, written: 1 = not dominated by any
+ *   other point; equal points do not dominate each other); hv [1] fp64 (device, written);
+ *   ws: morlax_hypervolume_workspace_bytes(n, K) bytes of device scratch.
+ * Independent of any morlax_ctx (an evaluation may use any number of trade-offs).  Sums in fp64 in a fixed
+ * order.  MORLAX_ERR_SHAPE unless 1 <= K <= 8, 1 <= n <= 1024 and n^(K-2) <= 2^32;
+ * morlax_hypervolume_workspace_bytes returns -1 for such sizes. */
+int64_t morlax_hypervolume_workspace_bytes(int32_t n, int32_t K);
+int morlax_pareto_hypervolume(const float* J, const float* ref, int32_t n, int32_t K, uint8_t* front,
+                              double* hv, void* ws, void* stream);
+
 /* Timing aid for benchmarks (not part of the method).  Between morlax_profile_begin() and
  * morlax_profile_end() every grouped-GEMM launch of policy_fwd / policy_bwd on this ctx is bracketed
  * by a pair of HIP events recorded on the launch stream.  morlax_profile_end() waits for the last

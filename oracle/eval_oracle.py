@@ -36,7 +36,7 @@ def discounted_returns(r, done, gamma, P):
     alive = np.ones(N, dtype=bool)
     disc = 1.0
     for t in range(T):
-        G += disc * r[t] * alive[:, None]
+        G += np.where(alive[:, None], disc * r[t], 0.0)   # a selection: cells after the end never enter
         alive &= ~done[t]
         disc *= gamma
     return G.reshape(P, N // P, K).mean(axis=1)

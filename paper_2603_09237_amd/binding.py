@@ -38,7 +38,8 @@ EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hpara
            "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_hypernet_bwd_kept",
            "morlax_policy_fwd",
            "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
-           "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad", "morlax_profile_begin",
+           "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad", "morlax_eval_returns",
+           "morlax_hypervolume_workspace_bytes", "morlax_pareto_hypervolume", "morlax_profile_begin",
            "morlax_profile_end")
 
 GEMM_KINDS = ("fwd_first", "fwd_hidden", "dx_hidden", "dw_hidden", "dw_first", "fwd_fused")
@@ -83,6 +84,12 @@ def load():
     lib.morlax_scalarize_normalized.argtypes = [vp, C.POINTER(Rows), vp, vp, vp, vp, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
                                          vp, vp, vp, vp, vp, vp]
+    lib.morlax_eval_returns.argtypes = [vp, vp, vp, f32, vp, vp]
+    lib.morlax_eval_returns.restype = C.c_int
+    lib.morlax_hypervolume_workspace_bytes.argtypes = [i32, i32]
+    lib.morlax_hypervolume_workspace_bytes.restype = i64
+    lib.morlax_pareto_hypervolume.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.morlax_pareto_hypervolume.restype = C.c_int
     lib.morlax_profile_begin.argtypes = [vp]
     lib.morlax_profile_begin.restype = C.c_int
     lib.morlax_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double)]
@@ -220,6 +227,10 @@ class Context:
         self._check(self.lib.morlax_sample_preferences(self.h, _ptr(u), int(kappa), _ptr(w),
                                                        stream if stream is not None else _stream()))
 
+    def eval_returns(self, r, done, gamma, J, stream=None):
+        self._check(self.lib.morlax_eval_returns(self.h, _ptr(r), _ptr(done), float(gamma), _ptr(J),
+                                                 stream if stream is not None else _stream()))
+
     def adam_step(self, net, hparams, dhparams, m, v, lr, beta1, beta2, eps, step, stream=None):
         self._check(self.lib.morlax_adam_step(self.h, net, _ptr(hparams), _ptr(dhparams), _ptr(m), _ptr(v),
                                               float(lr), float(beta1), float(beta2), float(eps), int(step),
@@ -236,3 +247,17 @@ class Context:
                                                   float(clip_eps), int(norm_adv), _ptr(dmu), _ptr(dlogsig),
                                                   _ptr(dv), _ptr(stats), _ptr(ws),
                                                   stream if stream is not None else _stream()))
+
+
+def hypervolume_workspace_bytes(n, K):
+    """Bytes of device scratch morlax_pareto_hypervolume needs for n points in K objectives (-1: sizes not served)."""
+    return int(load().morlax_hypervolume_workspace_bytes(int(n), int(K)))
+
+
+def pareto_hypervolume(J, ref, n, K, front, hv, ws, stream=None):
+    """morlax_pareto_hypervolume: needs no context; raises MorlaxError on failure."""
+    lib = load()
+    rc = lib.morlax_pareto_hypervolume(_ptr(J), _ptr(ref), int(n), int(K), _ptr(front), _ptr(hv), _ptr(ws),
+                                       stream if stream is not None else _stream())
+    if rc != OK:
+        raise MorlaxError(rc, lib.morlax_last_error().decode())

@@ -344,6 +344,35 @@ extern "C" int morlax_sample_preferences(morlax_ctx* ctx, const float* u, int32_
     return finish(who);
 }
 
+extern "C" int morlax_eval_returns(morlax_ctx* ctx, const float* r, const uint8_t* done, float gamma, float* J,
+                                   void* stream) {
+    const char* who = "morlax_eval_returns";
+    if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
+    REQ(r, who); REQ(done, who); REQ(J, who);
+    if (!(gamma > 0.f && gamma <= 1.f)) return fail(MORLAX_ERR_SHAPE, "%s: gamma must lie in (0, 1]", who);
+    launch_eval_returns(ctx, r, done, gamma, J, (hipStream_t)stream);
+    return finish(who);
+}
+
+static bool hv_sizes_ok(int32_t n, int32_t K) {
+    return K >= 1 && K <= 8 && n >= 1 && n <= 1024 && hv_tuples(n, K) <= (uint64_t(1) << 32);
+}
+
+extern "C" int64_t morlax_hypervolume_workspace_bytes(int32_t n, int32_t K) {
+    return hv_sizes_ok(n, K) ? hv_ws_bytes(n, K) : -1;
+}
+
+extern "C" int morlax_pareto_hypervolume(const float* J, const float* ref, int32_t n, int32_t K, uint8_t* front,
+                                         double* hv, void* ws, void* stream) {
+    const char* who = "morlax_pareto_hypervolume";
+    REQ(J, who); REQ(ref, who); REQ(front, who); REQ(hv, who); REQ(ws, who);
+    if (!hv_sizes_ok(n, K))
+        return fail(MORLAX_ERR_SHAPE, "%s: needs 1 <= K <= 8, 1 <= n <= 1024 and n^(K-2) <= 2^32 (n = %d, K = %d)", who,
+                    (int)n, (int)K);
+    launch_pareto_hypervolume(J, ref, n, K, front, hv, ws, (hipStream_t)stream);
+    return finish(who);
+}
+
 extern "C" int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const float* dhparams, float* m, float* v,
                                 float lr, float beta1, float beta2, float eps, int32_t step, void* stream) {
     const char* who = "morlax_adam_step";

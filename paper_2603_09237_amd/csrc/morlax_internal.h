@@ -100,4 +100,11 @@ void launch_policy_bwd(const morlax_ctx* c, int net, const void* theta_mat, cons
                        const float* dlogsig, float* dtheta_mat, float* dtheta_vec, void* ws,
                        hipStream_t s);
 
+void launch_eval_returns(const morlax_ctx* c, const float* r, const uint8_t* done, float gamma, float* J,
+                         hipStream_t s);
+int64_t hv_ws_bytes(int n, int K);
+uint64_t hv_tuples(int n, int K);
+void launch_pareto_hypervolume(const float* J, const float* ref, int n, int K, uint8_t* front, double* hv, void* ws,
+                               hipStream_t s);
+
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }

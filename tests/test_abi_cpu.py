@@ -139,3 +139,28 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
         ctx.vec_gae_trunc(good, good, good, None, good, 0.99, 0.95, None, good, good, stream=0)
     assert e.value.code == binding.ERR_NULL
     ctx.close()
+
+
+def test_evaluation_entry_points_reject_bad_arguments(lib):
+    cfg = configs.CONFIGS[1]
+    ctx = binding.Context.from_config(cfg)
+    good = 0x10000
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.eval_returns(good, None, 0.99, good, stream=0)
+    assert e.value.code == binding.ERR_NULL
+    for gamma in (0.0, 1.5, -0.1):
+        with pytest.raises(binding.MorlaxError) as e:
+            ctx.eval_returns(good, good, gamma, good, stream=0)
+        assert e.value.code == binding.ERR_SHAPE
+    # sizes the exact hypervolume serves: K <= 8, n <= 1024, n^(K-2) <= 2^32
+    for n, K, ok in [(1, 1, True), (1024, 4, True), (256, 6, True), (257, 6, False), (1025, 2, False), (4, 9, False),
+                     (0, 2, False), (40, 8, True), (41, 8, False)]:
+        b = binding.hypervolume_workspace_bytes(n, K)
+        assert (b > 0) == ok, (n, K, b)
+        if not ok:
+            with pytest.raises(binding.MorlaxError) as e:
+                binding.pareto_hypervolume(good, good, n, K, good, good, good, stream=0)
+            assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:
+        binding.pareto_hypervolume(good, None, 4, 2, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_NULL

@@ -31,6 +31,15 @@ def test_returns_stop_at_first_done_inclusive():
     np.testing.assert_allclose(J[:, 1], J[:, 0], rtol=0)
 
 
+def test_returns_ignore_whatever_follows_the_end():
+    r = np.ones((6, 2, 1))
+    r[3:, 0, 0] = [np.inf, np.nan, -np.inf]
+    done = np.zeros((6, 2), dtype=np.uint8)
+    done[2, 0] = 1
+    J = ev.discounted_returns(r, done, 0.5, 2)
+    np.testing.assert_allclose(J[:, 0], [1.75, 2 - 0.5 ** 5], rtol=1e-15)
+
+
 def test_returns_brute_force_loops():
     rng = np.random.default_rng(5)
     T, N, K, P, g = 9, 6, 3, 3, 0.97
