@@ -57,7 +57,7 @@ void launch_eval_returns(const morlax_ctx* c, const float* r, const uint8_t* don
 // Prefix sets are bit masks over the points in the order of decreasing objective 0, so a tuple's set is the
 // AND of K - 2 masks and its staircase one pass over the set bits: a point adds x * (y - top) when its y is
 // above the top so far.  All sums are fp64 in a fixed order (per thread by ascending tuple, then a fixed
-// tree per workgroup, then the workgroups in order): results are repeatable.
+// tree per workgroup, then a fixed tree over the workgroups): results are repeatable.
 #define HV_MAX_N 1024
 #define HV_MAX_K 8
 #define HV_BLOCKS 1024
@@ -269,12 +269,18 @@ __global__ __launch_bounds__(HV_THREADS) void k_hv_slices(int n, int K, HvWs h, 
     if (threadIdx.x == 0) h.part[blockIdx.x] = red[0];
 }
 
+// the workgroups' sums: thread t adds partials t, t + 64, ... in order, then a fixed tree over the 64 threads
 __global__ __launch_bounds__(64) void k_hv_final(const double* __restrict__ part, int nb, double* __restrict__ hv) {
-    if (threadIdx.x == 0) {
-        double s = 0.0;
-        for (int b = 0; b < nb; ++b) s += part[b];
-        hv[0] = s;
+    __shared__ double red[64];
+    double s = 0.0;
+    for (int b = threadIdx.x; b < nb; b += 64) s += part[b];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 32; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
     }
+    if (threadIdx.x == 0) hv[0] = red[0];
 }
 
 uint64_t hv_tuples(int n, int K) {  // n^(K-2), saturating at 2^63
