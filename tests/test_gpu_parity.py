@@ -413,11 +413,21 @@ def pref_env_mask(cfg, prefs):
     return np.isin(g, prefs)
 
 
+# every documented maximum at once: 16 objectives, 16 actions, observation width 1024, layer width 2048,
+# factor rank 32, 64 hypernet features; two preferences.  fp32: the whole update step.  bf16: the target networks'
+# forward and backward (1600 rows per preference), not the step -- with 26 M hypernet parameters the trunk's
+# gradient is a heavily cancelling sum whose bf16 rounding noise alone passes 2 % of its RMS
+LIMITS = scaled(RAGGED, name="limits-fp32", K=16, act_dim=16, obs_dim=1024, width=2048, n_hidden=2, rank=32,
+                hyper_width=64, P=2, N=2 * 9, T=4, minibatches=1, epochs=1)
+LIMITS_BF16 = scaled(LIMITS, name="limits-bf16", wdtype=1, N=2 * 400)
+
+
 FWD_CASES = [(CONFIGS[1], None), (CONFIGS[1], (3, 9, 5, 7)), (RAGGED, None), (RAGGED, (1, 5, 2, 19)),
              (RAGGED_BF16, None), (RAGGED_BF16, (0, 3, 7, 140)), (CONFIGS[2], None), (CONFIGS[3], None),
              (CONFIGS[4], None), (CONFIGS[5], None), (CONFIGS[5], "mb"), (RAGGED_FUSED, None),
              (RAGGED_FUSED, (2, 5, 3, 30)), (RAGGED_FUSED_TANH, None)] + [(c, None) for c in SIGMA_CASES] + \
-            [(SIGMA_CASES[2], (1, 5, 2, 19)), (RAGGED_FUSED, (3, 1, 5, 1)), (RAGGED_FUSED_WIDE, None)] + RANDOM_FUSED
+            [(SIGMA_CASES[2], (1, 5, 2, 19)), (RAGGED_FUSED, (3, 1, 5, 1)), (RAGGED_FUSED_WIDE, None), (LIMITS_BF16, None)] + \
+            RANDOM_FUSED
 
 
 @pytest.mark.parametrize("cfg,rows", FWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -486,7 +496,7 @@ BWD_CASES = [(CONFIGS[1], None), (RAGGED, None), (RAGGED, (1, 5, 2, 19)), (RAGGE
              (CONFIGS[5], "mb"), (RAGGED_FUSED, None), (RAGGED_FUSED_TANH, (1, 6, 0, 37))] + \
             [(c, None) for c in SIGMA_CASES] + \
             [(RAGGED_FUSED, (3, 1, 5, 1)), (scaled(RAGGED_FUSED_WIDE, name="ragged-fused-bf16-obs512-3layers", n_hidden=3), None)] + \
-            RANDOM_FUSED
+            RANDOM_FUSED + [(LIMITS_BF16, None)]
 # (the backward of the eight-layer network is left out: its bf16 rounding noise, re-rounded at every layer on both
 # sides, passes the 2 % band of single elements without either side being wrong)
 
@@ -723,7 +733,7 @@ def run_step(cfg, torch, keep_adv_vec=True):
 
 
 @pytest.mark.parametrize("cfg", [CONFIGS[1], scaled(CONFIGS[1], name="cfg1-mb2x2", minibatches=2, epochs=2),
-                                 scaled(RAGGED, name="ragged-step", minibatches=1), CONFIGS[2],
+                                 scaled(RAGGED, name="ragged-step", minibatches=1), CONFIGS[2], LIMITS,
                                  scaled(CONFIGS[1], name="cfg1-affine-step", rank=-1, minibatches=2, epochs=1),
                                  scaled(CONFIGS[1], name="cfg1-sigma-step", sigma_state=1, minibatches=2, epochs=1),
                                  scaled(RAGGED, name="ragged-sigma-step", sigma_state=1, minibatches=1)],
