@@ -566,6 +566,134 @@ __global__ __launch_bounds__(256) void k_hyper_df_part(const float* __restrict__
     }
 }
 
+// dM, dc and the df partials in one pass over the gradient g of the stacked affine rows (P <= 128):
+//   dM[q, :] = sum_p g[p, q] f[p, :],  dc[q] = sum_p g[p, q] (four interleaved shares of the preferences, each in
+//   order, added in a fixed order),  part[wg, p, j] = sum over the workgroup's rows q of g[p, q] M[q, j].
+// A workgroup walks DMF_TPW-or-more tiles of 64 rows.  The tile of g (all P preferences x 64 rows, every
+// preference's 64 values one 256-byte run) and the tile of M go through LDS and feed fp32 MFMAs twice: wave w
+// forms dM of rows 16 w .. 16 w + 15 (contraction over p), and accumulates, across the tiles, the df partial of
+// preferences 32 w .. 32 w + 31 (contraction over the tile's rows).  The next tiles of g and M are in flight in
+// registers meanwhile.  LDS pitches: g 68 floats (the df read, lane -> preference, is conflict free; the dM read
+// shares banks four ways), f and M 16 JT + 16 (conflict free).
+#define DMF_Q 64
+template <int JT>
+__global__ __launch_bounds__(256) void k_hyper_dM_df(AffineTable at, const float* __restrict__ hp,
+                                                    const int32_t* __restrict__ mrow, const float* __restrict__ f,
+                                                    const float* __restrict__ dfac, const float* __restrict__ dvec,
+                                                    float* __restrict__ dhp, float* __restrict__ part, int P, int F,
+                                                    int64_t fac_len, int64_t vec_len, int q_total, int n_tiles, int tpw) {
+    constexpr int PD = 68, PJ = 16 * JT + 16, PP = 128;
+    __shared__ float Dl[PP][PD];
+    __shared__ float Fl[PP][PJ];
+    __shared__ float Ml[DMF_Q][PJ];
+    __shared__ float Cl[4][DMF_Q];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ln = lane & 15, kg = lane >> 4;
+    const int t_lo = blockIdx.x * tpw, t_hi = (t_lo + tpw < n_tiles) ? (t_lo + tpw) : n_tiles;
+    // f, zero-padded to 128 preferences and 16 JT features
+    for (int idx = threadIdx.x; idx < PP * 16 * JT; idx += 256) {
+        const int pp = idx / (16 * JT), j = idx % (16 * JT);
+        Fl[pp][j] = (pp < P && j < F) ? f[(int64_t)pp * F + j] : 0.f;
+    }
+    // a thread's share of a tile of g (row qq = lane of preferences wave, wave + 4, ...) and of the tile of M
+    // (piece idx = thread + 256 i of the 64 x 16 JT values), requested one tile ahead
+    constexpr int MPT = DMF_Q * 16 * JT / 256;
+    float nxt[PP / 4], mnx[MPT];
+    auto fetch = [&](int tile) {
+        const int q = tile * DMF_Q + lane;
+#pragma unroll
+        for (int i = 0; i < PP / 4; ++i) {
+            const int pp = wave + 4 * i;
+            nxt[i] = (pp < P && q < q_total) ? grad_row(dfac, dvec, pp, q, fac_len, vec_len) : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < MPT; ++i) {
+            const int idx = threadIdx.x + 256 * i, qq = idx / (16 * JT), j = idx % (16 * JT), qm = tile * DMF_Q + qq;
+            mnx[i] = (qm < q_total && j < F) ? hp[mrow[qm] + j] : 0.f;
+        }
+    };
+    float4_t accF[2][JT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) accF[u][jt] = float4_t{0.f, 0.f, 0.f, 0.f};
+    if (t_lo < t_hi) fetch(t_lo);
+    for (int tile = t_lo; tile < t_hi; ++tile) {
+        const int q0 = tile * DMF_Q;
+        __syncthreads();  // the previous tile's readers are done (first pass: orders nothing that matters)
+        {
+            float c = 0.f;  // this wave's share of dc: its preferences in order
+#pragma unroll
+            for (int i = 0; i < PP / 4; ++i) {
+                Dl[wave + 4 * i][lane] = nxt[i];
+                c += nxt[i];
+            }
+            Cl[wave][lane] = c;
+        }
+#pragma unroll
+        for (int i = 0; i < MPT; ++i) {
+            const int idx = threadIdx.x + 256 * i;
+            Ml[idx / (16 * JT)][idx % (16 * JT)] = mnx[i];
+        }
+        if (tile + 1 < t_hi) fetch(tile + 1);
+        __syncthreads();
+        // dM of rows q0 + 16 wave + (0..15): contraction over the preferences
+        {
+            float4_t accM[JT];
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) accM[jt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            const int kmax = (P + 3) / 4;
+            for (int kk = 0; kk < kmax; ++kk) {
+                const float a = Dl[4 * kk + kg][16 * wave + ln];
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt)
+                    accM[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Fl[4 * kk + kg][16 * jt + ln], accM[jt], 0, 0, 0);
+            }
+            // lane holds feature j = 16 jt + ln of rows q0 + 16 wave + 4 kg + e
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int q = q0 + 16 * wave + 4 * kg + e;
+                if (q < q_total) {
+                    float* mr = dhp + mrow[q];
+#pragma unroll
+                    for (int jt = 0; jt < JT; ++jt)
+                        if (16 * jt + ln < F) mr[16 * jt + ln] = accM[jt][e];
+                }
+            }
+        }
+        // dc: the four waves' shares, in wave order
+        if (threadIdx.x < DMF_Q && q0 + (int)threadIdx.x < q_total) {
+            const int q = q0 + threadIdx.x;
+            const int sg = find_seg(at, q);
+            dhp[at.hp_c[sg] + (q - at.q0[sg])] =
+                (Cl[0][threadIdx.x] + Cl[1][threadIdx.x]) + (Cl[2][threadIdx.x] + Cl[3][threadIdx.x]);
+        }
+        // df partial of preferences 32 wave + (0..31): contraction over the tile's rows
+#pragma unroll
+        for (int kk = 0; kk < DMF_Q / 4; ++kk) {
+            float b[JT];
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) b[jt] = Ml[4 * kk + kg][16 * jt + ln];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const float a = Dl[32 * wave + 16 * u + ln][4 * kk + kg];
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt)
+                    accF[u][jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[jt], accF[u][jt], 0, 0, 0);
+            }
+        }
+    }
+    // lane holds feature j = 16 jt + ln of preferences 32 wave + 16 u + 4 kg + e
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int pp = 32 * wave + 16 * u + 4 * kg + e, j = 16 * jt + ln;
+                if (pp < P && j < F) part[((int64_t)blockIdx.x * P + pp) * F + j] = accF[u][jt][e];
+            }
+}
+
 // df[p, j] = sum_chunk part; dz2 = df * (1 - f^2).  64 outputs per block; the four thread groups take the
 // chunks c = g, g + 4, ... and are merged in group order.
 __global__ __launch_bounds__(256) void k_hyper_df_final(const float* __restrict__ part, int n_chunk,
@@ -715,17 +843,33 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
         if (split)
             k_hyper_dA_merge<<<dim3((int)((nd.fac_len + 255) / 256), P), 256, 0, s>>>(nd, L.da_part, L.dfac, r, P);
     }
-    k_hyper_dM<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.f, dlead, dtheta_vec, dhparams, P, F, nd.fac_len,
-                                                       nd.vec_len);
     k_hyper_mrow<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.mrow, F);
-    const int qw = df_chunk_rows(at.q_total);
-    const int n_chunk = (at.q_total + qw - 1) / qw;
-    if (F <= 32)
-        k_hyper_df_part<2><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, dlead, dtheta_vec, L.df_part, P, F,
-                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk, qw);
-    else
-        k_hyper_df_part<4><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, dlead, dtheta_vec, L.df_part, P, F,
-                                                            nd.fac_len, nd.vec_len, at.q_total, n_chunk, qw);
+    int n_chunk;
+    if (P <= 128) {
+        // one pass over the gradient of the stacked rows; at least four tiles per workgroup, about a thousand
+        // workgroups at most (never more partial slots than the layout holds)
+        const int n_tiles = (at.q_total + DMF_Q - 1) / DMF_Q;
+        int tpw = (n_tiles + 1023) / 1024;
+        if (tpw < 4) tpw = 4;
+        n_chunk = (n_tiles + tpw - 1) / tpw;
+        if (F <= 32)
+            k_hyper_dM_df<2><<<n_chunk, 256, 0, s>>>(at, hparams, L.mrow, L.f, dlead, dtheta_vec, dhparams, L.df_part, P, F,
+                                                     nd.fac_len, nd.vec_len, at.q_total, n_tiles, tpw);
+        else
+            k_hyper_dM_df<4><<<n_chunk, 256, 0, s>>>(at, hparams, L.mrow, L.f, dlead, dtheta_vec, dhparams, L.df_part, P, F,
+                                                     nd.fac_len, nd.vec_len, at.q_total, n_tiles, tpw);
+    } else {
+        k_hyper_dM<<<(at.q_total + 255) / 256, 256, 0, s>>>(at, L.f, dlead, dtheta_vec, dhparams, P, F, nd.fac_len,
+                                                           nd.vec_len);
+        const int qw = df_chunk_rows(at.q_total);
+        n_chunk = (at.q_total + qw - 1) / qw;
+        if (F <= 32)
+            k_hyper_df_part<2><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, dlead, dtheta_vec, L.df_part, P, F,
+                                                                nd.fac_len, nd.vec_len, at.q_total, n_chunk, qw);
+        else
+            k_hyper_df_part<4><<<(n_chunk + 3) / 4, 256, 0, s>>>(hparams, L.mrow, dlead, dtheta_vec, L.df_part, P, F,
+                                                                nd.fac_len, nd.vec_len, at.q_total, n_chunk, qw);
+    }
     k_hyper_df_final<<<(P * F + 63) / 64, 256, 0, s>>>(L.df_part, n_chunk, L.f, L.dz2, P * F);
     k_hyper_trunk_bwd_a<<<(F * F + F + P * F + 255) / 256, 256, 0, s>>>(hparams, L.h1, L.dz2, L.dz1, dhparams, P, F,
                                                                        nd.hp_wh2, nd.hp_bh2);
