@@ -336,7 +336,10 @@ def test_hypernet_fwd_matches_oracle(cfg, torch, binding):
             assert same > 0.999, same
 
 
-@pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, scaled(RAGGED, name="rank0", rank=0)] + AFFINE_CASES,
+# (more than 128 preferences: the backward's two-pass dM / df kernels instead of the fused one)
+@pytest.mark.parametrize("cfg", all_cfgs() + [RAGGED, scaled(RAGGED, name="rank0", rank=0),
+                                             scaled(RAGGED, name="ragged-P130", P=130, N=260),
+                                             scaled(RAGGED, name="ragged-P130-affine", P=130, N=260, rank=-1)] + AFFINE_CASES,
                          ids=lambda c: c.name)
 def test_hypernet_bwd_matches_oracle(cfg, torch, binding):
     ctx = binding.Context.from_config(cfg)
