@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
     constexpr int AP = 16 * RT + 4;
     __shared__ __align__(16) float sW[64][68];
     __shared__ float sA[64][AP];
-    __shared__ float sB[16 * RT][68];
+    __shared__ float sB[DAB_NCT][16 * RT][68];
     const int p = blockIdx.y;
     const LayerDev L = nd.layer[wk.layer[blockIdx.x]];
     const int cs = wk.cs[blockIdx.x];
@@ -353,15 +353,33 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
             regs[q] = v;
         }
     };
+    // the block's columns of B(p): the same for every row block
+    for (int idx = threadIdx.x; idx < DAB_NCT * 16 * RT * 64; idx += 256) {
+        const int ct = idx / (16 * RT * 64), k = (idx / 64) % (16 * RT), cc = idx % 64, i = c_lo + ct * 64 + cc;
+        sB[ct][k][cc] = (k < r && i < c_hi) ? Bp[(int64_t)k * L.d_in + i] : 0.f;
+    }
+    // a row block's rows of A(p), requested one row block ahead
+    constexpr int APT = 64 * 16 * RT / 256;
+    float anx[APT];
+    auto fetch_a = [&](int rb) {
+#pragma unroll
+        for (int q = 0; q < APT; ++q) {
+            const int idx = threadIdx.x + 256 * q, row = idx / (16 * RT), k = idx % (16 * RT);
+            anx[q] = (rb * 64 + row < L.d_out && k < r) ? Ap[(int64_t)(rb * 64 + row) * r + k] : 0.f;
+        }
+    };
     float4 nxt[4];
     fetch(0, nxt);
+    fetch_a(0);
     for (int rb = 0; rb < nrb; ++rb) {
         const int o0 = rb * 64;
         __syncthreads();
-        for (int idx = threadIdx.x; idx < 64 * 16 * RT; idx += 256) {
-            const int row = idx / (16 * RT), k = idx % (16 * RT);
-            sA[row][k] = (o0 + row < L.d_out && k < r) ? Ap[(int64_t)(o0 + row) * r + k] : 0.f;
+#pragma unroll
+        for (int q = 0; q < APT; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            sA[idx / (16 * RT)][idx % (16 * RT)] = anx[q];
         }
+        if (rb + 1 < nrb) fetch_a(rb + 1);
         float4_t accA[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) accA[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -375,10 +393,6 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
                     const int idx = threadIdx.x + 256 * q;
                     *reinterpret_cast<float4*>(&sW[idx / 16][(idx % 16) * 4]) = nxt[q];
                 }
-                for (int idx = threadIdx.x; idx < 16 * RT * 64; idx += 256) {
-                    const int k = idx / 64, cc = idx % 64;
-                    sB[k][cc] = (k < r && i0 + cc < c_hi) ? Bp[(int64_t)k * L.d_in + i0 + cc] : 0.f;
-                }
                 if (rb * nct + ct + 1 < ntile) fetch(rb * nct + ct + 1, nxt);
                 __syncthreads();
 #pragma unroll
@@ -386,7 +400,7 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
                     const float a = sW[16 * wave + ln][4 * kk + kg];
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt)
-                        accA[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, sB[16 * rt + ln][4 * kk + kg], accA[rt], 0, 0, 0);
+                        accA[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, sB[ct][16 * rt + ln][4 * kk + kg], accA[rt], 0, 0, 0);
                 }
 #pragma unroll
                 for (int kk = 0; kk < 16; ++kk) {
