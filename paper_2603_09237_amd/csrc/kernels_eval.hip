@@ -250,7 +250,7 @@ __global__ __launch_bounds__(HV_THREADS) void k_hv_slices(int n, int K, HvWs h, 
         if (j_lo >= j_hi) continue;
         double cur = j_lo > 0 ? staircase(j_lo - 1) : 0.0, acc = 0.0;
         for (int j = j_lo; j < j_hi; ++j) {
-            const int pos = pr0[j];
+            const int pos = (int)pr0[j];
             uint64_t word = 0;
 #pragma unroll
             for (int wd = 0; wd < WB; ++wd)
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(HV_THREADS) void k_hv_slices(int n, int K, HvWs h, 
     red[threadIdx.x] = sum;
     __syncthreads();
     for (int s = HV_THREADS / 2; s > 0; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
         __syncthreads();
     }
     if (threadIdx.x == 0) h.part[blockIdx.x] = red[0];

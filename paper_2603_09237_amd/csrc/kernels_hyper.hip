@@ -386,7 +386,6 @@ __global__ __launch_bounds__(256) void k_hyper_dAB(NetDev nd, DabWork wk, const 
 #pragma unroll
         for (int ct = 0; ct < DAB_NCT; ++ct) {
             if (ct < nct) {
-                const int i0 = c_lo + ct * 64;
                 __syncthreads();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -831,7 +830,7 @@ void launch_hypernet_bwd(const morlax_ctx* c, int net, const float* hparams, con
     const float* dlead = affine ? dtheta_mat : L.dfac;
     // kept: the workspace still holds what the forward pass of this network left there (h1, f, the factors)
     if (affine) {
-        // only f is needed again; dW0 and dMW come out of k_hyper_dM below (W0 is the constant term of those rows)
+        // only f is needed again; dW0 and dMW come out of the dM pass below (W0 is the constant term of those rows)
         if (!kept)
             k_hyper_trunk<<<P, 64, 0, s>>>(hparams, w, L.h1, L.f, K, F, nd.hp_wh1, nd.hp_bh1, nd.hp_wh2, nd.hp_bh2);
     } else {
