@@ -1212,7 +1212,7 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
 // ---- fused forward: observations -> every hidden layer -> output layer (bf16, width 512) --------------
 // (paper Sec. III-C: the target network of a preference applied to that preference's environments, in the
 // rollout and in the update.)  One workgroup of eight waves carries 128 rows of one preference through the
-// whole network.  The activations of the tile live in LDS (128 rows x 1 KB, 16-byte chunks XOR-swizzled by
+// whole network, tile after tile (one workgroup per CU).  The activations of the tile live in LDS (128 rows x 1 KB, 16-byte chunks XOR-swizzled by
 // the row) and are rewritten in place layer after layer; HBM sees the observations once, the outputs once
 // and, in the saving variant, the stores of h and act'(z) that the backward pass reads -- never a load of
 // an activation.
@@ -1306,224 +1306,231 @@ __device__ inline int opaque(int v) {
 template <int ACT, bool SAVE>
 __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
     extern __shared__ __align__(16) unsigned char dlds[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 31, lg = lane >> 5;
-    const int tile = xcd_remap(blockIdx.x, a.n_tiles);
-    const int p = tile / a.tiles_m, m0 = (tile % a.tiles_m) * FF_ROWS;
-    const int rows = a.M - m0 < FF_ROWS ? a.M - m0 : FF_ROWS;
-    const int wn = wave * 64;
+    // One workgroup per CU walks the tiles (no launch gap, no register spill in the saving variant).  Everything
+    // derived from the lane is formed again for every tile behind opaque(): kept across tiles it would occupy
+    // registers that the products and the epilogue need.
+    for (int vt = blockIdx.x; vt < a.n_tiles; vt += gridDim.x) {
+        const int lane = opaque((int)(threadIdx.x & 63)), lr = lane & 31, lg = lane >> 5;
+        const int wave = __builtin_amdgcn_readfirstlane(opaque((int)(threadIdx.x >> 6)));
+        const int tile = xcd_remap(vt, a.n_tiles);
+        const int p = tile / a.tiles_m, m0 = (tile % a.tiles_m) * FF_ROWS;
+        const int rows = a.M - m0 < FF_ROWS ? a.M - m0 : FF_ROWS;
+        const int wn = wave * 64;
 
-    const bf16_t* Wp = a.theta_frag + (int64_t)p * a.mat_len;
-    const float* bp = a.theta_vec + (int64_t)p * a.vec_len;
-    auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's place in the wave's stream of W_l(p), per feature half
-        const int K = l == 0 ? a.O : FF_W;
+        const bf16_t* Wp = a.theta_frag + (int64_t)p * a.mat_len;
+        const float* bp = a.theta_vec + (int64_t)p * a.vec_len;
+        auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's place in the wave's stream of W_l(p), per feature half
+            const int K = l == 0 ? a.O : FF_W;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            w[j] = reinterpret_cast<const char*>(Wp + a.mat_off[l]) + (int64_t)wave * (K >> 5) * 4096 + j * 2048 +
-                   lane * 16;
-    };
-    // unit u of a layer = 32 contraction indices per lane group, 4 KB of the wave's stream (fragment order)
-    auto load_w = [&](uint4 (&wf)[2][2], const char* w0, const char* w1, int u) {
-        const int off = u * 4096;
-        wf[0][0] = *reinterpret_cast<const uint4*>(w0 + off);
-        wf[0][1] = *reinterpret_cast<const uint4*>(w0 + off + 1024);
-        wf[1][0] = *reinterpret_cast<const uint4*>(w1 + off);
-        wf[1][1] = *reinterpret_cast<const uint4*>(w1 + off + 1024);
-    };
-    // W fragments: two buffers, a unit's request one unit ahead of its use (a longer distance with four
-    // buffers measured slower: the registers it takes spill in the epilogue)
-    const char* wp[2];
-    uint4 wfa[2][2], wfb[2][2];
-    float16_t acc[4][2];
-    w_rows(0, wp);
-    load_w(wfa, wp[0], wp[1], 0);
+            for (int j = 0; j < 2; ++j)
+                w[j] = reinterpret_cast<const char*>(Wp + a.mat_off[l]) + (int64_t)wave * (K >> 5) * 4096 + j * 2048 +
+                       lane * 16;
+        };
+        // unit u of a layer = 32 contraction indices per lane group, 4 KB of the wave's stream (fragment order)
+        auto load_w = [&](uint4 (&wf)[2][2], const char* w0, const char* w1, int u) {
+            const int off = u * 4096;
+            wf[0][0] = *reinterpret_cast<const uint4*>(w0 + off);
+            wf[0][1] = *reinterpret_cast<const uint4*>(w0 + off + 1024);
+            wf[1][0] = *reinterpret_cast<const uint4*>(w1 + off);
+            wf[1][1] = *reinterpret_cast<const uint4*>(w1 + off + 1024);
+        };
+        // W fragments: two buffers, a unit's request one unit ahead of its use (a longer distance with four
+        // buffers measured slower: the registers it takes spill in the epilogue)
+        const char* wp[2];
+        uint4 wfa[2][2], wfb[2][2];
+        float16_t acc[4][2];
+        w_rows(0, wp);
+        load_w(wfa, wp[0], wp[1], 0);
 
-    {  // the tile's observations, gathered from the time-major tensor and rounded to bf16; rows past the end
-       // repeat the last row (their results are never stored).  The saving variant keeps the compact copy
-       // that the first layer's dW product reads.
-        const int cpr = a.O >> 3;
-        for (int id = threadIdx.x; id < FF_ROWS * cpr; id += 512) {
-            const int r = id / cpr, c = id % cpr, rc = r < rows ? r : rows - 1;
-            float v[8];
-            get8(a.x + a.rm.row(p, m0 + rc) * a.O + 8 * c, v);
-            const uint4 q = pack_chunk<bf16_t>(v);
-            *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) = q;
-            if (SAVE && r < rows) *reinterpret_cast<uint4*>(a.x0 + ((int64_t)p * a.M + m0 + r) * a.O + 8 * c) = q;
-        }
-    }
-    // fragment addresses: row 32 i + lr, chunk (8 s + 4 lg + jj) ^ (lr & 15)
-    const int x = lr & 15;
-    const unsigned char* arow = dlds + lr * 1024;
-    uint32_t aoff[4];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) aoff[jj] = (uint32_t)(((4 * lg + jj) ^ (x & 7)) * 16);
-    const int sflip = x >> 3;
-
-    // one unit: 16 products; HALF = u & 1 picks the chunks 2 HALF, 2 HALF + 1 of the super-step
-    auto unit = [&](const uint4 (&wf)[2][2], int u, auto half_tag) {
-        constexpr int HALF = decltype(half_tag)::value;
-        const unsigned char* as = arow + ((u >> 1) ^ sflip) * 128;
-        uint4 fa[2][4];
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) fa[jj][i] = *reinterpret_cast<const uint4*>(as + i * 32768 + aoff[2 * HALF + jj]);
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(wf[j][jj], fa[jj][i], acc[i][j]);
-    };
-    // lane n of `bias` holds b_l[wn + n]; every accumulator of a lane's octet o starts from its feature's bias
-    auto init_acc = [&](float bias) {
-#pragma unroll
-        for (int o = 0; o < 4; ++o)
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float b = __shfl(bias, 16 * o + 8 * lg + u, 64);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) acc[i][o >> 1][8 * (o & 1) + u] = b;
+        {  // the tile's observations, gathered from the time-major tensor and rounded to bf16; rows past the end
+           // repeat the last row (their results are never stored).  The saving variant keeps the compact copy
+           // that the first layer's dW product reads.
+            const int cpr = a.O >> 3;
+            for (int id = threadIdx.x; id < FF_ROWS * cpr; id += 512) {
+                const int r = id / cpr, c = id % cpr, rc = r < rows ? r : rows - 1;
+                float v[8];
+                get8(a.x + a.rm.row(p, m0 + rc) * a.O + 8 * c, v);
+                const uint4 q = pack_chunk<bf16_t>(v);
+                *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) = q;
+                if (SAVE && r < rows) *reinterpret_cast<uint4*>(a.x0 + ((int64_t)p * a.M + m0 + r) * a.O + 8 * c) = q;
             }
-    };
-    auto load_bias = [&](int l) { return bp[a.vec_off[l] + wn + lane]; };
-
-    init_acc(load_bias(0));
-    __syncthreads();
-    for (int l = 0; l < a.L; ++l) {
-        const bool more = l + 1 < a.L;
-        // the last request of a layer fetches the first unit of the next one (of this one again after the last
-        // layer: a harmless, valid load), so that every pass through the loop has the same loads in flight
-        const char* wq[2];
-        w_rows(more ? l + 1 : l, wq);
-        const int nU = l == 0 ? a.O >> 5 : FF_W / 32;
-        for (int u = 0; u < nU; u += 2) {
-            load_w(wfb, wp[0], wp[1], u + 1);
-            __builtin_amdgcn_sched_barrier(0);  // the requests stay ahead of the products they overlap with
-            unit(wfa, u, std::integral_constant<int, 0>{});
-            const bool last = u + 2 == nU;
-            load_w(wfa, last ? wq[0] : wp[0], last ? wq[1] : wp[1], last ? 0 : u + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            unit(wfb, u + 1, std::integral_constant<int, 1>{});
         }
-        wp[0] = wq[0];
-        wp[1] = wq[1];
-        __syncthreads();  // every wave has read the layer's input for the last time
-        const float bnext = load_bias(more ? l + 1 : l);
-        {
-            const int ol = opaque(lane), olr = ol & 31, olg = ol >> 5, ox = ol & 15;
-            unsigned char* hrow = dlds + olr * 1024;
-            unsigned char* patch = dlds + FF_ACT_BYTES + wave * 4096;
-            gfix16_t* Gl = SAVE ? a.G + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
+        // fragment addresses: row 32 i + lr, chunk (8 s + 4 lg + jj) ^ (lr & 15)
+        const int x = lr & 15;
+        const unsigned char* arow = dlds + lr * 1024;
+        uint32_t aoff[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint4 gq[4];
+        for (int jj = 0; jj < 4; ++jj) aoff[jj] = (uint32_t)(((4 * lg + jj) ^ (x & 7)) * 16);
+        const int sflip = x >> 3;
+
+        // one unit: 16 products; HALF = u & 1 picks the chunks 2 HALF, 2 HALF + 1 of the super-step
+        auto unit = [&](const uint4 (&wf)[2][2], int u, auto half_tag) {
+            constexpr int HALF = decltype(half_tag)::value;
+            const unsigned char* as = arow + ((u >> 1) ^ sflip) * 128;
+            uint4 fa[2][4];
 #pragma unroll
-                for (int o = 0; o < 4; ++o) {
-                    const int j = o >> 1, h = o & 1;
-                    float v[8], g[8];
+            for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) act_pair<ACT>(acc[i][j][8 * h + u], v[u], g[u]);
-                    const int cc = 8 * wave + 4 * j + 2 * h + olg;
-                    *reinterpret_cast<uint4*>(hrow + i * 32768 + ((cc ^ ox) * 16)) = pack_chunk<bf16_t>(v);
-                    if (SAVE) gq[o] = pack8(g, (const gfix16_t*)nullptr).lo;
+                for (int i = 0; i < 4; ++i) fa[jj][i] = *reinterpret_cast<const uint4*>(as + i * 32768 + aoff[2 * HALF + jj]);
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) Mma32<bf16_t>::run(wf[j][jj], fa[jj][i], acc[i][j]);
+        };
+        // lane n of `bias` holds b_l[wn + n]; every accumulator of a lane's octet o starts from its feature's bias
+        auto init_acc = [&](float bias) {
+#pragma unroll
+            for (int o = 0; o < 4; ++o)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float b = __shfl(bias, 16 * o + 8 * lg + u, 64);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[i][o >> 1][8 * (o & 1) + u] = b;
                 }
-                if (SAVE) {  // act'(z) leaves through the wave's patch as whole 128-byte row segments
+        };
+        auto load_bias = [&](int l) { return bp[a.vec_off[l] + wn + lane]; };
+
+        init_acc(load_bias(0));
+        __syncthreads();
+        for (int l = 0; l < a.L; ++l) {
+            const bool more = l + 1 < a.L;
+            // the last request of a layer fetches the first unit of the next one (of this one again after the last
+            // layer: a harmless, valid load), so that every pass through the loop has the same loads in flight
+            const char* wq[2];
+            w_rows(more ? l + 1 : l, wq);
+            const int nU = l == 0 ? a.O >> 5 : FF_W / 32;
+            for (int u = 0; u < nU; u += 2) {
+                load_w(wfb, wp[0], wp[1], u + 1);
+                __builtin_amdgcn_sched_barrier(0);  // the requests stay ahead of the products they overlap with
+                unit(wfa, u, std::integral_constant<int, 0>{});
+                const bool last = u + 2 == nU;
+                load_w(wfa, last ? wq[0] : wp[0], last ? wq[1] : wp[1], last ? 0 : u + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                unit(wfb, u + 1, std::integral_constant<int, 1>{});
+            }
+            wp[0] = wq[0];
+            wp[1] = wq[1];
+            __syncthreads();  // every wave has read the layer's input for the last time
+            const float bnext = load_bias(more ? l + 1 : l);
+            {
+                const int ol = opaque(lane), olr = ol & 31, olg = ol >> 5, ox = ol & 15;
+                unsigned char* hrow = dlds + olr * 1024;
+                unsigned char* patch = dlds + FF_ACT_BYTES + wave * 4096;
+                gfix16_t* Gl = SAVE ? a.G + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint4 gq[4];
 #pragma unroll
                     for (int o = 0; o < 4; ++o) {
-                        const int cch = 4 * (o >> 1) + 2 * (o & 1) + olg;
-                        *reinterpret_cast<uint4*>(patch + olr * 128 + ((cch ^ (olr & 7)) * 16)) = gq[o];
-                    }
-                    __builtin_amdgcn_wave_barrier();
+                        const int j = o >> 1, h = o & 1;
+                        float v[8], g[8];
 #pragma unroll
-                    for (int it = 0; it < 4; ++it) {
-                        const int prow = it * 8 + (ol >> 3), pc = ol & 7;
-                        const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
-                        const int gr = 32 * i + prow;
-                        if (gr < rows) *reinterpret_cast<uint4*>(Gl + (int64_t)gr * FF_W + pc * 8) = u;
+                        for (int u = 0; u < 8; ++u) act_pair<ACT>(acc[i][j][8 * h + u], v[u], g[u]);
+                        const int cc = 8 * wave + 4 * j + 2 * h + olg;
+                        *reinterpret_cast<uint4*>(hrow + i * 32768 + ((cc ^ ox) * 16)) = pack_chunk<bf16_t>(v);
+                        if (SAVE) gq[o] = pack8(g, (const gfix16_t*)nullptr).lo;
                     }
-                    __builtin_amdgcn_wave_barrier();
+                    if (SAVE) {  // act'(z) leaves through the wave's patch as whole 128-byte row segments
+#pragma unroll
+                        for (int o = 0; o < 4; ++o) {
+                            const int cch = 4 * (o >> 1) + 2 * (o & 1) + olg;
+                            *reinterpret_cast<uint4*>(patch + olr * 128 + ((cch ^ (olr & 7)) * 16)) = gq[o];
+                        }
+                        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                        for (int it = 0; it < 4; ++it) {
+                            const int prow = it * 8 + (ol >> 3), pc = ol & 7;
+                            const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
+                            const int gr = 32 * i + prow;
+                            if (gr < rows) *reinterpret_cast<uint4*>(Gl + (int64_t)gr * FF_W + pc * 8) = u;
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
                 }
             }
-        }
-        __syncthreads();  // the layer's output is complete in LDS
-        if (SAVE) {  // h to memory, one whole row per wave and store
-            const int ol = opaque(lane);
-            bf16_t* Hl = a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + 8 * ol;
-            uint4 hv[16];
+            __syncthreads();  // the layer's output is complete in LDS
+            if (SAVE) {  // h to memory, one whole row per wave and store
+                const int ol = opaque(lane);
+                bf16_t* Hl = a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + 8 * ol;
+                uint4 hv[16];
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int r = 8 * q + wave;
-                hv[q] = *reinterpret_cast<const uint4*>(dlds + r * 1024 + ((ol ^ (r & 15)) * 16));
-            }
+                for (int q = 0; q < 16; ++q) {
+                    const int r = 8 * q + wave;
+                    hv[q] = *reinterpret_cast<const uint4*>(dlds + r * 1024 + ((ol ^ (r & 15)) * 16));
+                }
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int r = 8 * q + wave;
-                if (r < rows) *reinterpret_cast<uint4*>(Hl + (int64_t)r * FF_W) = hv[q];
+                for (int q = 0; q < 16; ++q) {
+                    const int r = 8 * q + wave;
+                    if (r < rows) *reinterpret_cast<uint4*>(Hl + (int64_t)r * FF_W) = hv[q];
+                }
             }
+            if (more) init_acc(bnext);
         }
-        if (more) init_acc(bnext);
-    }
 
-    // output layer: wave w takes rows 16 w .. 16 w + 15 of the tile with 16x16x32 products; lane (hl, hg)
-    // supplies row hl / output hl at contraction chunk 4 u + hg and receives output hl of rows 4 hg + e
-    {
-        const int hl = lane & 15, hg = lane >> 4;
-        const int r = 16 * wave + hl;
-        const unsigned char* hrow = dlds + r * 1024;
-        const bf16_t* wrow = a.theta_mat + (int64_t)p * a.mat_len + a.head_mat_off + (int64_t)hl * FF_W;
-        const bool b_ok = hl < a.out_dim;
-        float4_t c = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
+        // output layer: wave w takes rows 16 w .. 16 w + 15 of the tile with 16x16x32 products; lane (hl, hg)
+        // supplies row hl / output hl at contraction chunk 4 u + hg and receives output hl of rows 4 hg + e
+        {
+            const int hl = lane & 15, hg = lane >> 4;
+            const int r = 16 * wave + hl;
+            const unsigned char* hrow = dlds + r * 1024;
+            const bf16_t* wrow = a.theta_mat + (int64_t)p * a.mat_len + a.head_mat_off + (int64_t)hl * FF_W;
+            const bool b_ok = hl < a.out_dim;
+            float4_t c = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            uint4 fa[8], fb[8];
+            for (int half = 0; half < 2; ++half) {
+                uint4 fa[8], fb[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int ch = 32 * half + 4 * u + hg;
-                fa[u] = *reinterpret_cast<const uint4*>(hrow + ((ch ^ (r & 15)) * 16));
-                fb[u] = make_uint4(0, 0, 0, 0);
-                if (b_ok) fb[u] = *reinterpret_cast<const uint4*>(wrow + 8 * ch);
-            }
+                for (int u = 0; u < 8; ++u) {
+                    const int ch = 32 * half + 4 * u + hg;
+                    fa[u] = *reinterpret_cast<const uint4*>(hrow + ((ch ^ (r & 15)) * 16));
+                    fb[u] = make_uint4(0, 0, 0, 0);
+                    if (b_ok) fb[u] = *reinterpret_cast<const uint4*>(wrow + 8 * ch);
+                }
 #pragma unroll
-            for (int u = 0; u < 8; u += 2) {
-                Mma16<bf16_t>::run(fa[u], fb[u], c);
-                Mma16<bf16_t>::run(fa[u + 1], fb[u + 1], c2);
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] += c2[e];
-        const float bias = b_ok ? bp[a.head_vec_off + hl] : 0.f;
-        const bool a_ok = hl < a.adim;  // lanes that hold an action mean
-        float ls_p = 0.f;
-        if (a.eps && a_ok && !a.sig_state) ls_p = bp[a.logsig_off + hl];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int tr = 16 * wave + 4 * hg + e, m = m0 + tr;
-            const bool ok = (tr < rows) && b_ok;
-            const float z = c[e] + bias;
-            const float o = (hl < a.tanh_cols) ? tanhf(z) : z;
-            int64_t row = 0;
-            if (tr < rows) row = a.rm.row(p, m);
-            float term = 0.f;
-            // a state-dependent log sigma sits adim columns to the right, in the same group of 16 lanes
-            const float ls_s = __shfl(o, (lane & 48) | ((hl + a.adim) & 15), 64);
-            if (ok) {
-                a.out[row * a.out_dim + hl] = o;
-                if (SAVE) a.saved_out[((int64_t)p * a.M + m) * OUT_PITCH + hl] = o;
-                if (a.eps && a_ok) {
-                    const float ls = a.sig_state ? ls_s : ls_p;
-                    const float ep = a.eps[row * a.adim + hl];
-                    a.act[row * a.adim + hl] = o + expf(ls) * ep;
-                    term = -0.5f * ep * ep - ls;
+                for (int u = 0; u < 8; u += 2) {
+                    Mma16<bf16_t>::run(fa[u], fb[u], c);
+                    Mma16<bf16_t>::run(fa[u + 1], fb[u + 1], c2);
                 }
             }
-            if (a.eps) {
-                term += __shfl_xor(term, 8, 64);
-                term += __shfl_xor(term, 4, 64);
-                term += __shfl_xor(term, 2, 64);
-                term += __shfl_xor(term, 1, 64);
-                if (tr < rows && hl == 0) a.logp[row] = term - 0.918938533204672742f * (float)a.adim;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c[e] += c2[e];
+            const float bias = b_ok ? bp[a.head_vec_off + hl] : 0.f;
+            const bool a_ok = hl < a.adim;  // lanes that hold an action mean
+            float ls_p = 0.f;
+            if (a.eps && a_ok && !a.sig_state) ls_p = bp[a.logsig_off + hl];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int tr = 16 * wave + 4 * hg + e, m = m0 + tr;
+                const bool ok = (tr < rows) && b_ok;
+                const float z = c[e] + bias;
+                const float o = (hl < a.tanh_cols) ? tanhf(z) : z;
+                int64_t row = 0;
+                if (tr < rows) row = a.rm.row(p, m);
+                float term = 0.f;
+                // a state-dependent log sigma sits adim columns to the right, in the same group of 16 lanes
+                const float ls_s = __shfl(o, (lane & 48) | ((hl + a.adim) & 15), 64);
+                if (ok) {
+                    a.out[row * a.out_dim + hl] = o;
+                    if (SAVE) a.saved_out[((int64_t)p * a.M + m) * OUT_PITCH + hl] = o;
+                    if (a.eps && a_ok) {
+                        const float ls = a.sig_state ? ls_s : ls_p;
+                        const float ep = a.eps[row * a.adim + hl];
+                        a.act[row * a.adim + hl] = o + expf(ls) * ep;
+                        term = -0.5f * ep * ep - ls;
+                    }
+                }
+                if (a.eps) {
+                    term += __shfl_xor(term, 8, 64);
+                    term += __shfl_xor(term, 4, 64);
+                    term += __shfl_xor(term, 2, 64);
+                    term += __shfl_xor(term, 1, 64);
+                    if (tr < rows && hl == 0) a.logp[row] = term - 0.918938533204672742f * (float)a.adim;
+                }
             }
         }
+        __syncthreads();  // the tile's last readers are done before the next tile is gathered
     }
 }
 
@@ -2054,7 +2061,8 @@ static void launch_fused_fwd(const morlax_ctx* c, const FusedFwdArgs& a, hipStre
     const double per_row = 2.0 * FF_W * ((double)a.O + (double)(a.L - 1) * FF_W);
     GemmProf::Rec* r = prof_take(c, 5, per_row * a.M * c->d.P);
     if (r) (void)hipEventRecord(r->a, s);
-    k_mlp_fused_fwd<ACT, SAVE><<<a.n_tiles, 512, lds, s>>>(a);
+    const int cus = resident_slots() / 2;  // one workgroup per CU (the tile fills its LDS)
+    k_mlp_fused_fwd<ACT, SAVE><<<a.n_tiles < cus ? a.n_tiles : cus, 512, lds, s>>>(a);
     if (r) (void)hipEventRecord(r->b, s);
 }
 
