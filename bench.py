@@ -35,7 +35,7 @@ KERNEL_OF_KIND = {
 
 # HBM bytes per launch of a GEMM launch kind, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script scaled by
 # a copy of known size (profiles/fused_fwd_grouped_gemm_cfg5_hbm_traffic.txt); workloads without such a run report null
-MEASURED_TRAFFIC_BYTES = {("cfg5-largest-K6-P128-N16384-T64-4x512-silu-bf16-4mbx2ep", "fwd_fused"): 2456.1e6}
+MEASURED_TRAFFIC_BYTES = {("cfg5-largest-K6-P128-N16384-T64-4x512-silu-bf16-4mbx2ep", "fwd_fused"): 2273.8e6}
 
 
 def cpu_baseline(cfg_full):
