@@ -164,3 +164,14 @@ def test_evaluation_entry_points_reject_bad_arguments(lib):
     with pytest.raises(binding.MorlaxError) as e:
         binding.pareto_hypervolume(good, None, 4, 2, good, good, good, stream=0)
     assert e.value.code == binding.ERR_NULL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
