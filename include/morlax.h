@@ -10,7 +10,9 @@
  * Conventions for every entry point
  *  - All tensor pointers are DEVICE pointers owned by the caller, contiguous, 16-byte aligned.
  *    The library allocates no device memory and frees none.  `ws` is caller-provided device
- *    scratch of at least morlax_workspace_bytes(); its contents are undefined between calls.
+ *    scratch of `ws_bytes` bytes; morlax_workspace_bytes() is enough for every op on a selection,
+ *    a smaller buffer is accepted when it covers what the called op needs, else the call fails
+ *    with MORLAX_ERR_WORKSPACE.  Its contents are undefined between calls.
  *  - `stream` is a hipStream_t passed as void*.  Every op only enqueues kernels on it and returns;
  *    nothing synchronises.  Calls that share `ws`, `saved` or outputs must be stream-ordered.
  *  - Time-major layouts: x [Tx, N, O], out [Tx, N, A|K], r [T, N, K], done [T, N] ...; the row of
@@ -48,7 +50,7 @@ typedef enum {
     MORLAX_ERR_NULL = -1,        /* a required pointer is NULL */
     MORLAX_ERR_SHAPE = -2,       /* P < 2, P does not divide N, K < 1, bad row selection, misaligned pointer ... */
     MORLAX_ERR_UNSUPPORTED = -3, /* a size outside what the kernels are built for */
-    MORLAX_ERR_WORKSPACE = -4,   /* reserved */
+    MORLAX_ERR_WORKSPACE = -4,   /* ws_bytes is less than the op needs for these arguments */
     MORLAX_ERR_HIP = -5          /* a HIP runtime call failed */
 } morlax_status;
 
@@ -71,7 +73,7 @@ typedef struct {
 } morlax_rows;
 
 /* Limits: 1 <= K <= 16, 1 <= act_dim <= 16, 1 <= obs_dim <= 1024, 1 <= n_hidden <= 8,
- * width a multiple of 16 in [16, 2048], -1 <= rank <= 32, 1 <= hyper_width <= 64, P >= 2, P | N. */
+ * width a multiple of 16 in [16, 2048], -1 <= rank <= 32, 1 <= hyper_width <= 64, 2 <= P <= 65535, P | N. */
 int morlax_create(const morlax_dims* dims, morlax_ctx** out);
 void morlax_destroy(morlax_ctx* ctx);
 const char* morlax_last_error(void); /* thread-local, never NULL */
@@ -99,7 +101,7 @@ int morlax_env_pref_index(const morlax_ctx* ctx, int32_t* out, void* stream);
  *   hparams [hparam_count] fp32, w [P, K] fp32 (rows on the simplex; not checked on the device)
  *   -> theta_mat [P, theta_mat_len] (wdtype), theta_vec [P, theta_vec_len] fp32. */
 int morlax_hypernet_fwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
-                        void* theta_mat, float* theta_vec, void* ws, void* stream);
+                        void* theta_mat, float* theta_vec, void* ws, int64_t ws_bytes, void* stream);
 
 /* Reverse mode of morlax_hypernet_fwd (Sec. III-C, update phase: the losses are differentiated
  * back into each hypernetwork separately).  dtheta_mat [P, theta_mat_len] fp32 and dtheta_vec
@@ -107,7 +109,7 @@ int morlax_hypernet_fwd(morlax_ctx* ctx, int net, const float* hparams, const fl
  * dhparams [hparam_count] fp32 is overwritten.  Reductions run in a fixed order (no atomics). */
 int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
                         const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
-                        void* ws, void* stream);
+                        void* ws, int64_t ws_bytes, void* stream);
 
 /* The same reverse pass for a caller that kept the forward pass's workspace: ws_fwd must be the buffer the
  * last morlax_hypernet_fwd of this network ran in -- with these hparams and w -- and nothing may have
@@ -117,7 +119,7 @@ int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparams, const fl
  * gradients, not an error. */
 int morlax_hypernet_bwd_kept(morlax_ctx* ctx, int net, const float* hparams, const float* w,
                              const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
-                             void* ws_fwd, void* stream);
+                             void* ws_fwd, int64_t ws_bytes, void* stream);
 
 /* Grouped forward of the target-network family {pi_i} or {V_i} (Sec. III-C, rollout phase;
  * Sec. III-E for the tanh on the actor output): every selected (t, n) row of x goes through the
@@ -130,7 +132,7 @@ int morlax_hypernet_bwd_kept(morlax_ctx* ctx, int net, const float* hparams, con
  *   saved: NULL for inference/rollout, else morlax_saved_bytes() bytes that policy_bwd needs. */
 int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
                       const float* x, const morlax_rows* rows, float* out, const float* eps,
-                      float* act, float* logp, void* saved, void* ws, void* stream);
+                      float* act, float* logp, void* saved, void* ws, int64_t ws_bytes, void* stream);
 
 /* Grouped backward through the target networks (Sec. III-C, update phase).  dout [Tx, N, A|K] is
  * dL/d(out) on the selected rows; `saved` comes from the matching policy_fwd call (same ctx, net,
@@ -140,7 +142,7 @@ int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat, const flo
 int morlax_policy_bwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
                       const float* x, const morlax_rows* rows, const void* saved, const float* dout,
                       const float* dlogsig, float* dtheta_mat, float* dtheta_vec, void* ws,
-                      void* stream);
+                      int64_t ws_bytes, void* stream);
 
 /* Vector generalised advantage estimation, one reverse-time scan per (environment, objective),
  * then scalarisation with the environment's trade-off (Sec. III-C, update phase).
@@ -155,7 +157,7 @@ int morlax_vec_gae(morlax_ctx* ctx, const float* r, const float* v, const uint8_
                    const float* w, float gamma, float lambda, float* adv_vec, float* vtarg,
                    float* adv_s, void* stream);
 
-/* The same scan with time limits told apart from failures (Sec. III-D: terminations and truncations
+/* The same scan with time limits told apart from failures (Sec. III-E: terminations and truncations
  * are distinguished in value estimation).  trunc [T, N] u8, non-zero: the episode was cut by a time
  * limit at step t.  Such a step keeps the bootstrap, delta = r_t + gamma V_{t+1} - V_t with V_{t+1}
  * the value of the state the episode was cut at (the caller stores it in v[t+1]), and restarts the
@@ -193,26 +195,27 @@ int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const float* dhpa
  *   adv_out[t, n] = sum_k w[g(n), k] (adv_vec[t, n, k] - mean_k) / (std_k + 1e-8).
  * Feed adv_out to morlax_ppo_loss_grad with norm_adv = 0.  All pointers are DEVICE pointers:
  * adv_vec [T, N, K] (as written by morlax_vec_gae), w [P, K], adv_out [T, N] (only the selected cells are
- * written), ws >= morlax_workspace_bytes(ctx, rows).  rows selects t in [0, T).  Sums in fp64 in a fixed
+ * written).  rows selects t in [0, T).  Sums in fp64 in a fixed
  * order: results are repeatable.  Errors: NULL arguments, invalid rows. */
 int morlax_scalarize_normalized(morlax_ctx* ctx, const morlax_rows* rows, const float* adv_vec,
-                                const float* w, float* adv_out, void* ws, void* stream);
+                                const float* w, float* adv_out, void* ws, int64_t ws_bytes, void* stream);
 
 /* Clipped PPO surrogate and vector value loss with their gradients on one minibatch (Sec. III-C,
  * update phase).  B = selected cells.  Ahat = (adv_s - mean) / (std + 1e-8) over the selection
  * (population std) when norm_adv != 0, else adv_s.  logp = Gaussian log-density of act under
  * (mu, sigma = exp(logsig[g(n)])); rho = exp(logp - logp_old);
  *   L_pi = -(1/B) sum min(rho Ahat, clip(rho, 1-eps, 1+eps) Ahat);  L_V = (1/B) sum ||v - vtarg||^2.
- *   mu, act [Tx, N, A]; logsig [P, A] with row stride logsig_stride floats (pass the tail of the
- *   actor theta_vec and its row length); logp_old, adv_s [Tx, N]; v, vtarg [Tx, N, K].
- *   -> dmu [Tx, N, A], dv [Tx, N, K] on the selected cells; dlogsig [P, A] (summed over each
+ *   mu, act [T, N, A]; logsig [P, A] with row stride logsig_stride floats (pass the tail of the
+ *   actor theta_vec and its row length); logp_old, adv_s [T, N]; v, vtarg [T, N, K]; rows selects
+ *   t in [0, T) (the rollout's actions, advantages and targets exist for T steps, not T + 1).
+ *   -> dmu [T, N, A], dv [T, N, K] on the selected cells; dlogsig [P, A] (summed over each
  *   preference's selected rows, fixed order); stats [8] fp32 on the device:
  *   L_pi, L_V, fraction with |rho-1| > eps, mean(logp_old - logp), adv mean, adv std, mean rho, B. */
 int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
                          const float* logsig, int32_t logsig_stride, const float* act,
                          const float* logp_old, const float* adv_s, const float* v,
                          const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
-                         float* dlogsig, float* dv, float* stats, void* ws, void* stream);
+                         float* dlogsig, float* dv, float* stats, void* ws, int64_t ws_bytes, void* stream);
 
 /* Evaluation side (Fig. 2a: a trade-off is picked, its policy rolled out, and the returns judged).
  * morlax_eval_returns: the return vector of every trade-off from a finished roll-out (Sec. II-A:
@@ -237,19 +240,7 @@ int morlax_eval_returns(morlax_ctx* ctx, const float* r, const uint8_t* done, fl
  * morlax_hypervolume_workspace_bytes returns -1 for such sizes. */
 int64_t morlax_hypervolume_workspace_bytes(int32_t n, int32_t K);
 int morlax_pareto_hypervolume(const float* J, const float* ref, int32_t n, int32_t K, uint8_t* front,
-                              double* hv, void* ws, void* stream);
-
-/* Timing aid for benchmarks (not part of the method).  Between morlax_profile_begin() and
- * morlax_profile_end() every grouped-GEMM launch of policy_fwd / policy_bwd on this ctx is bracketed
- * by a pair of HIP events recorded on the launch stream.  morlax_profile_end() waits for the last
- * event (it synchronises with the stream) and returns, per GEMM kind k in
- * {0 forward first layer, 1 forward hidden layer, 2 dX hidden layer, 3 dW hidden layer, 4 dW first
- * layer, 5 fused forward of all hidden layers in one launch}: ms[k] total kernel time, launches[k],
- * flops[k] total algorithmic flops (2 * rows * cols * depth summed over layers and preferences; tile
- * padding not counted).  The three arrays are HOST pointers of length 6.  Profiling stops at
- * morlax_profile_end(). */
-int morlax_profile_begin(morlax_ctx* ctx);
-int morlax_profile_end(morlax_ctx* ctx, double* ms, int64_t* launches, double* flops);
+                              double* hv, void* ws, int64_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -72,23 +72,23 @@ def load():
     lib.morlax_workspace_bytes.argtypes = [vp, C.POINTER(Rows)]
     lib.morlax_workspace_bytes.restype = i64
     lib.morlax_env_pref_index.argtypes = [vp, vp, vp]
-    lib.morlax_hypernet_fwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp]
-    lib.morlax_hypernet_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
-    lib.morlax_hypernet_bwd_kept.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
-    lib.morlax_policy_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
-    lib.morlax_policy_bwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, vp]
+    lib.morlax_hypernet_fwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, i64, vp]
+    lib.morlax_hypernet_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.morlax_hypernet_bwd_kept.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.morlax_policy_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.morlax_policy_bwd.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(Rows), vp, vp, vp, vp, vp, vp, i64, vp]
     lib.morlax_vec_gae.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
     lib.morlax_vec_gae_trunc.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
     lib.morlax_adam_step.argtypes = [vp, C.c_int, vp, vp, vp, vp, f32, f32, f32, f32, i32, vp]
     lib.morlax_sample_preferences.argtypes = [vp, vp, i32, vp, vp]
-    lib.morlax_scalarize_normalized.argtypes = [vp, C.POINTER(Rows), vp, vp, vp, vp, vp]
+    lib.morlax_scalarize_normalized.argtypes = [vp, C.POINTER(Rows), vp, vp, vp, vp, i64, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
-                                         vp, vp, vp, vp, vp, vp]
+                                         vp, vp, vp, vp, vp, i64, vp]
     lib.morlax_eval_returns.argtypes = [vp, vp, vp, f32, vp, vp]
     lib.morlax_eval_returns.restype = C.c_int
     lib.morlax_hypervolume_workspace_bytes.argtypes = [i32, i32]
     lib.morlax_hypervolume_workspace_bytes.restype = i64
-    lib.morlax_pareto_hypervolume.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.morlax_pareto_hypervolume.argtypes = [vp, vp, i32, i32, vp, vp, vp, i64, vp]
     lib.morlax_pareto_hypervolume.restype = C.c_int
     lib.morlax_profile_begin.argtypes = [vp]
     lib.morlax_profile_begin.restype = C.c_int
@@ -108,7 +108,20 @@ def _ptr(t):
         return None
     if isinstance(t, int):
         return t
+    if isinstance(t, tuple):      # (address, bytes): a workspace given as a raw address
+        return t[0]
     return t.data_ptr()
+
+
+def _nbytes(t):
+    """Size of a workspace: a tensor's own, or -- for a raw address -- whatever the caller vouches for."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return 1 << 62
+    if isinstance(t, tuple):
+        return int(t[1])
+    return t.numel() * t.element_size()
 
 
 def _stream():
@@ -187,30 +200,30 @@ class Context:
 
     def hypernet_fwd(self, net, hparams, w, theta_mat, theta_vec, ws, stream=None):
         self._check(self.lib.morlax_hypernet_fwd(self.h, net, _ptr(hparams), _ptr(w), _ptr(theta_mat),
-                                                 _ptr(theta_vec), _ptr(ws),
+                                                 _ptr(theta_vec), _ptr(ws), _nbytes(ws),
                                                  stream if stream is not None else _stream()))
 
     def hypernet_bwd_kept(self, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws_fwd, stream=None):
         self._check(self.lib.morlax_hypernet_bwd_kept(self.h, net, _ptr(hparams), _ptr(w), _ptr(dtheta_mat),
-                                                      _ptr(dtheta_vec), _ptr(dhparams), _ptr(ws_fwd),
+                                                      _ptr(dtheta_vec), _ptr(dhparams), _ptr(ws_fwd), _nbytes(ws_fwd),
                                                       stream if stream is not None else _stream()))
 
     def hypernet_bwd(self, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, stream=None):
         self._check(self.lib.morlax_hypernet_bwd(self.h, net, _ptr(hparams), _ptr(w), _ptr(dtheta_mat),
-                                                 _ptr(dtheta_vec), _ptr(dhparams), _ptr(ws),
+                                                 _ptr(dtheta_vec), _ptr(dhparams), _ptr(ws), _nbytes(ws),
                                                  stream if stream is not None else _stream()))
 
     def policy_fwd(self, net, theta_mat, theta_vec, x, rows, out, eps=None, act=None, logp=None, saved=None,
                    ws=None, stream=None):
         self._check(self.lib.morlax_policy_fwd(self.h, net, _ptr(theta_mat), _ptr(theta_vec), _ptr(x), _rows(rows),
                                                _ptr(out), _ptr(eps), _ptr(act), _ptr(logp), _ptr(saved), _ptr(ws),
-                                               stream if stream is not None else _stream()))
+                                               _nbytes(ws), stream if stream is not None else _stream()))
 
     def policy_bwd(self, net, theta_mat, theta_vec, x, rows, saved, dout, dlogsig, dtheta_mat, dtheta_vec, ws,
                    stream=None):
         self._check(self.lib.morlax_policy_bwd(self.h, net, _ptr(theta_mat), _ptr(theta_vec), _ptr(x), _rows(rows),
                                                _ptr(saved), _ptr(dout), _ptr(dlogsig), _ptr(dtheta_mat),
-                                               _ptr(dtheta_vec), _ptr(ws),
+                                               _ptr(dtheta_vec), _ptr(ws), _nbytes(ws),
                                                stream if stream is not None else _stream()))
 
     def vec_gae(self, r, v, done, w, gamma, lam, adv_vec, vtarg, adv_s, stream=None):
@@ -238,14 +251,15 @@ class Context:
 
     def scalarize_normalized(self, rows, adv_vec, w, adv_out, ws, stream=None):
         self._check(self.lib.morlax_scalarize_normalized(self.h, _rows(rows), _ptr(adv_vec), _ptr(w), _ptr(adv_out),
-                                                         _ptr(ws), stream if stream is not None else _stream()))
+                                                         _ptr(ws), _nbytes(ws),
+                                                         stream if stream is not None else _stream()))
 
     def ppo_loss_grad(self, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv,
                       dmu, dlogsig, dv, stats, ws, stream=None):
         self._check(self.lib.morlax_ppo_loss_grad(self.h, _rows(rows), _ptr(mu), _ptr(logsig), int(logsig_stride),
                                                   _ptr(act), _ptr(logp_old), _ptr(adv_s), _ptr(v), _ptr(vtarg),
                                                   float(clip_eps), int(norm_adv), _ptr(dmu), _ptr(dlogsig),
-                                                  _ptr(dv), _ptr(stats), _ptr(ws),
+                                                  _ptr(dv), _ptr(stats), _ptr(ws), _nbytes(ws),
                                                   stream if stream is not None else _stream()))
 
 
@@ -258,6 +272,6 @@ def pareto_hypervolume(J, ref, n, K, front, hv, ws, stream=None):
     """morlax_pareto_hypervolume: needs no context; raises MorlaxError on failure."""
     lib = load()
     rc = lib.morlax_pareto_hypervolume(_ptr(J), _ptr(ref), int(n), int(K), _ptr(front), _ptr(hv), _ptr(ws),
-                                       stream if stream is not None else _stream())
+                                       _nbytes(ws), stream if stream is not None else _stream())
     if rc != OK:
         raise MorlaxError(rc, lib.morlax_last_error().decode())

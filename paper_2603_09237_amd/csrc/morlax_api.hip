@@ -8,6 +8,7 @@
 #include <new>
 
 #include "morlax_internal.h"
+#include "morlax_bench.h"
 
 static thread_local char g_err[512] = "";
 
@@ -98,6 +99,8 @@ extern "C" int morlax_create(const morlax_dims* dims, morlax_ctx** out) {
     if (d.P < 2) return fail(MORLAX_ERR_SHAPE, "morlax_create: need P > 1 trade-off vectors (got %d)", d.P);
     if (d.N % d.P != 0)
         return fail(MORLAX_ERR_SHAPE, "morlax_create: P = %d must divide N = %d", d.P, d.N);
+    // several launches carry the preference in gridDim.y or gridDim.z
+    if (d.P > 65535) return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: P must be <= 65535 (got %d)", d.P);
     if (d.K > MORLAX_MAX_OUT || d.act_dim > MORLAX_MAX_OUT)
         return fail(MORLAX_ERR_UNSUPPORTED, "morlax_create: K and act_dim must be <= %d", MORLAX_MAX_OUT);
     if (d.sigma_state != 0 && d.sigma_state != 1)
@@ -225,6 +228,15 @@ static int finish(const char* who) {
         if ((ptr) && !aligned16(ptr)) return fail(MORLAX_ERR_SHAPE, "%s: %s is not 16-byte aligned", who, #ptr); \
     } while (0)
 
+// caller-provided scratch: present, aligned and at least `need` bytes
+#define WS(ptr, bytes, need, who)                                                                        \
+    do {                                                                                                 \
+        REQ(ptr, who);                                                                                   \
+        if ((int64_t)(bytes) < (int64_t)(need))                                                          \
+            return fail(MORLAX_ERR_WORKSPACE, "%s: workspace of %lld bytes, %lld needed", who,           \
+                        (long long)(bytes), (long long)(need));                                          \
+    } while (0)
+
 extern "C" int morlax_env_pref_index(const morlax_ctx* ctx, int32_t* out, void* stream) {
     const char* who = "morlax_env_pref_index";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
@@ -234,46 +246,47 @@ extern "C" int morlax_env_pref_index(const morlax_ctx* ctx, int32_t* out, void* 
 }
 
 extern "C" int morlax_hypernet_fwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
-                                   void* theta_mat, float* theta_vec, void* ws, void* stream) {
+                                   void* theta_mat, float* theta_vec, void* ws, int64_t ws_bytes, void* stream) {
     const char* who = "morlax_hypernet_fwd";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
-    REQ(hparams, who); REQ(w, who); REQ(theta_mat, who); REQ(theta_vec, who); REQ(ws, who);
+    REQ(hparams, who); REQ(w, who); REQ(theta_mat, who); REQ(theta_vec, who);
+    WS(ws, ws_bytes, hyper_ws_bytes(ctx), who);
     launch_hypernet_fwd(ctx, net, hparams, w, theta_mat, theta_vec, ws, (hipStream_t)stream);
     return finish(who);
 }
 
 extern "C" int morlax_hypernet_bwd(morlax_ctx* ctx, int net, const float* hparams, const float* w,
                                    const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
-                                   void* ws, void* stream) {
+                                   void* ws, int64_t ws_bytes, void* stream) {
     const char* who = "morlax_hypernet_bwd";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
     REQ(hparams, who); REQ(w, who); REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(dhparams, who);
-    REQ(ws, who);
+    WS(ws, ws_bytes, hyper_ws_bytes(ctx), who);
     launch_hypernet_bwd(ctx, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws, false, (hipStream_t)stream);
     return finish(who);
 }
 
 extern "C" int morlax_hypernet_bwd_kept(morlax_ctx* ctx, int net, const float* hparams, const float* w,
                                         const float* dtheta_mat, const float* dtheta_vec, float* dhparams,
-                                        void* ws_fwd, void* stream) {
+                                        void* ws_fwd, int64_t ws_bytes, void* stream) {
     const char* who = "morlax_hypernet_bwd_kept";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
     REQ(hparams, who); REQ(w, who); REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(dhparams, who);
-    REQ(ws_fwd, who);
+    WS(ws_fwd, ws_bytes, hyper_ws_bytes(ctx), who);
     launch_hypernet_bwd(ctx, net, hparams, w, dtheta_mat, dtheta_vec, dhparams, ws_fwd, true, (hipStream_t)stream);
     return finish(who);
 }
 
 extern "C" int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
                                  const float* x, const morlax_rows* rows, float* out, const float* eps,
-                                 float* act, float* logp, void* saved, void* ws, void* stream) {
+                                 float* act, float* logp, void* saved, void* ws, int64_t ws_bytes, void* stream) {
     const char* who = "morlax_policy_fwd";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
-    REQ(theta_mat, who); REQ(theta_vec, who); REQ(x, who); REQ(out, who); REQ(ws, who);
+    REQ(theta_mat, who); REQ(theta_vec, who); REQ(x, who); REQ(out, who);
     OPT(eps, who); OPT(act, who); OPT(logp, who); OPT(saved, who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
     const bool any = eps || act || logp, all = eps && act && logp;
@@ -282,6 +295,7 @@ extern "C" int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat
     RowSel rs;
     int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
     if (rc != MORLAX_OK) return rc;
+    WS(ws, ws_bytes, mlp_ws_bytes(ctx, rs), who);
     launch_policy_fwd(ctx, net, theta_mat, theta_vec, x, rs, out, eps, act, logp, saved, ws, (hipStream_t)stream);
     return finish(who);
 }
@@ -289,12 +303,12 @@ extern "C" int morlax_policy_fwd(morlax_ctx* ctx, int net, const void* theta_mat
 extern "C" int morlax_policy_bwd(morlax_ctx* ctx, int net, const void* theta_mat, const float* theta_vec,
                                  const float* x, const morlax_rows* rows, const void* saved,
                                  const float* dout, const float* dlogsig, float* dtheta_mat,
-                                 float* dtheta_vec, void* ws, void* stream) {
+                                 float* dtheta_vec, void* ws, int64_t ws_bytes, void* stream) {
     const char* who = "morlax_policy_bwd";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (bad_net(net)) return fail(MORLAX_ERR_SHAPE, "%s: net must be 0 (actor) or 1 (critic)", who);
     REQ(theta_mat, who); REQ(theta_vec, who); REQ(x, who); REQ(saved, who); REQ(dout, who);
-    REQ(dtheta_mat, who); REQ(dtheta_vec, who); REQ(ws, who);
+    REQ(dtheta_mat, who); REQ(dtheta_vec, who);
     OPT(dlogsig, who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
     if (dlogsig && net != MORLAX_ACTOR) return fail(MORLAX_ERR_SHAPE, "%s: dlogsig is actor-only", who);
@@ -303,6 +317,7 @@ extern "C" int morlax_policy_bwd(morlax_ctx* ctx, int net, const void* theta_mat
     RowSel rs;
     int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
     if (rc != MORLAX_OK) return rc;
+    WS(ws, ws_bytes, mlp_ws_bytes(ctx, rs), who);
     launch_policy_bwd(ctx, net, theta_mat, theta_vec, x, rs, saved, dout, dlogsig, dtheta_mat, dtheta_vec,
                       ws, (hipStream_t)stream);
     return finish(who);
@@ -363,12 +378,13 @@ extern "C" int64_t morlax_hypervolume_workspace_bytes(int32_t n, int32_t K) {
 }
 
 extern "C" int morlax_pareto_hypervolume(const float* J, const float* ref, int32_t n, int32_t K, uint8_t* front,
-                                         double* hv, void* ws, void* stream) {
+                                         double* hv, void* ws, int64_t ws_bytes, void* stream) {
     const char* who = "morlax_pareto_hypervolume";
-    REQ(J, who); REQ(ref, who); REQ(front, who); REQ(hv, who); REQ(ws, who);
+    REQ(J, who); REQ(ref, who); REQ(front, who); REQ(hv, who);
     if (!hv_sizes_ok(n, K))
         return fail(MORLAX_ERR_SHAPE, "%s: needs 1 <= K <= 8, 1 <= n <= 1024 and n^(K-2) <= 2^32 (n = %d, K = %d)", who,
                     (int)n, (int)K);
+    WS(ws, ws_bytes, hv_ws_bytes(n, K), who);
     launch_pareto_hypervolume(J, ref, n, K, front, hv, ws, (hipStream_t)stream);
     return finish(who);
 }
@@ -391,14 +407,16 @@ extern "C" int morlax_adam_step(morlax_ctx* ctx, int net, float* hparams, const 
 }
 
 extern "C" int morlax_scalarize_normalized(morlax_ctx* ctx, const morlax_rows* rows, const float* adv_vec,
-                                           const float* w, float* adv_out, void* ws, void* stream) {
+                                           const float* w, float* adv_out, void* ws, int64_t ws_bytes,
+                                           void* stream) {
     const char* who = "morlax_scalarize_normalized";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
-    REQ(adv_vec, who); REQ(w, who); REQ(adv_out, who); REQ(ws, who);
+    REQ(adv_vec, who); REQ(w, who); REQ(adv_out, who);
     RowSel rs;
     int rc = resolve_rows(ctx, rows, ctx->d.T, rs, who);
     if (rc != MORLAX_OK) return rc;
+    WS(ws, ws_bytes, advnorm_ws_bytes(ctx, rs), who);
     launch_scalarize_normalized(ctx, rs, adv_vec, w, adv_out, ws, (hipStream_t)stream);
     return finish(who);
 }
@@ -407,12 +425,13 @@ extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, co
                                     const float* logsig, int32_t logsig_stride, const float* act,
                                     const float* logp_old, const float* adv_s, const float* v,
                                     const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
-                                    float* dlogsig, float* dv, float* stats, void* ws, void* stream) {
+                                    float* dlogsig, float* dv, float* stats, void* ws, int64_t ws_bytes,
+                                    void* stream) {
     const char* who = "morlax_ppo_loss_grad";
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
     REQ(mu, who); REQ(act, who); REQ(logp_old, who); REQ(adv_s, who); REQ(v, who);
-    REQ(vtarg, who); REQ(dmu, who); REQ(dv, who); REQ(stats, who); REQ(ws, who);
+    REQ(vtarg, who); REQ(dmu, who); REQ(dv, who); REQ(stats, who);
     if (ctx->d.sigma_state) {  // log sigma and its gradient travel inside mu / dmu (2 * act_dim columns)
         OPT(logsig, who); OPT(dlogsig, who);
     } else {
@@ -424,9 +443,10 @@ extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, co
             return fail(MORLAX_ERR_SHAPE, "%s: logsig_stride %d < act_dim %d", who, logsig_stride, ctx->d.act_dim);
     }
     if (!(clip_eps >= 0.f)) return fail(MORLAX_ERR_SHAPE, "%s: clip_eps must be >= 0", who);
-    RowSel rs;
-    int rc = resolve_rows(ctx, rows, ctx->d.T + 1, rs, who);
+    RowSel rs;  // the advantages, targets and actions exist for t < T only
+    int rc = resolve_rows(ctx, rows, ctx->d.T, rs, who);
     if (rc != MORLAX_OK) return rc;
+    WS(ws, ws_bytes, loss_ws_bytes(ctx, rs), who);
     launch_ppo_loss_grad(ctx, rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps,
                          norm_adv, dmu, dlogsig, dv, stats, ws, (hipStream_t)stream);
     return finish(who);

@@ -22,7 +22,8 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    hdr = open(os.path.join(ROOT, "include", "morlax.h")).read()
+    inc = os.path.join(ROOT, "include")
+    hdr = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = sorted(set(re.findall(r"\b(morlax_[a-z0-9_]+)\s*\(", hdr)))
     assert len(names) >= 15
@@ -55,6 +56,7 @@ def test_layout_queries_match_oracle_and_generator(lib):
     (dict(N=1 << 16, P=2, T=16383, width=2048), binding.ERR_UNSUPPORTED),       # one preference's activations too
     (dict(sigma_state=1, act_dim=9), binding.ERR_UNSUPPORTED),                  # 2A output columns must fit 16
     (dict(sigma_state=2), binding.ERR_UNSUPPORTED),
+    (dict(P=65536, N=65536), binding.ERR_UNSUPPORTED),                          # the preference rides in gridDim.y / .z
 ])
 def test_create_rejects_bad_dims(lib, over, code):
     d = configs.CONFIGS[1].dims_dict()
@@ -89,6 +91,10 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
     assert e.value.code == binding.ERR_NULL
     with pytest.raises(binding.MorlaxError) as e:
         ctx.hypernet_bwd_kept(3, good, good, good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    with pytest.raises(binding.MorlaxError) as e:      # actions, advantages and targets exist for t < T only
+        ctx.ppo_loss_grad((0, cfg.T + 1, 0, cfg.n_g), good, good, 4, good, good, good, good, good, 0.2, 1, good, good,
+                          good, good, good, stream=0)
     assert e.value.code == binding.ERR_SHAPE
     bad_rows = [(0, cfg.T + 2, 0, cfg.n_g), (0, 0, 0, 1), (0, 1, 0, cfg.n_g + 1), (-1, 1, 0, 1), (0, 1, cfg.n_g, 1)]
     for rows in bad_rows:
@@ -138,6 +144,39 @@ def test_ops_reject_bad_arguments_without_touching_the_gpu(lib):
     with pytest.raises(binding.MorlaxError) as e:      # the truncation mask is not optional here
         ctx.vec_gae_trunc(good, good, good, None, good, 0.99, 0.95, None, good, good, stream=0)
     assert e.value.code == binding.ERR_NULL
+    ctx.close()
+
+
+def test_too_small_workspace_is_refused_before_any_launch(lib):
+    """Every op that takes scratch checks its size on the host before anything is launched (the addresses here are
+    fake: only a refused call is safe to make)."""
+    cfg = configs.CONFIGS[1]
+    ctx = binding.Context.from_config(cfg)
+    good = 0x10000
+    rows = (0, cfg.T, 0, cfg.n_g)
+    calls = {
+        "hypernet_fwd": lambda ws: ctx.hypernet_fwd(0, good, good, good, good, ws, stream=0),
+        "hypernet_bwd": lambda ws: ctx.hypernet_bwd(0, good, good, good, good, good, ws, stream=0),
+        "hypernet_bwd_kept": lambda ws: ctx.hypernet_bwd_kept(1, good, good, good, good, good, ws, stream=0),
+        "policy_fwd": lambda ws: ctx.policy_fwd(0, good, good, good, rows, good, ws=ws, stream=0),
+        "policy_bwd": lambda ws: ctx.policy_bwd(1, good, good, good, rows, good, good, None, good, good, ws, stream=0),
+        "scalarize_normalized": lambda ws: ctx.scalarize_normalized(rows, good, good, good, ws, stream=0),
+        "ppo_loss_grad": lambda ws: ctx.ppo_loss_grad(rows, good, good, 4, good, good, good, good, good, 0.2, 1, good,
+                                                      good, good, good, ws, stream=0),
+        "pareto_hypervolume": lambda ws: binding.pareto_hypervolume(good, good, 8, 3, good, good, ws, stream=0),
+    }
+    for name, call in calls.items():
+        with pytest.raises(binding.MorlaxError) as e:
+            call((good, 0))
+        assert e.value.code == binding.ERR_WORKSPACE, name
+        with pytest.raises(binding.MorlaxError) as e:
+            call((good, 16))
+        assert e.value.code == binding.ERR_WORKSPACE, name
+        assert "needed" in str(e.value)
+    hv_need = binding.hypervolume_workspace_bytes(8, 3)
+    with pytest.raises(binding.MorlaxError) as e:
+        binding.pareto_hypervolume(good, good, 8, 3, good, good, (good, hv_need - 1), stream=0)
+    assert e.value.code == binding.ERR_WORKSPACE
     ctx.close()
 
 
