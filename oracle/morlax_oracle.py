@@ -413,7 +413,7 @@ def vec_gae(r, v, done, w, gamma, lam, trunc=None):
     Value target Vhat_t = A_t + V_t.  Scalar advantage A^s[t,n] = sum_k w[g(n),k] A_t[n,k].
     `done` acts as a select, so nothing after an episode end can reach the steps before it.
 
-    trunc [T,N] (optional; Sec. III-D separates failures from time limits in value estimation):
+    trunc [T,N] (optional; Sec. III-E separates failures from time limits in value estimation):
     1 where the episode end at step t was a time limit.  Reading taken: a truncated step still
     bootstraps from V_{t+1}, which the caller supplies as the value of the state the episode was cut
     at, but like every episode end it restarts the running sum: delta = r_t + gamma V_{t+1} - V_t,
