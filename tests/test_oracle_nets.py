@@ -538,3 +538,79 @@ def test_bf16_emulation_is_close_to_exact_and_changes_something():
         err = np.abs(a - b).max()
         # a tiny batch: one flipped clip decision moves the gradient by O(1/B)
         assert 0 < err < 0.2 * max(rms, np.abs(a).max())
+
+
+def _bf16_by_hand(v):
+    """Nearest bfloat16 of one float, ties to even, from the bit pattern (no call into the oracle)."""
+    import struct
+    u = struct.unpack("<I", struct.pack("<f", float(np.float32(v))))[0]
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return struct.unpack("<f", struct.pack("<I", u & 0xFFFFFFFF))[0]
+
+
+def _two_layer_by_hand(W1, b1, W2, b2, X, dout, act, skip=None):
+    """Forward and backward of one preference's network O -> W -> out (no tanh head) written out with plain
+    loops, every GEMM operand rounded to bfloat16 as it enters its product.  `skip` names ONE rounding point
+    to leave out: "x_fwd", "h_fwd", "dz2_dw", "h_dw", "dz2_dx", "dz1_dw", "x_dw"."""
+    rb = lambda v, point: float(v) if skip == point else _bf16_by_hand(v)
+    f = (lambda z: math.tanh(z)) if act == orc.ACT_TANH else (lambda z: z / (1.0 + math.exp(-z)))
+    if act == orc.ACT_TANH:
+        df = lambda z: 1.0 - math.tanh(z) ** 2
+    else:
+        df = lambda z: (1.0 / (1.0 + math.exp(-z))) * (1.0 + z * (1.0 - 1.0 / (1.0 + math.exp(-z))))
+    n, O = X.shape
+    W, out = W1.shape[0], W2.shape[0]
+    z1 = [[sum(rb(X[i, k], "x_fwd") * W1[o, k] for k in range(O)) + b1[o] for o in range(W)] for i in range(n)]
+    h1 = [[f(z1[i][o]) for o in range(W)] for i in range(n)]
+    z2 = [[sum(rb(h1[i][k], "h_fwd") * W2[o, k] for k in range(W)) + b2[o] for o in range(out)] for i in range(n)]
+    dz2 = [[float(dout[i, o]) for o in range(out)] for i in range(n)]
+    gW2 = [[sum(rb(dz2[i][o], "dz2_dw") * rb(h1[i][k], "h_dw") for i in range(n)) for k in range(W)] for o in range(out)]
+    gb2 = [sum(dz2[i][o] for i in range(n)) for o in range(out)]
+    dh1 = [[sum(rb(dz2[i][o], "dz2_dx") * W2[o, k] for o in range(out)) for k in range(W)] for i in range(n)]
+    dz1 = [[dh1[i][k] * df(z1[i][k]) for k in range(W)] for i in range(n)]
+    gW1 = [[sum(rb(dz1[i][o], "dz1_dw") * rb(X[i, k], "x_dw") for i in range(n)) for k in range(O)] for o in range(W)]
+    gb1 = [sum(dz1[i][o] for i in range(n)) for o in range(W)]
+    return np.array(z2), np.array(gW1), np.array(gb1), np.array(gW2), np.array(gb2)
+
+
+@pytest.mark.parametrize("act", [orc.ACT_TANH, orc.ACT_SILU])
+def test_bf16_rounding_points_against_a_hand_rounded_two_layer_network(act):
+    """Where emulate_bf16 rounds: every activation as it enters a product, both operands of every backward
+    product, nothing else (biases, bias gradients, activation derivatives stay exact).  The same small network is
+    written out with loops and a bit-level rounding; leaving out any single rounding point there must move the
+    result away from the oracle's, so an oracle that drops (or adds) one of them fails."""
+    d = SimpleNamespace(K=3, P=2, N=8, T=2, obs_dim=4, act_dim=2, n_hidden=1, width=5, act=act, rank=1,
+                        hyper_width=4, wdtype=1, mean_tanh=0)
+    rng = np.random.default_rng(7)
+    net = orc.CRITIC
+    shapes = orc.layer_shapes(d, net)
+    assert shapes == [(5, 4), (3, 5)]
+    tm = orc.round_bf16(rng.standard_normal((d.P, orc.theta_mat_len(d, net))))      # the weights arrive rounded
+    tv = rng.standard_normal((d.P, orc.theta_vec_len(d, net)))
+    x = rng.standard_normal((d.T, d.N, d.obs_dim)) * 1.7
+    dout = rng.standard_normal((d.T, d.N, d.K)) * 0.3
+    rows = (0, d.T, 1, 3)
+    out, _, _ = orc.policy_fwd(d, net, tm, tv, x, rows, emulate_bf16=True)
+    dm, dvec = orc.policy_bwd(d, net, tm, tv, x, rows, dout, None, emulate_bf16=True)
+    n_g = d.N // d.P
+    points = ("x_fwd", "h_fwd", "dz2_dw", "h_dw", "dz2_dx", "dz1_dw", "x_dw")
+    moved = {pt: 0.0 for pt in points}
+    for p in range(d.P):
+        W1, W2 = tm[p, :20].reshape(5, 4), tm[p, 20:].reshape(3, 5)
+        b1, b2 = tv[p, :5], tv[p, 5:8]
+        idx = p * n_g + 1 + np.arange(3)
+        X = x[:, idx, :].reshape(-1, d.obs_dim)
+        DO = dout[:, idx, :].reshape(-1, d.K)
+        got = (out[:, idx, :].reshape(-1, d.K), dm[p, :20].reshape(5, 4), dvec[p, :5], dm[p, 20:].reshape(3, 5),
+               dvec[p, 5:8])
+        ref = _two_layer_by_hand(W1, b1, W2, b2, X, DO, act)
+        for g, r in zip(got, ref):
+            assert np.allclose(g, r, rtol=0, atol=1e-13), np.abs(g - r).max()
+        for pt in points:
+            alt = _two_layer_by_hand(W1, b1, W2, b2, X, DO, act, skip=pt)
+            moved[pt] = max(moved[pt], max(float(np.abs(g - r).max()) for g, r in zip(got, alt)))
+    for pt, m in moved.items():
+        assert m > 1e-5, (pt, m)         # bf16 keeps 8 bits: a dropped rounding shows at the 1e-3 level
+    # and the rounding itself, against the bit-level one used above
+    v = rng.standard_normal(200) * np.exp(rng.standard_normal(200) * 3)
+    assert np.array_equal(orc.round_bf16(v), np.array([_bf16_by_hand(t) for t in v]))
