@@ -56,3 +56,24 @@ def rel_rms_err(got, ref):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     return float(np.sqrt(np.mean((got - ref) ** 2)) / max(np.sqrt(np.mean(ref ** 2)), 1e-300))
+
+
+def bf16_chain_report(got, ref, rel=REL_BF16):
+    """(fraction of elements outside rel * max(|ref|, rms), worst error in units of that band, relative RMS error)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref ** 2))) if ref.size else 0.0
+    band = rel * np.maximum(np.abs(ref), rms) + 1e-30
+    ratio = np.abs(got - ref) / band
+    return float(np.mean(ratio > 1.0)), float(ratio.max()), rel_rms_err(got, ref)
+
+
+def assert_close_bf16_chain(got, ref, what, rel=REL_BF16, outliers=1e-3, wide=3.0, rms=1e-2):
+    """For results at the end of a chain of bf16 products (hypernet gradients behind four re-rounded layers and the
+    factor products): the relative RMS error stays below `rms`, all but a fraction `outliers` of the elements sit
+    inside the band of a single bf16 GEMM output, rel * max(|ref|, RMS(ref)), and none leaves `wide` times that
+    band.  A wrong result (a dropped term, a transposed operand, a missing factor) misses all three by far."""
+    frac, worst, r = bf16_chain_report(got, ref, rel)
+    assert r < rms, f"{what}: relative RMS error {r:.4g} >= {rms}"
+    assert frac <= outliers, f"{what}: {frac:.2e} of the elements outside {rel} * max(|ref|, rms)"
+    assert worst <= wide, f"{what}: worst element {worst:.2f} bands away"

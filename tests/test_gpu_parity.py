@@ -14,7 +14,7 @@ from oracle import morlax_oracle as orc
 from paper_2603_09237_amd import configs, inputs
 from paper_2603_09237_amd.configs import CONFIGS, scaled
 
-from gpu_util import assert_close32, assert_close_bf16, dev, rel_rms_err, to_np
+from gpu_util import assert_close32, assert_close_bf16, assert_close_bf16_chain, bf16_chain_report, dev, rel_rms_err, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -253,7 +253,7 @@ def loss_inputs(cfg, seed=40):
 
 
 @pytest.mark.parametrize("cfg,mb,norm", [(CONFIGS[1], 0, 1), (RAGGED, 0, 1), (RAGGED, 1, 0), (CONFIGS[2], 0, 1),
-                                         (CONFIGS[3], 0, 1), (CONFIGS[5], 2, 1)],
+                                         (CONFIGS[3], 0, 1), (CONFIGS[4], 0, 1), (CONFIGS[5], 2, 1)],
                          ids=lambda x: getattr(x, "name", str(x)))
 def test_ppo_loss_grad_matches_oracle(cfg, mb, norm, torch, binding):
     say(f"ppo_loss_grad {cfg.name} mb={mb} norm={norm}")
@@ -500,8 +500,7 @@ BWD_CASES = [(CONFIGS[1], None), (RAGGED, None), (RAGGED, (1, 5, 2, 19)), (RAGGE
             [(c, None) for c in SIGMA_CASES] + \
             [(RAGGED_FUSED, (3, 1, 5, 1)), (scaled(RAGGED_FUSED_WIDE, name="ragged-fused-bf16-obs512-3layers", n_hidden=3), None)] + \
             RANDOM_FUSED + [(LIMITS_BF16, None)]
-# (the backward of the eight-layer network is left out: its bf16 rounding noise, re-rounded at every layer on both
-# sides, passes the 2 % band of single elements without either side being wrong)
+# (the eight-layer network has a test of its own below, test_policy_bwd_eight_hidden_layers_bf16)
 
 
 @pytest.mark.parametrize("cfg,rows", BWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -552,6 +551,50 @@ def test_policy_bwd_matches_oracle(cfg, rows, torch, binding):
             o2, _ = orc.policy_bwd(cfg, net, tm, tv.astype(np.float32), x, rows, dout, dls, emulate_bf16=False)
             e = rel_rms_err(g_dtm, o2)
             assert e < 2e-2, e
+
+
+def test_policy_bwd_eight_hidden_layers_bf16(torch, binding):
+    """The deepest network the library takes (eight hidden layers), bf16.  Both sides re-round every activation and
+    every dZ at every layer, so single elements of the first layers' gradients differ by accumulated rounding flips
+    by more than the 2 % band of one rounding; what is bounded instead is each layer's error in the RMS sense,
+    against the emulating oracle and against the exact one, with the element-wise band widened by sqrt(depth)."""
+    cfg = RAGGED_FUSED_WIDE
+    assert cfg.n_hidden == 8
+    ctx = binding.Context.from_config(cfg)
+    x = inputs.make_trajectory(cfg)["obs"][:cfg.T]
+    rows = (0, cfg.T, 0, cfg.n_g)
+    for net in (ACTOR, CRITIC):
+        say(f"policy_bwd eight hidden layers {cfg.name} net={net}")
+        tm, tv = theta_for(cfg, net, True)
+        odim = orc.head_dim(cfg, net)
+        rng = np.random.default_rng(80 + net)
+        dout = (rng.standard_normal((cfg.T, cfg.N, odim), dtype=np.float32) / np.float32(np.sqrt(rows[1] * rows[3])))
+        dls = rng.standard_normal((cfg.P, cfg.act_dim), dtype=np.float32) if net == ACTOR else None
+        d_tm, d_tv, d_x = dev(tm, torch.bfloat16), dev(tv.astype(np.float32)), dev(x)
+        ws = torch.empty(ctx.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
+        saved = torch.empty(ctx.saved_bytes(net, rows), dtype=torch.uint8, device="cuda")
+        out = torch.zeros(cfg.T, cfg.N, odim, device="cuda")
+        ctx.policy_fwd(net, d_tm, d_tv, d_x, rows, out, saved=saved, ws=ws)
+        dtm = torch.full((cfg.P, ctx.theta_mat_len(net)), 5.0, device="cuda")
+        dtv = torch.full((cfg.P, ctx.theta_vec_len(net)), 5.0, device="cuda")
+        ctx.policy_bwd(net, d_tm, d_tv, d_x, rows, saved, dev(dout), dev(dls) if dls is not None else None, dtm, dtv, ws)
+        torch.cuda.synchronize()
+        o_dtm, o_dtv = orc.policy_bwd(cfg, net, tm, tv.astype(np.float32), x, rows, dout, dls, emulate_bf16=True)
+        e_dtm, e_dtv = orc.policy_bwd(cfg, net, tm, tv.astype(np.float32), x, rows, dout, dls, emulate_bf16=False)
+        g_dtm, g_dtv = to_np(dtm), to_np(dtv)
+        moff = voff = 0
+        depth = cfg.n_hidden + 1
+        for l, (do, di) in enumerate(orc.layer_shapes(cfg, net)):
+            sl, sv = slice(moff, moff + do * di), slice(voff, voff + do)
+            r_emu, r_exact = rel_rms_err(g_dtm[:, sl], o_dtm[:, sl]), rel_rms_err(g_dtm[:, sl], e_dtm[:, sl])
+            say(f"  layer {l}: rel. RMS error {r_emu:.4f} (emulating oracle) {r_exact:.4f} (exact oracle)")
+            assert r_emu < 2e-2 and r_exact < 2e-2, (l, r_emu, r_exact)
+            assert rel_rms_err(g_dtv[:, sv], o_dtv[:, sv]) < 2e-2
+            wide = 2e-2 * float(np.sqrt(depth - l))       # roundings between this layer's dZ and the output
+            assert_close_bf16(g_dtm[:, sl], o_dtm[:, sl], f"dW_{l} net={net}", rel=wide)
+            assert_close_bf16(g_dtv[:, sv], o_dtv[:, sv], f"db_{l} net={net}", rel=wide)
+            moff += do * di
+            voff += do
 
 
 # ------------------------------------------------------------------------------------------------
@@ -751,14 +794,17 @@ def test_update_step_fp32_matches_oracle(cfg, torch, binding):
     assert_close32(to_np(st.act), res["act"], "act")
     assert_close32(to_np(st.logp_old), res["logp_old"], "logp_old")
     assert_close32(to_np(st.v_roll), res["v_roll"], "v_roll")
-    assert_close32(to_np(st.adv_vec), res["adv_vec"], "adv_vec", rel=2e-4, abs_=2e-5)
-    assert_close32(to_np(st.vtarg), res["vtarg"], "vtarg", rel=2e-4, abs_=2e-5)
-    assert_close32(to_np(st.adv_s), res["adv_s"], "adv_s", rel=2e-4, abs_=2e-5)
+    assert_close32(to_np(st.adv_vec), res["adv_vec"], "adv_vec")
+    assert_close32(to_np(st.vtarg), res["vtarg"], "vtarg")
+    assert_close32(to_np(st.adv_s), res["adv_s"], "adv_s")
     assert len(grads) == cfg.minibatches * cfg.epochs
     for i, (ga, gc, stt) in enumerate(grads):
         ref = res["grads"][i]
-        assert_close32(stt[[0, 1, 3, 4, 5, 6]], ref["stats"][[0, 1, 3, 4, 5, 6]], "stats", rel=2e-4, abs_=2e-5)
-        # hypernet gradients: sums over the whole minibatch; tolerance relative to each block's scale
+        assert_close32(stt[[0, 1, 3, 4, 5, 6]], ref["stats"][[0, 1, 3, 4, 5, 6]], "stats")
+        assert abs(stt[2] - ref["stats"][2]) <= 2.0 / stt[7]
+        assert 0.02 < ref["stats"][2] < 0.6          # the clipped branch is exercised end to end
+        # hypernet gradients, element by element at the fp32 tolerance; the absolute part is in units of the
+        # block's largest entry (the gradients carry 1/B and differ in scale from block to block)
         for key, g, net in (("dhp_actor", ga, ACTOR), ("dhp_critic", gc, CRITIC)):
             lay = orc.hparam_layout(cfg, net)
             for name, (o, s) in lay.items():
@@ -767,7 +813,7 @@ def test_update_step_fp32_matches_oracle(cfg, torch, binding):
                 n = int(np.prod(s))
                 r = ref[key][o:o + n]
                 scale = max(float(np.abs(r).max()), 1e-12)
-                assert_close32(g[o:o + n] / scale, r / scale, f"{key}[{name}] mb {i}", rel=1e-3, abs_=1e-4)
+                assert_close32(g[o:o + n] / scale, r / scale, f"{key}[{name}] mb {i}")
 
 
 @pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), RAGGED_PERS, CONFIGS[3],
@@ -800,20 +846,48 @@ def test_update_step_bf16_matches_oracle(cfg, torch, binding):
                 assert_close_bf16(g[o:o + n], ref[key][o:o + n], f"{key}[{name}] mb {i}")
 
 
+def _blocks_close(close, got, ref, cfg, net, what, **kw):
+    for name, (o, shp) in orc.hparam_layout(cfg, net).items():
+        if name == "_total":
+            continue
+        n = int(np.prod(shp))
+        close(got[o:o + n], ref[o:o + n], f"{what}[{name}]", **kw)
+
+
 @pytest.mark.parametrize("cfg", [CONFIGS[4], CONFIGS[5]], ids=lambda c: c.name)
-def test_update_step_full_size_sampled(cfg, torch, binding):
-    """The bench configuration end to end.  The oracle follows the rollout and GAE for a sample of
-    preferences (their environments' outputs are complete), and size-independent properties are checked
-    on everything: finite outputs, done masking, identical gradients from identical minibatch passes."""
+def test_update_step_full_size_chain(cfg, torch, binding):
+    """The bench configuration end to end, in the launch shapes the bench times.  The oracle cannot follow all
+    P preferences of the 4 x 512 networks in seconds, so the chain is checked link by link, every link against the
+    oracle on the GPU's own inputs to that link: rollout and GAE on a sample of preferences (preferences do not
+    interact there, so their rows are complete outputs); then, in the first minibatch, the update forward on the
+    same sample, the loss on every cell, the grouped backward on the sample (fed the GPU's dmu / dv), and the
+    hypernet backward on the GPU's whole dtheta.  Size-independent properties are checked on all minibatches."""
+    from paper_2603_09237_amd.step import UpdateStep
     say(f"update_step full size {cfg.name}")
-    st, d, grads = run_step(cfg, torch, keep_adv_vec=False)
+    st = UpdateStep(cfg)
+    d = inputs.make_all(cfg)
+    st.load_inputs(d)
+    grads, first = [], {}
+
+    def grab(e, b):
+        torch.cuda.synchronize()
+        grads.append((to_np(st.dhp[ACTOR]).copy(), to_np(st.dhp[CRITIC]).copy(), to_np(st.stats).copy()))
+        if e == 0 and b == 0:
+            first.update(mu=to_np(st.mu).copy(), v=to_np(st.v).copy(), dmu=to_np(st.dmu).copy(), dv=to_np(st.dv).copy(),
+                         dls=to_np(st.dlogsig).copy(), tv_a=to_np(st.theta_vec[ACTOR]).copy(),
+                         dtm={n: st.dtheta_mat[n].clone() for n in (ACTOR, CRITIC)},
+                         dtv={n: to_np(st.dtheta_vec[n]).copy() for n in (ACTOR, CRITIC)})
+
+    st.run(on_minibatch=grab)
+    torch.cuda.synchronize()
     prefs = sorted({0, cfg.P // 2 + 1, cfg.P - 1})
     emask = pref_env_mask(cfg, prefs)
-    hp_a, hp_c, w = d["hparams_actor_old"], d["hparams_critic_old"], d["w"]
-    tm_a, tv_a = orc.hypernet_fwd(cfg, ACTOR, hp_a, w)
-    tm_c, tv_c = orc.hypernet_fwd(cfg, CRITIC, hp_c, w)
-    tm_a, tm_c = orc.round_bf16(tm_a), orc.round_bf16(tm_c)
+    w = d["w"]
     T = cfg.T
+    # ---- rollout and GAE on the sample
+    tm_a, tv_a = orc.hypernet_fwd(cfg, ACTOR, d["hparams_actor_old"], w)
+    tm_c, tv_c = orc.hypernet_fwd(cfg, CRITIC, d["hparams_critic_old"], w)
+    tm_a, tm_c = orc.round_bf16(tm_a), orc.round_bf16(tm_c)
     mu, act, logp = orc.policy_fwd(cfg, ACTOR, tm_a, tv_a, d["obs"][:T], (0, T, 0, cfg.n_g), eps=d["eps"],
                                    emulate_bf16=True, prefs=prefs)
     v, _, _ = orc.policy_fwd(cfg, CRITIC, tm_c, tv_c, d["obs"], (0, T + 1, 0, cfg.n_g), emulate_bf16=True, prefs=prefs)
@@ -821,20 +895,106 @@ def test_update_step_full_size_sampled(cfg, torch, binding):
     m2 = np.broadcast_to(emask[None, :], (T, cfg.N))
     m3a = np.broadcast_to(emask[None, :, None], mu.shape)
     m3k = np.broadcast_to(emask[None, :, None], vtarg.shape)
+    g_act, g_logp, g_vtarg, g_adv = to_np(st.act), to_np(st.logp_old), to_np(st.vtarg), to_np(st.adv_s)
     assert_close_bf16(to_np(st.mu_old), mu, "mu_old", mask=m3a)
-    assert_close_bf16(to_np(st.act), act, "act", mask=m3a)
-    assert_close32(to_np(st.logp_old), logp, "logp_old", mask=m2)
+    assert_close_bf16(g_act, act, "act", mask=m3a)
+    assert_close32(g_logp, logp, "logp_old", mask=m2)
     assert_close_bf16(to_np(st.v_roll)[:T], v[:T], "v_roll", mask=m3k)
-    assert_close_bf16(to_np(st.vtarg), vtarg, "vtarg", mask=m3k)
-    assert_close_bf16(to_np(st.adv_s), adv_s, "adv_s", mask=m2)
+    assert_close_bf16(g_vtarg, vtarg, "vtarg", mask=m3k)
+    assert_close_bf16(g_adv, adv_s, "adv_s", mask=m2)
+    # the scan itself on every environment, from the GPU's own critic values
+    _, vt_all, as_all = orc.vec_gae(d["rewards"], to_np(st.v_roll), d["dones"], w, cfg.gamma, cfg.lam)
+    for k in range(cfg.K):
+        sk = max(1.0, float(np.sqrt(np.mean((vt_all[..., k] - to_np(st.v_roll)[:T, :, k]) ** 2))))
+        assert_close32(g_vtarg[..., k], vt_all[..., k], f"vtarg[{k}] from the device's values", abs_=1e-5 * sk)
+    assert_close32(g_adv, as_all, "adv_s from the device's values", abs_=1e-5 * max(1.0, float(np.sqrt(np.mean(as_all ** 2)))))
+    # ---- first minibatch, link by link
+    rows = st.mb_rows[0]
+    rmask = orc.row_mask(cfg, rows, T)
+    tm_a, tv_a = orc.hypernet_fwd(cfg, ACTOR, d["hparams_actor"], w)
+    tm_c, tv_c = orc.hypernet_fwd(cfg, CRITIC, d["hparams_critic"], w)
+    tm_a, tm_c = orc.round_bf16(tm_a), orc.round_bf16(tm_c)
+    assert_close32(first["tv_a"], tv_a, "theta_vec actor (update-time parameters)")
+    o_mu, _, _ = orc.policy_fwd(cfg, ACTOR, tm_a, tv_a, d["obs"][:T], rows, emulate_bf16=True, prefs=prefs)
+    o_v, _, _ = orc.policy_fwd(cfg, CRITIC, tm_c, tv_c, d["obs"][:T], rows, emulate_bf16=True, prefs=prefs)
+    sm = rmask & m2
+    assert_close_bf16(first["mu"], o_mu, "mu (update forward)", mask=sm[..., None] & np.ones_like(o_mu, bool))
+    assert_close_bf16(first["v"], o_v, "v (update forward)", mask=sm[..., None] & np.ones_like(o_v, bool))
+    # the loss on every cell of the minibatch, from the device's own inputs
+    logsig = first["tv_a"][:, -cfg.act_dim:]
+    o_dmu, o_dls, o_dv, o_st = orc.ppo_loss_grad(cfg, rows, first["mu"], logsig, g_act, g_logp, g_adv, first["v"], g_vtarg,
+                                                 cfg.clip_eps, True)
+    B = float(rmask.sum())
+    gi = orc.env_pref_index(cfg.N, cfg.P)
+    lp = orc.gaussian_logp(g_act.astype(np.float64), first["mu"].astype(np.float64), logsig[gi][None].astype(np.float64))
+    rho = np.exp(lp - g_logp)
+    kink = (np.abs(rho - (1 + cfg.clip_eps)) < 1e-5) | (np.abs(rho - (1 - cfg.clip_eps)) < 1e-5)
+    assert_close32(first["dmu"] * B, o_dmu * B, "dmu*B", mask=(rmask & ~kink)[..., None] & np.ones_like(o_dmu, bool))
+    assert_close32(first["dv"] * B, o_dv * B, "dv*B", mask=rmask[..., None] & np.ones_like(o_dv, bool))
+    stt = grads[0][2]
+    assert_close32(stt[[0, 1, 3, 4, 5, 6]], o_st[[0, 1, 3, 4, 5, 6]], "stats", rel=1e-4, abs_=1e-5)
+    assert abs(stt[2] - o_st[2]) <= (2.0 + kink[rmask].sum()) / B and stt[7] == B
+    assert 0.02 < o_st[2] < 0.6                      # the clipped branch is exercised end to end
+    if not kink[rmask].any():
+        assert_close32(first["dls"], o_dls, "dlogsig", rel=1e-4, abs_=1e-5)
+    # the grouped backward on the sample, fed the device's loss gradients
+    for net, tm, tv, dout, dls in ((ACTOR, tm_a, tv_a, first["dmu"], first["dls"]), (CRITIC, tm_c, tv_c, first["dv"], None)):
+        o_dtm, o_dtv = orc.policy_bwd(cfg, net, tm, tv, d["obs"][:T], rows, dout, dls, emulate_bf16=True, prefs=prefs)
+        g_dtm = to_np(first["dtm"][net][prefs])
+        g_dtv = first["dtv"][net]
+        moff = voff = 0
+        for l, (do, di) in enumerate(orc.layer_shapes(cfg, net)):
+            assert_close_bf16(g_dtm[:, moff:moff + do * di], o_dtm[prefs, moff:moff + do * di], f"dW_{l} net={net}")
+            assert_close_bf16(g_dtv[prefs, voff:voff + do], o_dtv[prefs, voff:voff + do], f"db_{l} net={net}")
+            moff += do * di
+            voff += do
+        if net == ACTOR:
+            assert np.array_equal(g_dtv[:, voff:], first["dls"])
+    # the hypernet backward on the device's whole dtheta (fp32 arithmetic on both sides)
+    for net, key in ((ACTOR, "hparams_actor"), (CRITIC, "hparams_critic")):
+        ref = orc.hypernet_bwd(cfg, net, d[key], w, to_np(first["dtm"][net]), first["dtv"][net])
+        _blocks_close(assert_close32, grads[0][net], ref, cfg, net, f"dhparams net={net}")
+    first.clear()
+    # ---- every minibatch
     assert len(grads) == cfg.minibatches * cfg.epochs
     for ga, gc, stt in grads:
         assert np.isfinite(ga).all() and np.isfinite(gc).all() and np.isfinite(stt).all()
         assert stt[7] == T * cfg.N // cfg.minibatches
-        assert 0.0 < stt[2] < 0.6 and abs(stt[4]) < 10 * stt[5]
+        assert 0.02 < stt[2] < 0.6 and abs(stt[4]) < 10 * stt[5]
     # no optimiser step is taken, so epoch 2 repeats epoch 1 bit for bit (fixed-order reductions)
     MB = cfg.minibatches
     for b in range(MB):
         for e in range(1, cfg.epochs):
             assert np.array_equal(grads[b][0], grads[e * MB + b][0])
             assert np.array_equal(grads[b][1], grads[e * MB + b][1])
+
+
+@pytest.mark.parametrize("cfg", [scaled(CONFIGS[4], name="cfg4-per-preference-shapes-P3", P=3, N=3 * CONFIGS[4].n_g),
+                                 scaled(CONFIGS[5], name="cfg5-per-preference-shapes-P3", P=3, N=3 * CONFIGS[5].n_g)],
+                         ids=lambda c: c.name)
+def test_update_step_wide_networks_reduced_preferences(cfg, torch, binding):
+    """The two widest workloads with their full per-preference shapes (all T steps, all n_g environments of a
+    preference, every minibatch and epoch, the 4 x 512 bf16 networks) and three preferences instead of 64 / 128:
+    the whole chain -- rollout, GAE, and per minibatch forward, loss, grouped backward, hypernet backward -- against
+    the oracle as one chain, every rollout tensor and every block of both hypernet gradients."""
+    say(f"update_step wide networks, reduced P {cfg.name}")
+    st, d, grads = run_step(cfg, torch)
+    res = orc.update_step(cfg, d["w"], d["hparams_actor_old"], d["hparams_critic_old"], d["hparams_actor"],
+                          d["hparams_critic"], d["obs"], d["rewards"], d["dones"], d["eps"], cfg.gamma, cfg.lam,
+                          cfg.clip_eps, cfg.minibatches, cfg.epochs, emulate_bf16=True, keep=True)
+    assert_close_bf16(to_np(st.mu_old), res["mu_old"], "mu_old")
+    assert_close_bf16(to_np(st.act), res["act"], "act")
+    assert_close32(to_np(st.logp_old), res["logp_old"], "logp_old")
+    assert_close_bf16(to_np(st.v_roll), res["v_roll"], "v_roll")
+    assert_close_bf16(to_np(st.vtarg), res["vtarg"], "vtarg")
+    assert_close_bf16(to_np(st.adv_s), res["adv_s"], "adv_s")
+    assert len(grads) == cfg.minibatches * cfg.epochs
+    for i, (ga, gc, stt) in enumerate(grads):
+        ref = res["grads"][i]
+        assert_close_bf16(stt[:2], ref["stats"][:2], "losses")
+        assert 0.02 < ref["stats"][2] < 0.6 and abs(stt[2] - ref["stats"][2]) < 5e-3
+        for net, g, key in ((ACTOR, ga, "dhp_actor"), (CRITIC, gc, "dhp_critic")):
+            _blocks_close(assert_close_bf16_chain, g, ref[key], cfg, net, f"{key} mb {i}")
+            rep = [bf16_chain_report(g[o:o + int(np.prod(shp))], ref[key][o:o + int(np.prod(shp))]) + (name,)
+                   for name, (o, shp) in orc.hparam_layout(cfg, net).items() if name != "_total"]
+            say(f"  mb {i} {key}: worst block by outliers {max(rep, key=lambda r: r[0])}, by RMS {max(rep, key=lambda r: r[2])}")
