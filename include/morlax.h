@@ -217,6 +217,22 @@ int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* 
                          const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
                          float* dlogsig, float* dv, float* stats, void* ws, int64_t ws_bytes, void* stream);
 
+/* morlax_ppo_loss_grad for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments (without ws),
+ * same kernels, same results bit for bit; the partial sums live in a static device array inside the
+ * library, MORLAX_STATIC_SCRATCH_BYTES bytes on every GPU the library runs on, held until the process
+ * ends.  The call allocates and frees nothing.  A selection whose partial sums do not fit -- more than
+ * about 8000 blocks of 256 selected cells over all preferences -- is refused with MORLAX_ERR_WORKSPACE before
+ * anything is launched.  All calls on one GPU share that GPU's array: calls that may overlap there (two
+ * streams, two threads) race; order them.  Nothing in the array needs to survive or be cleared between
+ * calls. */
+#define MORLAX_STATIC_SCRATCH_BYTES (2 * 1024 * 1024)
+int morlax_ppo_loss_grad_static(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
+                                const float* logsig, int32_t logsig_stride, const float* act,
+                                const float* logp_old, const float* adv_s, const float* v,
+                                const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
+                                float* dlogsig, float* dv, float* stats, void* stream);
+
 /* Evaluation side (Fig. 2a: a trade-off is picked, its policy rolled out, and the returns judged).
  * morlax_eval_returns: the return vector of every trade-off from a finished roll-out (Sec. II-A:
  * J = expected discounted return from the initial state): J[p, k] = mean over the n_g environments of

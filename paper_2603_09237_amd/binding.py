@@ -38,7 +38,8 @@ EXPORTS = ("morlax_create", "morlax_destroy", "morlax_last_error", "morlax_hpara
            "morlax_env_pref_index", "morlax_hypernet_fwd", "morlax_hypernet_bwd", "morlax_hypernet_bwd_kept",
            "morlax_policy_fwd",
            "morlax_policy_bwd", "morlax_vec_gae", "morlax_vec_gae_trunc", "morlax_adam_step",
-           "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad", "morlax_eval_returns",
+           "morlax_sample_preferences", "morlax_scalarize_normalized", "morlax_ppo_loss_grad",
+           "morlax_ppo_loss_grad_static", "morlax_eval_returns",
            "morlax_hypervolume_workspace_bytes", "morlax_pareto_hypervolume", "morlax_profile_begin",
            "morlax_profile_end")
 
@@ -84,6 +85,9 @@ def load():
     lib.morlax_scalarize_normalized.argtypes = [vp, C.POINTER(Rows), vp, vp, vp, vp, i64, vp]
     lib.morlax_ppo_loss_grad.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
                                          vp, vp, vp, vp, vp, i64, vp]
+    lib.morlax_ppo_loss_grad_static.argtypes = [vp, C.POINTER(Rows), vp, vp, i32, vp, vp, vp, vp, vp, f32, i32,
+                                                vp, vp, vp, vp, vp]
+    lib.morlax_ppo_loss_grad_static.restype = C.c_int
     lib.morlax_eval_returns.argtypes = [vp, vp, vp, f32, vp, vp]
     lib.morlax_eval_returns.restype = C.c_int
     lib.morlax_hypervolume_workspace_bytes.argtypes = [i32, i32]
@@ -254,6 +258,15 @@ class Context:
                                                          _ptr(ws), _nbytes(ws),
                                                          stream if stream is not None else _stream()))
 
+    def ppo_loss_grad_static(self, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv,
+                             dmu, dlogsig, dv, stats, stream=None):
+        """The loss call on the library's static scratch array (no workspace argument, nothing allocated)."""
+        self._check(self.lib.morlax_ppo_loss_grad_static(self.h, _rows(rows), _ptr(mu), _ptr(logsig), int(logsig_stride),
+                                                         _ptr(act), _ptr(logp_old), _ptr(adv_s), _ptr(v), _ptr(vtarg),
+                                                         float(clip_eps), int(norm_adv), _ptr(dmu), _ptr(dlogsig),
+                                                         _ptr(dv), _ptr(stats),
+                                                         stream if stream is not None else _stream()))
+
     def ppo_loss_grad(self, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, norm_adv,
                       dmu, dlogsig, dv, stats, ws, stream=None):
         self._check(self.lib.morlax_ppo_loss_grad(self.h, _rows(rows), _ptr(mu), _ptr(logsig), int(logsig_stride),
@@ -261,6 +274,9 @@ class Context:
                                                   float(clip_eps), int(norm_adv), _ptr(dmu), _ptr(dlogsig),
                                                   _ptr(dv), _ptr(stats), _ptr(ws), _nbytes(ws),
                                                   stream if stream is not None else _stream()))
+
+
+STATIC_SCRATCH_BYTES = 2 * 1024 * 1024
 
 
 def hypervolume_workspace_bytes(n, K):

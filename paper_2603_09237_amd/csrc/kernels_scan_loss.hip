@@ -383,6 +383,29 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
     k_loss_final<<<P + 1, 256, 0, s>>>(L.stat_part, L.dls_part, L.adv_stat, nbm, P, A, cnt, dlogsig, stats);
 }
 
+// The same call on scratch that lives in the library's own image, for callers that cannot allocate: a
+// file-scope device array, one copy per GPU at an address of its own, which host code learns once per
+// device from hipGetSymbolAddress (the array's name itself is not a device address on the host side).
+static __device__ __align__(256) unsigned char scratch[MORLAX_STATIC_SCRATCH_BYTES];
+
+#include <mutex>
+#define MORLAX_MAX_DEVICES 64
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[MORLAX_MAX_DEVICES];  // per device, filled on the first call with that device current
+
+int loss_static_scratch(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MORLAX_MAX_DEVICES) return -1;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return -1;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return 0;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Per-objective advantage normalisation before scalarisation (the other reading of "normalised across
 // the batch" in the update phase, Sec. III-C): every objective is standardised over the selected cells

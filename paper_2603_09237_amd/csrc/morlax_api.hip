@@ -421,13 +421,11 @@ extern "C" int morlax_scalarize_normalized(morlax_ctx* ctx, const morlax_rows* r
     return finish(who);
 }
 
-extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
-                                    const float* logsig, int32_t logsig_stride, const float* act,
-                                    const float* logp_old, const float* adv_s, const float* v,
-                                    const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
-                                    float* dlogsig, float* dv, float* stats, void* ws, int64_t ws_bytes,
-                                    void* stream) {
-    const char* who = "morlax_ppo_loss_grad";
+// argument checks shared by the two forms of the loss call
+static int check_loss_args(morlax_ctx* ctx, const morlax_rows* rows, const float* mu, const float* logsig,
+                           int32_t logsig_stride, const float* act, const float* logp_old, const float* adv_s,
+                           const float* v, const float* vtarg, float clip_eps, float* dmu, float* dlogsig, float* dv,
+                           float* stats, RowSel& rs, const char* who) {
     if (!ctx) return fail(MORLAX_ERR_NULL, "%s: ctx is NULL", who);
     if (!rows) return fail(MORLAX_ERR_NULL, "%s: rows is NULL", who);
     REQ(mu, who); REQ(act, who); REQ(logp_old, who); REQ(adv_s, who); REQ(v, who);
@@ -443,10 +441,46 @@ extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, co
             return fail(MORLAX_ERR_SHAPE, "%s: logsig_stride %d < act_dim %d", who, logsig_stride, ctx->d.act_dim);
     }
     if (!(clip_eps >= 0.f)) return fail(MORLAX_ERR_SHAPE, "%s: clip_eps must be >= 0", who);
-    RowSel rs;  // the advantages, targets and actions exist for t < T only
-    int rc = resolve_rows(ctx, rows, ctx->d.T, rs, who);
+    // the advantages, targets and actions exist for t < T only
+    return resolve_rows(ctx, rows, ctx->d.T, rs, who);
+}
+
+extern "C" int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
+                                    const float* logsig, int32_t logsig_stride, const float* act,
+                                    const float* logp_old, const float* adv_s, const float* v,
+                                    const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
+                                    float* dlogsig, float* dv, float* stats, void* ws, int64_t ws_bytes,
+                                    void* stream) {
+    const char* who = "morlax_ppo_loss_grad";
+    RowSel rs;
+    int rc = check_loss_args(ctx, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, dmu,
+                             dlogsig, dv, stats, rs, who);
     if (rc != MORLAX_OK) return rc;
     WS(ws, ws_bytes, loss_ws_bytes(ctx, rs), who);
+    launch_ppo_loss_grad(ctx, rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps,
+                         norm_adv, dmu, dlogsig, dv, stats, ws, (hipStream_t)stream);
+    return finish(who);
+}
+
+extern "C" int morlax_ppo_loss_grad_static(morlax_ctx* ctx, const morlax_rows* rows, const float* mu,
+                                           const float* logsig, int32_t logsig_stride, const float* act,
+                                           const float* logp_old, const float* adv_s, const float* v,
+                                           const float* vtarg, float clip_eps, int32_t norm_adv, float* dmu,
+                                           float* dlogsig, float* dv, float* stats, void* stream) {
+    const char* who = "morlax_ppo_loss_grad_static";
+    RowSel rs;
+    int rc = check_loss_args(ctx, rows, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps, dmu,
+                             dlogsig, dv, stats, rs, who);
+    if (rc != MORLAX_OK) return rc;
+    const int64_t need = loss_ws_bytes(ctx, rs);
+    if (need > (int64_t)MORLAX_STATIC_SCRATCH_BYTES)
+        return fail(MORLAX_ERR_WORKSPACE,
+                    "%s: this selection needs %lld bytes of scratch, the library's static array holds %lld; "
+                    "use morlax_ppo_loss_grad with a workspace", who, (long long)need,
+                    (long long)MORLAX_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (loss_static_scratch(&ws) != 0)
+        return fail(MORLAX_ERR_HIP, "%s: the address of the static scratch array is not available on this device", who);
     launch_ppo_loss_grad(ctx, rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, clip_eps,
                          norm_adv, dmu, dlogsig, dv, stats, ws, (hipStream_t)stream);
     return finish(who);

@@ -79,6 +79,10 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
                           int norm_adv, float* dmu, float* dlogsig, float* dv, float* stats,
                           void* ws, hipStream_t s);
 
+// device address of this GPU's copy of the library's static scratch array (MORLAX_STATIC_SCRATCH_BYTES bytes);
+// 0 on success.  Allocates nothing.
+int loss_static_scratch(void** ptr);
+
 int64_t advnorm_ws_bytes(const morlax_ctx* c, const RowSel& rs);
 void launch_scalarize_normalized(const morlax_ctx* c, const RowSel& rs, const float* adv_vec, const float* w,
                                  float* adv_out, void* ws, hipStream_t s);

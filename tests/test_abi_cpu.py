@@ -180,6 +180,21 @@ def test_too_small_workspace_is_refused_before_any_launch(lib):
     ctx.close()
 
 
+def test_static_scratch_loss_refuses_what_does_not_fit(lib):
+    cfg = configs.scaled(configs.CONFIGS[5], name="too-many-cells", N=128 * 512)   # 16384 blocks of 256 cells
+    ctx = binding.Context.from_config(cfg)
+    good = 0x10000
+    with pytest.raises(binding.MorlaxError) as e:
+        ctx.ppo_loss_grad_static((0, cfg.T, 0, cfg.n_g), good, good, cfg.act_dim, good, good, good, good, good, 0.2, 1,
+                                 good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_WORKSPACE and "static" in str(e.value)
+    with pytest.raises(binding.MorlaxError) as e:      # the same argument checks as the workspace form
+        ctx.ppo_loss_grad_static((0, cfg.T + 1, 0, 1), good, good, cfg.act_dim, good, good, good, good, good, 0.2, 1,
+                                 good, good, good, good, stream=0)
+    assert e.value.code == binding.ERR_SHAPE
+    ctx.close()
+
+
 def test_evaluation_entry_points_reject_bad_arguments(lib):
     cfg = configs.CONFIGS[1]
     ctx = binding.Context.from_config(cfg)
