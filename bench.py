@@ -235,6 +235,10 @@ def main():
                     help="what to time: the whole update step (default) or one of the bandwidth-bound kernels alone")
     ap.add_argument("--sigma-state", action="store_true",
                     help="variant: the actor network outputs its own log sigma (needs 2 * act_dim <= 16: configs 1-3)")
+    ap.add_argument("--stress", action="store_true",
+                    help="with --row vec_gae | vec_gae_trunc | ppo_loss_grad | scalarize_normalized: the same kernel on a "
+                         "labelled stress shape (T = 256, N = 65536, the workload's other sizes) whose tensors do not fit "
+                         "the 256 MB memory-side cache, so that the bandwidth figure is HBM's")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale hardware byte counters)")
     a = ap.parse_args()
@@ -256,6 +260,10 @@ def main():
         from paper_2603_09237_amd.configs import scaled
         cfg = scaled(cfg, name=cfg.name + "-sigma", sigma_state=1)
     if a.row != "update_step":
+        if a.stress:
+            from paper_2603_09237_amd.configs import scaled
+            # (the observation width plays no part in these kernels; 16 keeps the context inside its 4 GiB limit)
+            cfg = scaled(cfg, name=cfg.name + "-stress-T256-N65536", T=256, N=65536, obs_dim=16)
         bench_kernel(a, cfg)
         return
     opt = dict(lr_actor=3e-4, lr_critic=1e-3, beta1=0.9, beta2=0.999, eps=1e-8) if a.with_optimizer else None

@@ -699,24 +699,6 @@ __global__ __launch_bounds__(256) void k_grouped_gemm(GemmArgs<T, KA, KB, Epi, F
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
-// wave-uniform 64-bit address held in scalar registers, whatever unit computed it
-__device__ inline uint64_t uniform_addr(const void* p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ inline void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff),
-                 "s"(uniform_addr(sbase))
-                 : "memory");
-}
-__device__ inline void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr) {  // 4 bytes per lane
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff),
-                 "s"(uniform_addr(sbase))
-                 : "memory");
-}
-template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
 // The LDS has 64 banks of 4 bytes: it serves 16 lanes of a 16-byte read, or 32 lanes of an 8-byte read,
 // per cycle, and the lanes of such a group must touch distinct slots modulo 256 bytes.  With 64-byte rows,
 // rows r .. r+3 fill one 256-byte window, so the chunk index is XORed with bits 2, 3 of the row; the

@@ -2,6 +2,9 @@
 // index map, the reverse-time vector GAE scan with scalarisation, the advantage statistics and the
 // clipped-PPO / value loss with its gradients.  All reductions are two-stage and fixed-order.
 #include "morlax_internal.h"
+#include "numeric.h"
+
+#include <type_traits>
 
 #define WAVE 64
 
@@ -19,45 +22,52 @@ void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s) {
 
 // ------------------------------------------------------------------------------------------------
 // Vector GAE (Sec. III-C, update phase: the estimator applied to every objective on its own, then
-// scalarised).  One lane per (environment, objective): a wave holds G = 64 / K environments with their
-// K objectives in adjacent lanes, so every load of r[t] and v[t] is one contiguous run of G*K floats and
-// the scalarisation sum_k w_k A_k is a K-lane shuffle reduction.
+// scalarised).  A workgroup owns GAE_E = 32 consecutive environments: their (environment, objective)
+// pairs are F = 32 K consecutive floats of every time row of r, v and vtarg -- a whole number of 128-byte
+// lines starting on a line, whatever K is -- and lane f of the row takes pair f, so every load and store of a
+// wave is one aligned run of 256 bytes.
 //
 // The recursion over t, A_t = cut_t ? a_t : a_t + gl A_{t+1} (a_t = r_t - V_t at an episode end, else the
 // TD error; cut_t = episode end or time limit), is a chain of affine maps, so the time axis is split as
-// well: the four waves of a workgroup take four consecutive chunks of up to GAE_CH steps of the same
-// lanes.  A wave requests all loads of its chunk at once, runs the recursion from zero (A'_t), and posts
+// well: the LW = ceil(F / 64) waves that cover a row exist NC times, copy c taking chunk c of up to GAE_CH
+// steps.  A wave requests all loads of its chunk at once, runs the recursion from zero (A'_t), and posts
 // the value at its first step and whether its chunk holds a cut.  After a barrier it folds the posts of
 // the later chunks into the advantage that enters its own chunk, x, and finishes
 // A_t = (a cut between t and the chunk's end) ? A'_t : A'_t + gl^(steps to the chunk's end) x.
 // Cuts stay selects throughout, so nothing behind an episode end -- NaN and Inf included -- reaches the
-// steps before it.  Horizons above 4 * GAE_CH are walked in groups of four chunks, last group first.
-template <int GAE_CH, int NW, int OCC>
-__global__ __launch_bounds__(64 * NW, OCC) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
-                                                const uint8_t* __restrict__ done,
-                                                const uint8_t* __restrict__ trunc, const float* __restrict__ w,
-                                                float gamma, float gl, float* __restrict__ adv_vec,
-                                                float* __restrict__ vtarg, float* __restrict__ adv_s,
-                                                int T, int N, int K, int n_g, int ch) {
-    __shared__ float post_a[2][NW][WAVE];
-    __shared__ uint8_t post_cut[2][NW][WAVE];
-    __shared__ float carry[2][WAVE];
-    // cw: chunk within the group; made visibly wave-uniform so that the step offsets stay in scalar registers
-    const int lane = threadIdx.x & (WAVE - 1), cw = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
-    const int G = WAVE / K;
-    const int e = lane / K, k = lane - e * K;
-    const int n = blockIdx.x * G + e;
-    const bool live = (e < G) && (n < N);
+// steps before it.  Horizons above NC * GAE_CH are walked in groups of NC chunks, last group first.
+// The scalarisation sum_k w_k A_k goes through LDS: every lane leaves w_k A_t there, and after a second
+// barrier the workgroup adds the K terms of a cell in ascending k and writes adv_s as 128-byte runs.
+#define GAE_E 32
+template <int GAE_CH>
+__global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
+                                                     const uint8_t* __restrict__ done,
+                                                     const uint8_t* __restrict__ trunc, const float* __restrict__ w,
+                                                     float gamma, float gl, float* __restrict__ adv_vec,
+                                                     float* __restrict__ vtarg, float* __restrict__ adv_s,
+                                                     int T, int N, int K, int n_g, int ch, int LW, int NC) {
+    __shared__ float post_a[2][1024];     // [slot][chunk copy][pair]: NC * F <= 1024
+    __shared__ uint8_t post_cut[2][1024];
+    __shared__ float carry[2][512];
+    __shared__ float sc[GAE_CH * 1024];   // [chunk copy][step][pair]: w_k A_t of the group being written
+    const int F = GAE_E * K;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int cw = wv / LW, lw = wv - cw * LW;  // chunk copy, wave within the row (both wave-uniform)
+    const int f = lw * WAVE + lane;
+    const int e = f / K, k = f - e * K;
+    const int n0 = blockIdx.x * GAE_E, n = n0 + e;
+    const bool live = (f < F) && (n < N);
     const int64_t NK = (int64_t)N * K;
-    const int64_t idx = (int64_t)n * K + k;
+    const int64_t idx = (int64_t)n0 * K + f;
     const float wk = live ? w[(n / n_g) * K + k] : 0.f;
     float gl_ch = 1.f;  // gl^ch: what a whole chunk without a cut multiplies the entering advantage by
     for (int m = 0; m < ch; ++m) gl_ch *= gl;
 
-    const int n_chunks = (T + ch - 1) / ch, n_groups = (n_chunks + NW - 1) / NW;
+    const int n_chunks = (T + ch - 1) / ch, n_groups = (n_chunks + NC - 1) / NC;
     for (int g = n_groups - 1, it = 0; g >= 0; --g, ++it) {
-        const int buf = it & 1;  // posts and carries alternate between two slots: one barrier per group
-        const int c = NW * g + cw;
+        const int buf = it & 1;  // posts and carries alternate between two slots
+        const int c = NC * g + cw;
         const int t0 = c * ch;
         int len = T - t0;
         len = len < 0 ? 0 : (len > ch ? ch : len);
@@ -91,46 +101,58 @@ __global__ __launch_bounds__(64 * NW, OCC) void k_vec_gae(const float* __restric
             }
             ap[u] = acc;
         }
-        post_a[buf][cw][lane] = ap[0];
-        post_cut[buf][cw][lane] = (uint8_t)(cutm != 0);
-        __syncthreads();
+        if (f < F) {
+            post_a[buf][cw * F + f] = ap[0];
+            post_cut[buf][cw * F + f] = (uint8_t)(cutm != 0);
+        }
+        __syncthreads();  // (also: every wave is done reading the previous group's scalarisation terms)
         // advantage entering this chunk: later chunks of the group folded onto the group's carry-in
-        float x = (it == 0) ? 0.f : carry[buf ^ 1][lane];
-        for (int j = NW - 1; j > cw; --j) {
-            int lj = T - (NW * g + j) * ch;
+        float x = (it == 0 || f >= F) ? 0.f : carry[buf ^ 1][f];
+        for (int j = NC - 1; j > cw; --j) {
+            int lj = T - (NC * g + j) * ch;
             lj = lj < 0 ? 0 : (lj > ch ? ch : lj);
-            float f = gl_ch;
+            float fj = gl_ch;
             if (lj < ch) {  // the last chunk of the horizon may be short (uniform)
-                f = 1.f;
-                for (int m = 0; m < lj; ++m) f *= gl;
+                fj = 1.f;
+                for (int m = 0; m < lj; ++m) fj *= gl;
             }
-            if (lj > 0) x = post_cut[buf][j][lane] ? post_a[buf][j][lane] : post_a[buf][j][lane] + f * x;
+            if (lj > 0 && f < F) x = post_cut[buf][j * F + f] ? post_a[buf][j * F + f] : post_a[buf][j * F + f] + fj * x;
         }
         // finish the chunk and write it out
         uint32_t cut_after = 0;  // a cut at or after step u, within the chunk
-        float f = gl;            // gl^(steps from u to the chunk's end)
+        float fu = gl;           // gl^(steps from u to the chunk's end)
 #pragma unroll
         for (int u = GAE_CH - 1; u >= 0; --u) {
             if (u < len) {
                 cut_after |= (cutm >> u) & 1u;
-                ap[u] = cut_after ? ap[u] : ap[u] + f * x;
-                f *= gl;
+                ap[u] = cut_after ? ap[u] : ap[u] + fu * x;
+                fu *= gl;
             }
         }
-        if (cw == 0) carry[buf][lane] = ap[0];  // read by every wave after the next group's barrier
+        if (cw == 0 && f < F) carry[buf][f] = ap[0];  // read by every wave after the next group's first barrier
 #pragma unroll
         for (int u = 0; u < GAE_CH; ++u) {
             if (u < len) {  // uniform across the wave
                 const float a = ap[u];
-                const float sc = wk * a;
-                float tot = sc;
-                for (int j = 1; j < K; ++j) tot += __shfl_down(sc, j, WAVE);
+                if (f < F) sc[(cw * GAE_CH + u) * F + f] = wk * a;
                 if (live) {
                     const int64_t o = (int64_t)(t0 + u) * NK + idx;
                     if (adv_vec) adv_vec[o] = a;
                     vtarg[o] = a + vt[u];
-                    if (k == 0) adv_s[(int64_t)(t0 + u) * N + n] = tot;
                 }
+            }
+        }
+        __syncthreads();
+        // scalarised advantage of the group's cells: 32 environments of a step per half-wave
+        for (int q = threadIdx.x; q < NC * GAE_CH * GAE_E; q += blockDim.x) {
+            const int cu = q / GAE_E, ee = q % GAE_E;       // (chunk copy, step), environment
+            const int cj = cu / GAE_CH, u = cu % GAE_CH;
+            const int t = (NC * g + cj) * ch + u;
+            if (u < ch && t < T && n0 + ee < N) {
+                const float* term = sc + cu * F + ee * K;
+                float tot = term[0];
+                for (int j = 1; j < K; ++j) tot += term[j];
+                adv_s[(int64_t)t * N + n0 + ee] = tot;
             }
         }
     }
@@ -140,21 +162,40 @@ void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const u
                     const uint8_t* trunc, const float* w, float gamma, float lambda, float* adv_vec,
                     float* vtarg, float* adv_s, hipStream_t s) {
     const int K = c->d.K, N = c->d.N, T = c->d.T;
-    const int G = WAVE / K;
-    const int blocks = (N + G - 1) / G;
-    // the chunks of one group cover the horizon when it is short; CH steps each, in several groups, when it is long
-    // eight chunks of up to eight steps, at most 64 registers per lane (eight waves per SIMD): the fastest of the
-    // shapes tried at T = 64 (16 x 4: 36 us, 8 x 8: 30 us, 4 x 16: 33 us for 81 MB)
-    constexpr int CH = 8, NW = 8;
-    int ch = (T + NW - 1) / NW;
+    const int blocks = (N + GAE_E - 1) / GAE_E;
+    // chunks of up to eight steps (registers: at most 64 per lane, eight waves per SIMD); the chunk copies of a
+    // workgroup: the largest power of two that keeps it within 16 waves, at most eight (K = 6: four copies of three
+    // waves; five measured slower at T = 64 and T = 256), then no more than evens out the groups of chunks
+    constexpr int CH = 8;
+    const int LW = (GAE_E * K + WAVE - 1) / WAVE;
+    int NC = 8;
+    while (NC * LW > 16) NC >>= 1;
+    int ch = (T + NC - 1) / NC;
     ch = ch > CH ? CH : ch;
-    k_vec_gae<CH, NW, 8><<<blocks, 64 * NW, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s,
-                                                   T, N, K, c->n_g, ch);
+    const int n_chunks = (T + ch - 1) / ch, n_groups = (n_chunks + NC - 1) / NC;
+    NC = (n_chunks + n_groups - 1) / n_groups;
+    k_vec_gae<CH><<<blocks, WAVE * LW * NC, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s,
+                                                   T, N, K, c->n_g, ch, LW, NC);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Loss.  Selected cells are enumerated per preference: cell m of preference p is time
-// t0 + m / j_cnt, environment p * n_g + j0 + m % j_cnt.  A block handles 256 cells of one p.
+// t0 + m / j_cnt, environment p * n_g + j0 + m % j_cnt.  A block handles G consecutive groups of 256 cells
+// of one p, one group after the other; a group is up to 256 / j_cnt + 2 runs of consecutive rows of the
+// time-major tensors.  The runs of mu, act, v and vtarg go from global memory straight into LDS as they lie in
+// memory (direct-to-LDS loads, 256 contiguous bytes per wave instruction, all of a group's requests in flight
+// at once), a thread then works on its cell out of LDS, leaves the gradients there, and the block writes
+// them back run by run -- every global access of the kernel is a contiguous run instead of one 4-byte piece
+// per 40-byte row and lane.
+//
+// Three launches per call.  k_adv_partial adds up the scalar advantage of the selection into at most
+// LOSS_MAX_ADV_PART fixed partial sums; every block of k_ppo_loss_grad adds those partials in the same fixed
+// order and so knows mean and standard deviation without a launch in between.  The block sums of the
+// statistics and of the log-sigma gradients are written per block (G is chosen so that there are about
+// LOSS_TARGET_BLOCKS of them, few enough for one workgroup to add up) and k_loss_final adds them in block order:
+// fixed orders throughout, no atomics, results repeatable bit for bit.  (Finishing inside the loss kernel, by
+// whichever block comes last, needs a device-scope release in every block; on this chip that is a write-back of
+// the whole L2 and made the call three times slower.)
 
 __device__ inline double block_sum(double v, double* sh) {
 #pragma unroll
@@ -167,19 +208,46 @@ __device__ inline double block_sum(double v, double* sh) {
     return tot;
 }
 
+#define LOSS_NT 128              // cells per group = threads per block of the loss kernel
+#define LOSS_MAX_ADV_PART 512
+#define LOSS_TARGET_BLOCKS 2048
+
+struct LossPlan {
+    int nbm;     // groups of LOSS_NT cells per preference
+    int G;       // groups per block
+    int nbx;     // blocks per preference
+    int nb256;   // groups of 256 cells per preference (the advantage statistics pass)
+    int n_adv;   // partial sums of the advantage statistics
+    int per;     // 256-cell groups (over all preferences) per advantage partial
+};
+
+static LossPlan loss_plan(const morlax_ctx* c, const RowSel& rs) {
+    LossPlan L;
+    L.nbm = (rs.M + LOSS_NT - 1) / LOSS_NT;
+    const int64_t ngrp = (int64_t)L.nbm * c->d.P;
+    int G = (int)((ngrp + LOSS_TARGET_BLOCKS - 1) / LOSS_TARGET_BLOCKS);
+    L.G = G < 1 ? 1 : G;
+    L.nbx = (L.nbm + L.G - 1) / L.G;
+    L.nb256 = (rs.M + 255) / 256;
+    const int64_t n256 = (int64_t)L.nb256 * c->d.P;
+    const int64_t cap = n256 < LOSS_MAX_ADV_PART ? n256 : LOSS_MAX_ADV_PART;
+    L.per = (int)((n256 + cap - 1) / cap);
+    L.n_adv = (int)((n256 + L.per - 1) / L.per);
+    return L;
+}
+
 struct LossWs {
-    double* adv_part;   // [nblk][2]
-    double* adv_stat;   // [2]: mean, std
-    double* stat_part;  // [nblk][5]
-    double* dls_part;   // [nblk][A]
+    double* adv_part;   // [n_adv][2]
+    double* stat_part;  // [P * nbx][5]
+    double* dls_part;   // [P * nbx][A]
 };
 
 static LossWs loss_ws_layout(const morlax_ctx* c, const RowSel& rs, void* ws, int64_t* total) {
-    const int64_t nbm = (rs.M + 255) / 256, nblk = nbm * c->d.P;
+    const LossPlan pl = loss_plan(c, rs);
+    const int64_t nblk = (int64_t)pl.nbx * c->d.P;
     LossWs L;
     double* p = reinterpret_cast<double*>(ws);
-    L.adv_part = p; p += nblk * 2;
-    L.adv_stat = p; p += 2;
+    L.adv_part = p; p += (int64_t)pl.n_adv * 2;
     L.stat_part = p; p += nblk * 5;
     L.dls_part = p; p += nblk * c->d.act_dim;
     if (total) *total = (int64_t)((char*)p - (char*)ws);
@@ -198,124 +266,278 @@ __device__ inline int64_t cell_row(const RowSel& rs, int p, int m, int N, int n_
     return (int64_t)t * N + (int64_t)p * n_g + j;
 }
 
+// partial b covers the 256-cell groups [b * per, (b + 1) * per) of the (preference, group) enumeration; the
+// loads of sixteen groups are issued together.  V4 (every run of selected cells starts on a 16-byte boundary
+// and holds a multiple of four cells): a group is 64 threads x four consecutive cells, 16 bytes per load.
+template <bool V4>
 __global__ __launch_bounds__(256) void k_adv_partial(RowSel rs, const float* __restrict__ adv_s,
-                                                    double* __restrict__ part, int N, int n_g) {
-    __shared__ double sh[4];
-    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
-    double a = 0.0;
-    if (m < rs.M) a = (double)adv_s[cell_row(rs, p, m, N, n_g)];
-    const double s1 = block_sum(a, sh);
-    const double s2 = block_sum(a * a, sh);
-    if (threadIdx.x == 0) {
-        const int64_t b = (int64_t)p * gridDim.x + blockIdx.x;
-        part[b * 2] = s1;
-        part[b * 2 + 1] = s2;
-    }
-}
-
-__global__ __launch_bounds__(256) void k_adv_final(const double* __restrict__ part, int64_t nblk, double cnt,
-                                                  double* __restrict__ stat) {
+                                                    double* __restrict__ part, int N, int n_g, int nbm, int ngrp,
+                                                    int per) {
     __shared__ double sh[4];
     double s1 = 0.0, s2 = 0.0;
-    for (int64_t b = threadIdx.x; b < nblk; b += 256) {
-        s1 += part[b * 2];
-        s2 += part[b * 2 + 1];
+    const int lo = blockIdx.x * per, hi = (lo + per < ngrp) ? lo + per : ngrp;
+    if (V4) {
+        // the block's 256 threads take four groups at a time: wave w group cb + w, lane l its cells 4 l .. 4 l + 3
+        const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        for (int cb = lo; cb < hi; cb += 16) {
+            float4 a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = cb + 4 * u + wv, p = g / nbm, m = (g - p * nbm) * 256 + 4 * lane;
+                a[u] = (g < hi && m < rs.M) ? *reinterpret_cast<const float4*>(adv_s + cell_row(rs, p, m, N, n_g))
+                                            : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const double x0 = a[u].x, x1 = a[u].y, x2 = a[u].z, x3 = a[u].w;
+                s1 += (x0 + x1) + (x2 + x3);
+                s2 += (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
+            }
+        }
+    } else {
+        for (int cb = lo; cb < hi; cb += 16) {
+            float a[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int g = cb + u, p = g / nbm, m = (g - p * nbm) * 256 + threadIdx.x;
+                a[u] = (g < hi && m < rs.M) ? adv_s[cell_row(rs, p, m, N, n_g)] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                s1 += (double)a[u];
+                s2 += (double)a[u] * (double)a[u];
+            }
+        }
     }
     s1 = block_sum(s1, sh);
     s2 = block_sum(s2, sh);
     if (threadIdx.x == 0) {
-        const double mean = s1 / cnt;
-        double var = s2 / cnt - mean * mean;
-        if (var < 0.0) var = 0.0;
-        stat[0] = mean;
-        stat[1] = sqrt(var);
+        part[2 * blockIdx.x] = s1;
+        part[2 * blockIdx.x + 1] = s2;
     }
 }
 
-template <int A_MAX>
-__global__ __launch_bounds__(256) void k_ppo_loss_grad(
+// One array of a group's cells between global memory and LDS.  The group's cells [m0, m1) of preference p
+// fall into runs of consecutive rows, one per time step touched; a run holds ncell * C consecutive floats.
+struct CellRuns {
+    int m0, m1, j_cnt, tA, tB;
+    int64_t row00;  // row of (time step t0, position j0) of this preference
+    int64_t N;
+    __device__ inline void run(int tt, int& cell0, int& ncell, int64_t& row) const {
+        const int a = tt * j_cnt, b = a + j_cnt;
+        const int cA = m0 > a ? m0 : a, cB = m1 < b ? m1 : b;
+        cell0 = cA - m0;
+        ncell = cB - cA;
+        row = row00 + (int64_t)tt * N + (cA - a);
+    }
+};
+
+// V4: every run starts on a 16-byte boundary and holds a multiple of four floats (the launcher checks the
+// selection), so a lane moves 16 bytes at a time
+template <bool V4, int NT>
+__device__ inline void runs_to_lds(const CellRuns& cr, const float* __restrict__ X, int C, uint32_t lds_addr) {
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int tt = cr.tA; tt <= cr.tB; ++tt) {
+        int cell0, ncell;
+        int64_t row;
+        cr.run(tt, cell0, ncell, row);
+        const float* src = X + row * C;
+        if (V4) {
+            const int count = ncell * C / 4;
+            for (int c0 = wave * 64; c0 < count; c0 += NT)
+                if (c0 + lane < count)
+                    dma16(src + 4 * c0, (uint32_t)lane * 16u,
+                          __builtin_amdgcn_readfirstlane(lds_addr + (uint32_t)(cell0 * C + 4 * c0) * 4u));
+        } else {
+            const int count = ncell * C;
+            for (int c0 = wave * 64; c0 < count; c0 += NT)
+                if (c0 + lane < count)
+                    dma4(src + c0, (uint32_t)lane * 4u,
+                         __builtin_amdgcn_readfirstlane(lds_addr + (uint32_t)(cell0 * C + c0) * 4u));
+        }
+    }
+}
+
+template <bool V4, int NT>
+__device__ inline void lds_to_runs(const CellRuns& cr, float* __restrict__ X, int C, const float* lds) {
+    for (int tt = cr.tA; tt <= cr.tB; ++tt) {
+        int cell0, ncell;
+        int64_t row;
+        cr.run(tt, cell0, ncell, row);
+        float* dst = X + row * C;
+        const float* src = lds + cell0 * C;
+        if (V4) {
+            const int count = ncell * C / 4;
+            for (int i = threadIdx.x; i < count; i += NT)
+                reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+        } else {
+            const int count = ncell * C;
+            for (int i = threadIdx.x; i < count; i += NT) dst[i] = src[i];
+        }
+    }
+}
+
+// sum over the block's NT / 64 waves, fixed order
+template <int NT>
+__device__ inline double block_sum_nt(double v, double* sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) sh[wv] = v;
+    __syncthreads();
+    double tot = sh[0];
+#pragma unroll
+    for (int i = 1; i < NT / 64; ++i) tot += sh[i];
+    __syncthreads();
+    return tot;
+}
+
+// NT threads work on groups of NT cells
+template <int A_MAX, int NT, bool V4>
+__global__ __launch_bounds__(NT, 8) void k_ppo_loss_grad(
     RowSel rs, const float* __restrict__ mu, const float* __restrict__ logsig, int ls_stride,
     const float* __restrict__ act, const float* __restrict__ logp_old, const float* __restrict__ adv_s,
-    const float* __restrict__ v, const float* __restrict__ vtarg, const double* __restrict__ adv_stat,
-    float clip_eps, int norm_adv, float inv_B, float* __restrict__ dmu, float* __restrict__ dv,
-    double* __restrict__ stat_part, double* __restrict__ dls_part, int N, int n_g, int A, int K, int sig_state) {
+    const float* __restrict__ v, const float* __restrict__ vtarg, const double* __restrict__ adv_part, int n_adv,
+    float clip_eps, int norm_adv, double cnt_cells, float* __restrict__ dmu, float* __restrict__ dv,
+    double* __restrict__ stat_part, double* __restrict__ dls_part, int N, int n_g, int A, int K, int G,
+    int sig_state) {
     // sig_state: mu and dmu have 2A columns per cell -- means, then log sigmas (state dependent) / their gradients
-    __shared__ float red[5 + A_MAX][256 + 16];
+    extern __shared__ __align__(16) float lds[];
     __shared__ float s_ls[A_MAX], s_isig[A_MAX];
-    const int p = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
+    __shared__ double sh[4];
+    constexpr int RP = NT + 16;  // pitch of a reduction row
+    const int p = blockIdx.y, tid = threadIdx.x;
     const int mus = sig_state ? 2 * A : A;  // row stride of mu and dmu
-    if (threadIdx.x < A && !sig_state) {
-        const float ls = logsig[(int64_t)p * ls_stride + threadIdx.x];
-        s_ls[threadIdx.x] = ls;
-        s_isig[threadIdx.x] = expf(-ls);
+    // LDS: mu (dmu) | v (dv) | act | vtarg, cell-major as in memory; the reduction rows later reuse act | vtarg.
+    // (Two such buffers, the next group arriving while this one is worked on, halve the blocks per CU and
+    // measured a quarter slower: the kernel lives on many independent blocks, eight per CU.)
+    float* l_mu = lds;
+    float* l_v = l_mu + NT * mus;
+    float* l_act = l_v + NT * K;
+    float* l_vt = l_act + NT * A;
+    const uint32_t lbase = (uint32_t)(size_t)lds;
+    CellRuns cr;
+    cr.j_cnt = rs.j_cnt;
+    cr.N = N;
+    cr.row00 = (int64_t)rs.t0 * N + (int64_t)p * n_g + rs.j0;
+    auto request = [&](int grp) {  // a group's runs of the four arrays, on their way into LDS
+        cr.m0 = grp * NT;
+        cr.m1 = cr.m0 + NT < rs.M ? cr.m0 + NT : rs.M;
+        cr.tA = cr.m0 / rs.j_cnt;
+        cr.tB = (cr.m1 - 1) / rs.j_cnt;
+        runs_to_lds<V4, NT>(cr, mu, mus, lbase);
+        runs_to_lds<V4, NT>(cr, v, K, lbase + (uint32_t)(NT * mus) * 4u);
+        runs_to_lds<V4, NT>(cr, act, A, lbase + (uint32_t)(NT * (mus + K)) * 4u);
+        runs_to_lds<V4, NT>(cr, vtarg, K, lbase + (uint32_t)(NT * (mus + K + A)) * 4u);
+    };
+    const int nbm = (rs.M + NT - 1) / NT;
+    const int g_lo = blockIdx.x * G, g_hi = (g_lo + G < nbm) ? g_lo + G : nbm;
+    request(g_lo);
+    if (tid < A && !sig_state) {
+        const float ls = logsig[(int64_t)p * ls_stride + tid];
+        s_ls[tid] = ls;
+        s_isig[tid] = expf(-ls);
     }
-    __syncthreads();
-    const bool ok = m < rs.M;
-    float l_pi = 0.f, l_v = 0.f, clipped = 0.f, kl = 0.f, rho_s = 0.f;
+    // mean and standard deviation of the selection's advantage from the fixed partial sums
+    double s1 = 0.0, s2 = 0.0;
+    for (int i = tid; i < n_adv; i += NT) {
+        s1 += adv_part[2 * i];
+        s2 += adv_part[2 * i + 1];
+    }
+    s1 = block_sum_nt<NT>(s1, sh);
+    s2 = block_sum_nt<NT>(s2, sh);
+    const double a_mean = s1 / cnt_cells;
+    double a_var = s2 / cnt_cells - a_mean * a_mean;
+    a_var = a_var < 0.0 ? 0.0 : a_var;
+    const double a_std = sqrt(a_var);
+    const float inv_B = (float)(1.0 / cnt_cells);
+    const double inv_std = 1.0 / (a_std + 1e-8);
+
+    float l_pi = 0.f, l_val = 0.f, clipped = 0.f, kl = 0.f, rho_s = 0.f;
     float dls[A_MAX];
 #pragma unroll
     for (int a = 0; a < A_MAX; ++a) dls[a] = 0.f;
-    if (ok) {
-        const int64_t row = cell_row(rs, p, m, N, n_g);
-        float ahat = adv_s[row];
-        if (norm_adv) ahat = (float)(((double)ahat - adv_stat[0]) / (adv_stat[1] + 1e-8));
-        float q[A_MAX], isig[A_MAX];
-        float logp = -0.918938533204672742f * (float)A;  // -(A/2) log(2 pi)
+    for (int grp = g_lo; grp < g_hi; ++grp) {
+        const int m = grp * NT + tid;
+        const bool ok = m < rs.M;
+        float ahat = 0.f, lpo = 0.f;
+        if (ok) {
+            const int64_t row = cell_row(rs, p, m, N, n_g);
+            ahat = adv_s[row];
+            lpo = logp_old[row];
+        }
+        wait_vm<0>();
+        __syncthreads();  // the group's runs are in LDS
+        if (ok) {
+            if (norm_adv) ahat = (float)(((double)ahat - a_mean) * inv_std);
+            float* c_mu = l_mu + tid * mus;
+            const float* c_act = l_act + tid * A;
+            // two passes over the action components (the second forms q again from LDS) instead of per-component
+            // register arrays: 64 registers per lane, eight waves per SIMD
+            float logp = -0.918938533204672742f * (float)A;  // -(A/2) log(2 pi)
 #pragma unroll
-        for (int a = 0; a < A_MAX; ++a) {
-            if (a < A) {
-                float ls = 0.f;
-                if (sig_state) {
-                    ls = mu[row * mus + A + a];
-                    isig[a] = expf(-ls);
-                } else {
-                    ls = s_ls[a];
-                    isig[a] = s_isig[a];
+            for (int a = 0; a < A_MAX; ++a) {
+                if (a < A) {
+                    const float ls = sig_state ? c_mu[A + a] : s_ls[a];
+                    const float is = sig_state ? expf(-ls) : s_isig[a];
+                    const float q = (c_act[a] - c_mu[a]) * is;
+                    logp += -0.5f * q * q - ls;
                 }
-                q[a] = (act[row * A + a] - mu[row * mus + a]) * isig[a];
-                logp += -0.5f * q[a] * q[a] - ls;
             }
-        }
-        const float lpo = logp_old[row];
-        const float rho = expf(logp - lpo);
-        const float rc = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
-        l_pi = -fminf(rho * ahat, rc * ahat);
-        const bool pass = (ahat >= 0.f) ? (rho <= 1.f + clip_eps) : (rho >= 1.f - clip_eps);
-        const float dlogp = pass ? (-ahat * rho * inv_B) : 0.f;
-        clipped = (fabsf(rho - 1.f) > clip_eps) ? 1.f : 0.f;
-        kl = lpo - logp;
-        rho_s = rho;
+            const float rho = expf(logp - lpo);
+            const float rc = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
+            l_pi += -fminf(rho * ahat, rc * ahat);
+            const bool pass = (ahat >= 0.f) ? (rho <= 1.f + clip_eps) : (rho >= 1.f - clip_eps);
+            const float dlogp = pass ? (-ahat * rho * inv_B) : 0.f;
+            clipped += (fabsf(rho - 1.f) > clip_eps) ? 1.f : 0.f;
+            kl += lpo - logp;
+            rho_s += rho;
 #pragma unroll
-        for (int a = 0; a < A_MAX; ++a) {
-            if (a < A) {
-                dmu[row * mus + a] = dlogp * q[a] * isig[a];
-                const float g = dlogp * (q[a] * q[a] - 1.f);
-                if (sig_state) dmu[row * mus + A + a] = g;  // stays per cell: it flows back through the network
-                else dls[a] = g;
+            for (int a = 0; a < A_MAX; ++a) {
+                if (a < A) {
+                    const float is = sig_state ? expf(-c_mu[A + a]) : s_isig[a];
+                    const float q = (c_act[a] - c_mu[a]) * is;
+                    c_mu[a] = dlogp * q * is;
+                    const float g = dlogp * (q * q - 1.f);
+                    if (sig_state) c_mu[A + a] = g;  // stays per cell: it flows back through the network
+                    else dls[a] += g;
+                }
+            }
+            float* c_v = l_v + tid * K;
+            const float* c_vt = l_vt + tid * K;
+            for (int k = 0; k < K; ++k) {
+                const float dd = c_v[k] - c_vt[k];
+                l_val += dd * dd;
+                c_v[k] = 2.f * dd * inv_B;
             }
         }
-        for (int k = 0; k < K; ++k) {
-            const float dd = v[row * K + k] - vtarg[row * K + k];
-            l_v += dd * dd;
-            dv[row * K + k] = 2.f * dd * inv_B;
+        __syncthreads();  // gradients complete in LDS; act and vtarg no longer needed
+        lds_to_runs<V4, NT>(cr, dmu, mus, l_mu);
+        lds_to_runs<V4, NT>(cr, dv, K, l_v);
+        if (grp + 1 < g_hi) {
+            __syncthreads();  // every thread has read what it stores before the next group's runs arrive
+            request(grp + 1);
         }
     }
     // block sums of the 5 statistics and the A log-sigma terms: the per-cell values go to LDS (one padded row
-    // per quantity), then 16 lanes add up each row in fp64 -- 16 values each in ascending order, then four
+    // per quantity), then 16 lanes add up each row in fp64 -- NT / 16 values each in ascending order, then four
     // exchange steps -- so the whole reduction costs two barriers and has a fixed order
+    float* red = l_act;
     const int64_t b = (int64_t)p * gridDim.x + blockIdx.x;
-    const int nq = 5 + A;
-    red[0][threadIdx.x] = l_pi; red[1][threadIdx.x] = l_v; red[2][threadIdx.x] = clipped;
-    red[3][threadIdx.x] = kl; red[4][threadIdx.x] = rho_s;
+    const int nq = 5 + (sig_state ? 0 : A);
+    red[0 * RP + tid] = l_pi; red[1 * RP + tid] = l_val; red[2 * RP + tid] = clipped;
+    red[3 * RP + tid] = kl; red[4 * RP + tid] = rho_s;
+    if (!sig_state) {
 #pragma unroll
-    for (int a = 0; a < A_MAX; ++a)
-        if (a < A) red[5 + a][threadIdx.x] = dls[a];
+        for (int a = 0; a < A_MAX; ++a)
+            if (a < A) red[(5 + a) * RP + tid] = dls[a];
+    }
     __syncthreads();
-    const int qi = threadIdx.x >> 4, li = threadIdx.x & 15;
-    for (int q = qi; q < nq; q += 16) {  // (a wave's four groups of 16 lanes take the same number of turns)
+    const int qi = tid >> 4, li = tid & 15;
+    for (int q = qi; q < nq; q += NT / 16) {  // (a wave's four groups of 16 lanes take the same number of turns)
         double t = 0.0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) t += (double)red[q][16 * j + li];
+        for (int j = 0; j < NT / 16; ++j) t += (double)red[q * RP + 16 * j + li];
         t += __shfl_xor(t, 8, WAVE);
         t += __shfl_xor(t, 4, WAVE);
         t += __shfl_xor(t, 2, WAVE);
@@ -327,41 +549,87 @@ __global__ __launch_bounds__(256) void k_ppo_loss_grad(
     }
 }
 
-// blocks 0..P-1: dlogsig[p][:]; block P: stats
-__global__ __launch_bounds__(256) void k_loss_final(const double* __restrict__ stat_part,
-                                                   const double* __restrict__ dls_part,
-                                                   const double* __restrict__ adv_stat, int nbm, int P, int A,
-                                                   double cnt, float* __restrict__ dlogsig,
-                                                   float* __restrict__ stats) {
-    __shared__ double sh[4];
+// blocks 0 .. P-1: dlogsig[p][:] (the preference's block partials in block order); block P: the statistics.
+// 1024 threads, so that the one block that adds up the statistics has enough loads in flight.
+__device__ inline double block_sum16(double v, double* sh) {  // 16 waves, fixed order
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) sh[wv] = v;
+    __syncthreads();
+    double tot = sh[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) tot += sh[i];
+    __syncthreads();
+    return tot;
+}
+
+__global__ __launch_bounds__(1024) void k_loss_final(const double* __restrict__ stat_part,
+                                                    const double* __restrict__ dls_part,
+                                                    const double* __restrict__ adv_part, int n_adv, int nbx, int P,
+                                                    int A, double cnt, float* __restrict__ dlogsig,
+                                                    float* __restrict__ stats) {
+    __shared__ double sh[16];
     const int p = blockIdx.x;
     if (p < P) {
         if (!dlogsig) return;  // (state-dependent sigma: there is no per-preference log-sigma gradient)
-        for (int a = 0; a < A; ++a) {
-            double s = 0.0;
-            for (int b = threadIdx.x; b < nbm; b += 256) s += dls_part[((int64_t)p * nbm + b) * A + a];
-            s = block_sum(s, sh);
-            if (threadIdx.x == 0) dlogsig[p * A + a] = (float)s;
+        // thread (a, i) adds the partials i, i + 64, ... of component a; then the 64 shares of a component in order
+        __shared__ double part[MORLAX_MAX_OUT][64];
+        const int a = threadIdx.x >> 6, i = threadIdx.x & 63;
+        double s = 0.0;
+        if (a < A)
+            for (int b = i; b < nbx; b += 64) s += dls_part[((int64_t)p * nbx + b) * A + a];
+        part[a][i] = s;
+        __syncthreads();
+        if (threadIdx.x < A) {
+            double t = 0.0;
+            for (int j = 0; j < 64; ++j) t += part[threadIdx.x][j];
+            dlogsig[p * A + threadIdx.x] = (float)t;
         }
     } else {
-        const int64_t nblk = (int64_t)nbm * P;
-        double acc[5];
-        for (int i = 0; i < 5; ++i) {
-            double s = 0.0;
-            for (int64_t b = threadIdx.x; b < nblk; b += 256) s += stat_part[b * 5 + i];
-            acc[i] = block_sum(s, sh);
+        const int64_t nblk = (int64_t)nbx * P;
+        double s[7] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+        for (int64_t b = threadIdx.x; b < nblk; b += 1024) {
+#pragma unroll
+            for (int i = 0; i < 5; ++i) s[i] += stat_part[b * 5 + i];
         }
+        for (int b = threadIdx.x; b < n_adv; b += 1024) {
+            s[5] += adv_part[2 * b];
+            s[6] += adv_part[2 * b + 1];
+        }
+        double acc[7];
+        for (int i = 0; i < 7; ++i) acc[i] = block_sum16(s[i], sh);
         if (threadIdx.x == 0) {
+            const double mean = acc[5] / cnt;
+            double var = acc[6] / cnt - mean * mean;
+            var = var < 0.0 ? 0.0 : var;
             stats[0] = (float)(acc[0] / cnt);
             stats[1] = (float)(acc[1] / cnt);
             stats[2] = (float)(acc[2] / cnt);
             stats[3] = (float)(acc[3] / cnt);
-            stats[4] = (float)adv_stat[0];
-            stats[5] = (float)adv_stat[1];
+            stats[4] = (float)mean;
+            stats[5] = (float)sqrt(var);
             stats[6] = (float)(acc[4] / cnt);
             stats[7] = (float)cnt;
         }
     }
+}
+
+static int64_t loss_lds_floats(int mus, int A, int K, int nq) {
+    const int64_t dead = LOSS_NT * (int64_t)(A + K), red = (int64_t)(LOSS_NT + 16) * nq;
+    return LOSS_NT * (int64_t)(mus + K) + (dead > red ? dead : red);
+}
+
+// every run of every array starts on a 16-byte boundary and is a multiple of 16 bytes long
+static bool loss_vec4_ok(const morlax_ctx* c, const RowSel& rs, int mus) {
+    const int A = c->d.act_dim, K = c->d.K;
+    const int cs[3] = {mus, A, K};
+    for (int C : cs) {
+        if (((int64_t)c->d.N * C) % 4 || ((int64_t)c->n_g * C) % 4 || ((int64_t)rs.j0 * C) % 4 ||
+            ((int64_t)rs.j_cnt * C) % 4 || ((int64_t)LOSS_NT * C) % 4)
+            return false;
+    }
+    return true;
 }
 
 void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu, const float* logsig,
@@ -369,18 +637,24 @@ void launch_ppo_loss_grad(const morlax_ctx* c, const RowSel& rs, const float* mu
                           const float* adv_s, const float* v, const float* vtarg, float clip_eps,
                           int norm_adv, float* dmu, float* dlogsig, float* dv, float* stats, void* ws,
                           hipStream_t s) {
-    const int P = c->d.P, N = c->d.N, A = c->d.act_dim, K = c->d.K;
+    const int P = c->d.P, N = c->d.N, A = c->d.act_dim, K = c->d.K, sig = c->d.sigma_state;
+    const LossPlan pl = loss_plan(c, rs);
     LossWs L = loss_ws_layout(c, rs, ws, nullptr);
-    const int nbm = (rs.M + 255) / 256;
-    const dim3 grid(nbm, P);
     const double cnt = (double)rs.M * P;
-    k_adv_partial<<<grid, 256, 0, s>>>(rs, adv_s, L.adv_part, N, c->n_g);
-    k_adv_final<<<1, 256, 0, s>>>(L.adv_part, (int64_t)nbm * P, cnt, L.adv_stat);
-    k_ppo_loss_grad<MORLAX_MAX_OUT><<<grid, 256, 0, s>>>(rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v,
-                                                        vtarg, L.adv_stat, clip_eps, norm_adv,
-                                                        (float)(1.0 / cnt), dmu, dv, L.stat_part, L.dls_part,
-                                                        N, c->n_g, A, K, c->d.sigma_state);
-    k_loss_final<<<P + 1, 256, 0, s>>>(L.stat_part, L.dls_part, L.adv_stat, nbm, P, A, cnt, dlogsig, stats);
+    if (N % 4 == 0 && c->n_g % 4 == 0 && rs.j0 % 4 == 0 && rs.j_cnt % 4 == 0)
+        k_adv_partial<true><<<pl.n_adv, 256, 0, s>>>(rs, adv_s, L.adv_part, N, c->n_g, pl.nb256, pl.nb256 * P, pl.per);
+    else
+        k_adv_partial<false><<<pl.n_adv, 256, 0, s>>>(rs, adv_s, L.adv_part, N, c->n_g, pl.nb256, pl.nb256 * P, pl.per);
+    const int mus = sig ? 2 * A : A;
+    const size_t lds_bytes = (size_t)loss_lds_floats(mus, A, K, 5 + (sig ? 0 : A)) * 4;
+    auto launch = [&](auto v4) {
+        constexpr bool V4 = decltype(v4)::value;
+        k_ppo_loss_grad<MORLAX_MAX_OUT, LOSS_NT, V4><<<dim3(pl.nbx, P), LOSS_NT, lds_bytes, s>>>(
+            rs, mu, logsig, logsig_stride, act, logp_old, adv_s, v, vtarg, L.adv_part, pl.n_adv, clip_eps, norm_adv,
+            cnt, dmu, dv, L.stat_part, L.dls_part, N, c->n_g, A, K, pl.G, sig);
+    };
+    if (loss_vec4_ok(c, rs, mus)) launch(std::true_type{}); else launch(std::false_type{});
+    k_loss_final<<<P + 1, 1024, 0, s>>>(L.stat_part, L.dls_part, L.adv_part, pl.n_adv, pl.nbx, P, A, cnt, dlogsig, stats);
 }
 
 // The same call on scratch that lives in the library's own image, for callers that cannot allocate: a

@@ -47,3 +47,25 @@ __device__ inline void store8(bf16_t* dst, const float v[8]) {
     for (int i = 0; i < 8; ++i) o[i] = (bf16_t)v[i];
     *reinterpret_cast<bf16x8_t*>(dst) = o;
 }
+
+// ---- direct-to-LDS loads (global_load_lds_*): a wave-uniform 64-bit base in scalar registers plus a 32-bit
+// lane offset; lane l of the wave writes its 4 (16) bytes at LDS address lds_addr + 4 l (16 l).  Asynchronous:
+// counted by vmcnt like any load, no staging registers.
+// wave-uniform 64-bit address held in scalar registers, whatever unit computed it
+__device__ inline uint64_t uniform_addr(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ inline void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff),
+                 "s"(uniform_addr(sbase))
+                 : "memory");
+}
+__device__ inline void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr) {  // 4 bytes per lane
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff),
+                 "s"(uniform_addr(sbase))
+                 : "memory");
+}
+template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+

@@ -181,7 +181,8 @@ def test_too_small_workspace_is_refused_before_any_launch(lib):
 
 
 def test_static_scratch_loss_refuses_what_does_not_fit(lib):
-    cfg = configs.scaled(configs.CONFIGS[5], name="too-many-cells", N=128 * 512)   # 16384 blocks of 256 cells
+    # the per-block partial sums grow with the number of preferences: 16384 of them with 16 actions need 2.7 MB
+    cfg = configs.scaled(configs.CONFIGS[1], name="too-many-preferences", P=16384, N=16384, act_dim=16)
     ctx = binding.Context.from_config(cfg)
     good = 0x10000
     with pytest.raises(binding.MorlaxError) as e:
