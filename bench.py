@@ -200,6 +200,12 @@ def bench_kernel(a, cfg):
     for _ in range(max(a.warmup, 1)):
         launch()
     torch.cuda.synchronize()
+    if a.calib_copy:   # a kernel of known traffic (reads 1 GiB, writes 1 GiB) to scale hardware byte counters by
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(a.steps):

@@ -56,7 +56,11 @@ __global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r
     const int cw = wv / LW, lw = wv - cw * LW;  // chunk copy, wave within the row (both wave-uniform)
     const int f = lw * WAVE + lane;
     const int e = f / K, k = f - e * K;
-    const int n0 = blockIdx.x * GAE_E, n = n0 + e;
+    // workgroups are dealt to the chip's eight dies in turn; the block of environments follows the die, so that
+    // neighbouring blocks -- which share the 128-byte lines of `done` -- meet in one die's L2
+    const int nb = gridDim.x, xq = nb / 8, xr = nb % 8, xd = blockIdx.x % 8;
+    const int blk = xd * xq + (xd < xr ? xd : xr) + blockIdx.x / 8;
+    const int n0 = blk * GAE_E, n = n0 + e;
     const bool live = (f < F) && (n < N);
     const int64_t NK = (int64_t)N * K;
     const int64_t idx = (int64_t)n0 * K + f;
