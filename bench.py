@@ -33,9 +33,20 @@ KERNEL_OF_KIND = {
     "fwd_fused": "k_mlp_fused_fwd: first layer and all W x W layers of a 128-row tile in one launch (rollout + update)",
 }
 
-# HBM bytes per launch of a GEMM launch kind, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script scaled by
-# a copy of known size (profiles/fused_fwd_grouped_gemm_cfg5_hbm_traffic.txt); workloads without such a run report null
-MEASURED_TRAFFIC_BYTES = {("cfg5-largest-K6-P128-N16384-T64-4x512-silu-bf16-4mbx2ep", "fwd_fused"): 2273.8e6}
+
+
+def measured_traffic(workload, kind):
+    """HBM bytes per launch of a launch kind (or of a bandwidth row), read from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    summaries under profiles/: every summary ends with lines `traffic_bytes_per_launch workload=<name> kind=<kind>
+    bytes=<n>`.  None when no summary covers the pair."""
+    import glob
+    import re
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(f):
+            m = re.match(r"traffic_bytes_per_launch workload=(\S+) kind=(\S+) bytes=([0-9.eE+]+)", line.strip())
+            if m and m.group(1) == workload and m.group(2) == kind:
+                return float(m.group(3))
+    return None
 
 
 def cpu_baseline(cfg_full):
@@ -219,7 +230,7 @@ def bench_kernel(a, cfg):
         "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic", "config": {"workload": cfg.name, "row": a.row},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
-                     "traffic": None, "bytes_per_launch": bytes_per_launch}}))
+                     "traffic": measured_traffic(cfg.name, a.row), "bytes_per_launch": bytes_per_launch}}))
 
 
 def main():
@@ -286,12 +297,25 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    st.ctx.profile_begin()
+    # timed region: exactly `steps` update steps between two synchronisations, every step between a pair of events on
+    # the launch stream (every launch of the default schedule is on torch's current stream)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for e0, e1 in ev:
+        e0.record()
+        st.run()
+        e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
+    # second pass, outside the timed region: the library brackets every grouped-GEMM launch with its own event pair,
+    # which gives the per-kind kernel times behind `roofline`
+    st.ctx.profile_begin()
     for _ in range(a.steps):
         st.run()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
     prof = st.ctx.profile_end()
 
     env_steps = cfg.T * cfg.N
@@ -307,6 +331,7 @@ def main():
         "unit": "env-steps/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": dt / a.steps * 1e3,
+        "ms_per_step_event_median": median_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "K": cfg.K, "P": cfg.P, "N": cfg.N, "T": cfg.T, "obs_dim": cfg.obs_dim,
@@ -314,7 +339,7 @@ def main():
                    "minibatches": cfg.minibatches, "epochs": cfg.epochs, "env_steps_per_step": env_steps,
                    "optimizer_step": "adam, one learning rate per hypernet" if a.with_optimizer else "not included"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, kind)),
+                     "frac": achieved / peak, "traffic": measured_traffic(cfg.name, kind),
                      "kernel": KERNEL_OF_KIND[kind], "launches_per_step": launches / a.steps,
                      "avg_launch_ms": ms / max(launches, 1), "flop_per_launch": flops / max(launches, 1),
                      "all_gemm_ms_per_step": gemm_ms / a.steps,
