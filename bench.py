@@ -245,6 +245,9 @@ def main():
                          "those of kernels running alone; side: the hypernet calls on a second stream next to the grouped "
                          "GEMMs, which stay on the main stream; 2: actor and critic chains on their own streams (two GEMMs "
                          "in flight stretch each other's event-timed durations)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step into a HIP graph once and time its replays (one submission per step instead of a "
+                         "few hundred launches); same kernels, same results")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="take an Adam step on both hypernets after every minibatch (the headline metric leaves it out)")
     ap.add_argument("--row", choices=("update_step", "adam_step", "vec_gae", "vec_gae_trunc", "ppo_loss_grad", "scalarize_normalized",
@@ -300,11 +303,17 @@ def main():
     # timed region: exactly `steps` update steps between two synchronisations, every step between a pair of events on
     # the launch stream (every launch of the default schedule is on torch's current stream)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    step = st.run
+    if a.graph:
+        st.capture()
+        step = st.replay
+        for _ in range(2):
+            step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for e0, e1 in ev:
         e0.record()
-        st.run()
+        step()
         e1.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -337,7 +346,8 @@ def main():
         "config": {"workload": cfg.name, "K": cfg.K, "P": cfg.P, "N": cfg.N, "T": cfg.T, "obs_dim": cfg.obs_dim,
                    "act_dim": cfg.act_dim, "mlp": f"{cfg.n_hidden}x{cfg.width}", "rank": cfg.rank,
                    "minibatches": cfg.minibatches, "epochs": cfg.epochs, "env_steps_per_step": env_steps,
-                   "optimizer_step": "adam, one learning rate per hypernet" if a.with_optimizer else "not included"},
+                   "optimizer_step": "adam, one learning rate per hypernet" if a.with_optimizer else "not included",
+                   "submission": "one HIP graph per step" if a.graph else "eager launches"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": measured_traffic(cfg.name, kind),
                      "kernel": KERNEL_OF_KIND[kind], "launches_per_step": launches / a.steps,

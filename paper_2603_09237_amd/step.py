@@ -174,6 +174,27 @@ class UpdateStep:
         ctx.ppo_loss_grad(rows, self.mu, logsig, ctx.theta_vec_len(ACTOR), self.act, self.logp_old, adv,
                           self.v, self.vtarg, c.clip_eps, norm, self.dmu, self.dlogsig, self.dv, self.stats, self.ws)
 
+    def capture(self):
+        """Record one whole update step into a HIP graph (the default one-stream schedule, no optimiser step: its step
+        counter is a host-side argument).  The few hundred launches of a step then cost one submission; what they
+        compute is unchanged.  One eager step runs first, so that one-time set-up inside the library (function
+        attributes, device queries) happens outside the capture.  Nothing in the step allocates or clears memory
+        with a memset node."""
+        t = self.torch
+        if self.optimizer is not None or self.streams is not None or self.side is not None:
+            raise ValueError("capture() records the one-stream schedule without optimiser step")
+        self.run()
+        t.cuda.synchronize()
+        g = t.cuda.CUDAGraph()
+        with t.cuda.graph(g):
+            self.run()
+        self.graph = g
+        return g
+
+    def replay(self):
+        """Submit the recorded step (capture() first) on the current stream."""
+        self.graph.replay()
+
     def run(self, on_minibatch=None):
         """One whole update step.  `on_minibatch(e, b)` (optional) is called after each minibatch."""
         if self.side is not None:

@@ -998,3 +998,44 @@ def test_update_step_wide_networks_reduced_preferences(cfg, torch, binding):
             rep = [bf16_chain_report(g[o:o + int(np.prod(shp))], ref[key][o:o + int(np.prod(shp))]) + (name,)
                    for name, (o, shp) in orc.hparam_layout(cfg, net).items() if name != "_total"]
             say(f"  mb {i} {key}: worst block by outliers {max(rep, key=lambda r: r[0])}, by RMS {max(rep, key=lambda r: r[2])}")
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS[1], scaled(RAGGED_FUSED, name="ragged-fused-graph", minibatches=1, epochs=2)],
+                         ids=lambda c: c.name)
+def test_update_step_graph_replays_equal_eager(cfg, torch, binding):
+    """The step recorded into a HIP graph: every replay -- with eager work of the same library and synchronisations
+    in between, and with new inputs in the same buffers -- gives the eager step's results bit for bit."""
+    from paper_2603_09237_amd.step import UpdateStep
+    say(f"update_step graph {cfg.name}")
+    st = UpdateStep(cfg, keep_adv_vec=True)
+    d = inputs.make_all(cfg)
+    st.load_inputs(d)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [to_np(t).copy() for t in (st.dhp[ACTOR], st.dhp[CRITIC], st.stats, st.adv_s, st.vtarg, st.act, st.logp_old)]
+
+    st.run()
+    eager = snapshot()
+    st.capture()
+    other = scaled(cfg, name="other-seed", seed=7)
+    d2 = inputs.make_all(other)
+    ctx2 = binding.Context.from_config(cfg)
+    for it in range(4):
+        for t in (st.dhp[ACTOR], st.dhp[CRITIC], st.stats, st.adv_s, st.vtarg):
+            t.fill_(float("nan"))                       # a replay has to write everything again
+        if it == 2:                                     # new inputs in the same buffers: the graph follows the data
+            st.load_inputs(d2)
+            st.run()
+            eager = snapshot()
+            for t in (st.dhp[ACTOR], st.dhp[CRITIC], st.stats):
+                t.fill_(float("nan"))
+        st.replay()
+        got = snapshot()
+        for g, e in zip(got, eager):
+            assert np.array_equal(g, e), it
+        # eager work of the library between the replays
+        out = torch.empty(cfg.N, dtype=torch.int32, device="cuda")
+        ctx2.env_pref_index(out)
+        torch.cuda.synchronize()
+    assert np.isfinite(eager[0]).all() and np.abs(eager[0]).max() > 0
