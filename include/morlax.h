@@ -222,8 +222,8 @@ int morlax_ppo_loss_grad(morlax_ctx* ctx, const morlax_rows* rows, const float* 
  * same kernels, same results bit for bit; the partial sums live in a static device array inside the
  * library, MORLAX_STATIC_SCRATCH_BYTES bytes on every GPU the library runs on, held until the process
  * ends.  The call allocates and frees nothing.  The partial sums take 8 (5 + act_dim) bytes per block and
- * there are at most about 4096 + P blocks whatever the number of selected cells, so every selection of up to
- * some 8 000 trade-offs fits; one that does not is refused with MORLAX_ERR_WORKSPACE before anything is
+ * there are at most about 2048 + P blocks whatever the number of selected cells, so every selection of up to
+ * some 10 000 trade-offs fits; one that does not is refused with MORLAX_ERR_WORKSPACE before anything is
  * launched.  All calls on one GPU share that GPU's array: calls that may overlap there (two
  * streams, two threads) race; order them.  Nothing in the array needs to survive or be cleared between
  * calls. */
