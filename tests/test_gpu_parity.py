@@ -843,7 +843,8 @@ def test_update_step_bf16_matches_oracle(cfg, torch, binding):
                 if name == "_total":
                     continue
                 n = int(np.prod(s))
-                assert_close_bf16(g[o:o + n], ref[key][o:o + n], f"{key}[{name}] mb {i}")
+                # (end of a chain of re-rounded layers: RMS bound, single-GEMM band with a small outlier budget)
+                assert_close_bf16_chain(g[o:o + n], ref[key][o:o + n], f"{key}[{name}] mb {i}")
 
 
 def _blocks_close(close, got, ref, cfg, net, what, **kw):
