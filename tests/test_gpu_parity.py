@@ -1040,3 +1040,99 @@ def test_update_step_graph_replays_equal_eager(cfg, torch, binding):
         ctx2.env_pref_index(out)
         torch.cuda.synchronize()
     assert np.isfinite(eager[0]).all() and np.abs(eager[0]).max() > 0
+
+
+STRESS = scaled(CONFIGS[5], name="cfg5-stress-T256-N65536", T=256, N=65536, obs_dim=16)
+
+
+def test_vec_gae_stress_shape_sampled(torch, binding):
+    """The shape bench.py --stress times (T = 256, N = 65536: eight groups of chunks per workgroup).  Environments do
+    not interact in the scan, so the oracle follows a sample of them (whole blocks of 32 and scattered single ones)
+    column by column; all-done and no-done rows are planted to hit both branches at every chunk boundary."""
+    cfg = STRESS
+    say(f"vec_gae {cfg.name}")
+    rng = np.random.default_rng(123)
+    T, N, K = cfg.T, cfg.N, cfg.K
+    r = rng.standard_normal((T, N, K), dtype=np.float32)
+    v = rng.standard_normal((T + 1, N, K), dtype=np.float32)
+    done = (rng.random((T, N)) < cfg.p_done).astype(np.uint8)
+    done[:, 5] = 1
+    done[:, 6] = 0
+    done[7::8, 9] = 1                                   # an episode end at the last step of every chunk
+    done[0::8, 10] = 1                                  # ... and at the first
+    w = inputs.make_preferences(cfg)
+    _, vtarg, adv_s = run_gae(cfg, torch, binding, r, v, done, w, want_vec=False)
+    idx = np.unique(np.concatenate([np.arange(0, 64), np.arange(N - 32, N), rng.integers(0, N, size=400),
+                                    np.arange(31 * cfg.n_g - 16, 31 * cfg.n_g + 48)]))
+    g = orc.env_pref_index(N, cfg.P)[idx]
+    # the oracle on the sampled columns: every sampled environment becomes a group of its own with its trade-off
+    ws = np.repeat(w[g], 2, axis=0)                      # (the oracle wants P > 1 and P | N: two copies of each)
+    rs, vs, ds = (np.repeat(a[:, idx], 2, axis=1) for a in (r, v, done))
+    o_adv, o_vt, o_as = orc.vec_gae(rs, vs, ds, ws, cfg.gamma, cfg.lam)
+    o_vt, o_as, o_adv = o_vt[:, ::2], o_as[:, ::2], o_adv[:, ::2]
+    for k in range(K):
+        sk = max(1.0, float(np.sqrt(np.mean(o_adv[..., k] ** 2))))
+        assert_close32(vtarg[:, idx, k], o_vt[..., k], f"vtarg[{k}]", abs_=1e-5 * sk)
+    assert_close32(adv_s[:, idx], o_as, "adv_s", abs_=1e-5 * max(1.0, float(np.sqrt(np.mean(o_as ** 2)))))
+    assert np.array_equal(vtarg[:, 5], (r[:, 5] - v[:T, 5]) + v[:T, 5])    # all done: A = r - V, Vhat = A + V, in fp32
+    assert np.isfinite(vtarg).all() and np.isfinite(adv_s).all()
+
+
+def test_ppo_loss_grad_stress_shape_sampled(torch, binding):
+    """The loss call at the stress shape on one of four minibatches (blocks take several groups of cells in sequence
+    there): the statistics against float64 sums over every selected cell, the gradients against the oracle on a
+    sample of preferences (cells interact only through the advantage statistics, which are handed to the oracle's
+    formula through the normalised advantage)."""
+    cfg = STRESS
+    say(f"ppo_loss_grad {cfg.name}")
+    T, N, A, K, P = cfg.T, cfg.N, cfg.act_dim, cfg.K, cfg.P
+    mu, logsig, act, logp_old, adv_s, v, vtarg = loss_inputs(cfg, seed=41)
+    rows = (0, T, cfg.n_g // 4, cfg.n_g // 4)
+    ctx = binding.Context.from_config(cfg)
+    SENT = 3.25
+    dmu = torch.full(mu.shape, SENT, device="cuda")
+    dv = torch.full(v.shape, SENT, device="cuda")
+    dls = torch.full(logsig.shape, SENT, device="cuda")
+    stats = torch.zeros(8, device="cuda")
+    ws = torch.empty(ctx.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
+    ctx.ppo_loss_grad(rows, dev(mu), dev(logsig), A, dev(act), dev(logp_old), dev(adv_s), dev(v), dev(vtarg),
+                      cfg.clip_eps, 1, dmu, dls, dv, stats, ws)
+    torch.cuda.synchronize()
+    mask = orc.row_mask(cfg, rows, T)
+    B = float(mask.sum())
+    sel = adv_s.astype(np.float64)[mask]
+    mean, std = sel.mean(), np.sqrt(((sel - sel.mean()) ** 2).mean())
+    st = to_np(stats)
+    assert st[7] == B
+    assert_close32(st[4:6], np.array([mean, std]), "advantage statistics")
+    # the oracle on three preferences: a reduced problem with the same per-cell arithmetic, fed the normalised advantage
+    prefs = [0, P // 2 + 3, P - 1]
+    n_g = cfg.n_g
+    cols = np.concatenate([np.arange(p * n_g, (p + 1) * n_g) for p in prefs])
+    small = scaled(cfg, name="stress-sample", P=len(prefs), N=len(cols))
+    ahat = ((adv_s.astype(np.float64) - mean) / (std + 1e-8))
+    o_dmu, o_dls, o_dv, o_st = orc.ppo_loss_grad(small, rows, mu[:, cols], logsig[prefs], act[:, cols], logp_old[:, cols],
+                                                 ahat[:, cols], v[:, cols], vtarg[:, cols], cfg.clip_eps, False)
+    Bs = float(orc.row_mask(small, rows, T).sum())
+    g_dmu, g_dv = to_np(dmu), to_np(dv)
+    assert np.all(g_dmu[~mask] == SENT) and np.all(g_dv[~mask] == SENT)
+    m_s = mask[:, cols]
+    lp = orc.gaussian_logp(act[:, cols].astype(np.float64), mu[:, cols].astype(np.float64),
+                           np.repeat(logsig[prefs], n_g, axis=0)[None].astype(np.float64))
+    rho = np.exp(lp - logp_old[:, cols])
+    kink = (np.abs(rho - (1 + cfg.clip_eps)) < 1e-5) | (np.abs(rho - (1 - cfg.clip_eps)) < 1e-5) | (np.abs(ahat[:, cols]) < 1e-6)
+    # the oracle's gradients carry 1 / B of the reduced problem, the device's 1 / B of the whole selection
+    assert_close32(g_dmu[:, cols] * B, o_dmu * Bs, "dmu*B", mask=(m_s & ~kink)[..., None] & np.ones_like(o_dmu, bool))
+    assert_close32(g_dv[:, cols] * B, o_dv * Bs, "dv*B", mask=m_s[..., None] & np.ones_like(o_dv, bool))
+    if not kink[m_s].any():
+        assert_close32(to_np(dls)[prefs] * B, o_dls * Bs, "dlogsig*B", rel=1e-4, abs_=1e-5 * np.sqrt(Bs))
+    # losses and clip fraction over every selected cell, in float64 from the same formulas
+    gi = orc.env_pref_index(N, P)
+    lp_all = orc.gaussian_logp(act.astype(np.float64), mu.astype(np.float64), logsig[gi][None].astype(np.float64))
+    rho_all = np.exp(lp_all - logp_old)
+    surr = np.minimum(rho_all * ahat, np.clip(rho_all, 1 - cfg.clip_eps, 1 + cfg.clip_eps) * ahat)
+    L_pi = -surr[mask].mean()
+    L_V = ((v.astype(np.float64) - vtarg) ** 2).sum(-1)[mask].mean()
+    assert_close32(st[:2], np.array([L_pi, L_V]), "losses")
+    assert abs(st[2] - (np.abs(rho_all - 1) > cfg.clip_eps)[mask].mean()) < 1e-4
+    assert_close32(st[6:7], np.array([rho_all[mask].mean()]), "mean rho")
