@@ -1917,6 +1917,110 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ d
     }
 }
 
+// ---- first layer with a narrow observation (O <= 32) and few preferences ----------------------------------
+// dW_0(p)[o, i] = sum_m dZ_0[m, o] x[m, i] has W x O outputs and the whole selection as its contraction: as a tiled
+// GEMM it is two or three tiles per preference walking thousands of rows each (workload 2: 32 workgroups on 256 CUs).
+// It is the output layer's dW with the roles exchanged, so it takes the same streaming form: the observation rows
+// are gathered once into compact fp32 rows padded to 16 JB columns, a block takes one of n_split row ranges of one
+// preference and 128 columns of dZ_0, and the ranges are added in order by k_first_dw_final.
+template <typename T>
+__global__ __launch_bounds__(256) void k_gather_x_pad(const float* __restrict__ x, float* __restrict__ xz, int O, int OP,
+                                                     int M, RowMap rm) {
+    const int p = blockIdx.y;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)M * OP) return;
+    const int m = (int)(idx / OP), c = (int)(idx % OP);
+    xz[((int64_t)p * M + m) * OP + c] = c < O ? x[rm.row(p, m) * O + c] : 0.f;
+}
+
+template <typename T, int JB>
+__global__ __launch_bounds__(256) void k_first_bwd_dw(const float* __restrict__ xz, const T* __restrict__ dZ,
+                                                     float* __restrict__ pw, int W, int M, int n_split) {
+    constexpr int VE = Elems<T>::VE;
+    constexpr int HP = 128 + VE;
+    constexpr int CPR = 128 / VE;
+    constexpr int NPT = HB_ROWS * CPR / 256;
+    constexpr int OP = 16 * JB;
+    __shared__ float sdr[HB_ROWS][OP];
+    __shared__ __align__(16) T sh[HB_ROWS][HP];
+    const int p = blockIdx.z, rs = blockIdx.y, i0 = blockIdx.x * 128;
+    const int per = ((M + n_split - 1) / n_split + HB_ROWS - 1) / HB_ROWS * HB_ROWS;  // rows per range
+    const int m_lo = rs * per, m_hi = (m_lo + per < M) ? (m_lo + per) : M;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ln = lane & 15, kg = lane >> 4;
+    float4_t acc[JB][2][2];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) acc[jb][c][q] = float4_t{0.f, 0.f, 0.f, 0.f};
+    uint4 nxt[NPT];
+    auto fetch = [&](int m0) {
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {
+            const int idx = threadIdx.x + 256 * q, mm = idx / CPR, cc = (idx % CPR) * VE;
+            uint4 u = make_uint4(0, 0, 0, 0);
+            if (m0 + mm < m_hi && i0 + cc < W)
+                u = *reinterpret_cast<const uint4*>(dZ + ((int64_t)p * M + m0 + mm) * W + i0 + cc);
+            nxt[q] = u;
+        }
+    };
+    if (m_lo < m_hi) fetch(m_lo);
+    for (int m0 = m_lo; m0 < m_hi; m0 += HB_ROWS) {
+        __syncthreads();  // the previous tile has been multiplied
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            *reinterpret_cast<uint4*>(&sh[idx / CPR][(idx % CPR) * VE]) = nxt[q];
+        }
+        for (int idx = threadIdx.x; idx < HB_ROWS * (OP / 4); idx += 256) {
+            const int mm = idx / (OP / 4), q = idx % (OP / 4);
+            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m0 + mm < m_hi) d = *reinterpret_cast<const float4*>(xz + ((int64_t)p * M + m0 + mm) * OP + 4 * q);
+            sdr[mm][4 * q] = to_f(cvt<T>(d.x)); sdr[mm][4 * q + 1] = to_f(cvt<T>(d.y));  // GEMM input rounding
+            sdr[mm][4 * q + 2] = to_f(cvt<T>(d.z)); sdr[mm][4 * q + 3] = to_f(cvt<T>(d.w));
+        }
+        if (m0 + HB_ROWS < m_hi) fetch(m0 + HB_ROWS);
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
+            const int m = 4 * kk + kg;
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const float b = to_f(sh[m][32 * wave + 16 * c + ln]);  // dZ_0[m][column]
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+                    acc[jb][c][kk & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(sdr[m][16 * jb + ln], b, acc[jb][c][kk & 1], 0, 0, 0);
+            }
+        }
+    }
+    // lane holds column ln of observation components 16 jb + 4 kg + e
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int col = i0 + 32 * wave + 16 * c + ln;
+            if (col < W) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    pw[(((int64_t)p * n_split + rs) * OP + 16 * jb + 4 * kg + e) * W + col] = acc[jb][c][0][e] + acc[jb][c][1][e];
+            }
+        }
+}
+
+// dW_0(p)[o, i] = the ranges' partials [i][o] added in order
+__global__ __launch_bounds__(256) void k_first_dw_final(const float* __restrict__ pw, int n_split, int OP,
+                                                       float* __restrict__ dtheta_mat, int64_t mat_len, int64_t mat_off,
+                                                       int W, int O) {
+    const int p = blockIdx.y, idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= W * O) return;
+    const int o = idx / O, i = idx % O;
+    float v = 0.f;
+    for (int c = 0; c < n_split; ++c) v += pw[(((int64_t)p * n_split + c) * OP + i) * W + o];
+    dtheta_mat[(int64_t)p * mat_len + mat_off + idx] = v;
+}
+
 __global__ __launch_bounds__(256) void k_head_bwd_dw_final(const float* __restrict__ pw, const float* __restrict__ pb,
                                                           int n_chunk_w, int n_chunk_b, float* __restrict__ dtheta_mat,
                                                           float* __restrict__ dtheta_vec, int64_t mat_len,
@@ -1997,8 +2101,25 @@ static int64_t head_lo_elems(const morlax_ctx* c, const RowSel& rs) {
     const int64_t head = head_pw_elems(c) + (int64_t)c->d.P * ((rs.M + 255) / 256) * MORLAX_MAX_OUT;
     return align_up(colsum > head ? colsum : head, 64);
 }
+// the first layer's dW as a streaming split-K kernel: narrow observations and too few GEMM tiles to fill the chip
+static bool first_skinny(const morlax_ctx* c) {
+    return c->d.obs_dim <= 32 && ((c->d.width + 127) / 128) * c->d.P < 256;
+}
+static int first_split(const morlax_ctx* c, const RowSel& rs) {
+    const int tiles = ((c->d.width + 127) / 128) * c->d.P;
+    int n = (1024 + tiles - 1) / tiles;
+    const int cap = (rs.M + HB_ROWS - 1) / HB_ROWS;
+    n = n > 64 ? 64 : n;
+    n = n > cap ? cap : n;
+    return n < 1 ? 1 : n;
+}
+static int64_t first_skinny_elems(const morlax_ctx* c, const RowSel& rs) {  // padded rows, then the ranges' partials
+    if (!first_skinny(c)) return 0;
+    const int OP = c->d.obs_dim <= 16 ? 16 : 32;
+    return align_up((int64_t)c->d.P * rs.M * OP, 64) + align_up((int64_t)c->d.P * first_split(c, rs) * OP * c->d.width, 64);
+}
 static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
-    return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64);
+    return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64) + first_skinny_elems(c, rs);
 }
 static bool fused_fwd_dims_ok(const morlax_ctx* c) {
     return c->d.wdtype == 1 && c->d.width == FF_W && c->d.obs_dim % 64 == 0 && c->d.obs_dim <= FF_W &&
@@ -2229,6 +2350,19 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             h.e0_pstride = (int64_t)M * W; h.e1_pstride = 0; h.e2_pstride = 0;
             run_gemm(c, 2, h, P, s);
             n_part = h.tiles_m;  // row tiles of the kernel that ran (128 or 256 rows)
+        } else if (first_skinny(c)) {
+            const int OP = O <= 16 ? 16 : 32, ns = first_split(c, rs);
+            float* xz = part + head_lo_elems(c, rs) + align_up((int64_t)P * M * MORLAX_MAX_OUT, 64);
+            float* pw1 = xz + align_up((int64_t)P * M * OP, 64);
+            const int64_t n = (int64_t)M * OP;
+            GemmProf::Rec* r = prof_take(c, 4, 2.0 * W * (double)O * M * P);
+            if (r) (void)hipEventRecord(r->a, s);
+            k_gather_x_pad<T><<<dim3((unsigned)((n + 255) / 256), P), 256, 0, s>>>(x, xz, O, OP, M, rm);
+            const dim3 grid((W + 127) / 128, ns, P);
+            if (OP == 16) k_first_bwd_dw<T, 1><<<grid, 256, 0, s>>>(xz, dZbuf(0), pw1, W, M, ns);
+            else k_first_bwd_dw<T, 2><<<grid, 256, 0, s>>>(xz, dZbuf(0), pw1, W, M, ns);
+            k_first_dw_final<<<dim3((W * O + 255) / 256, P), 256, 0, s>>>(pw1, ns, OP, dtheta_mat, nd.mat_len, Ld.mat_off, W, O);
+            if (r) (void)hipEventRecord(r->b, s);
         } else if (use_x0(c)) {
             if constexpr (std::is_same<T, bf16_t>::value) {
                 // the rows gathered by the forward pass
