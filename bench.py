@@ -22,14 +22,14 @@ sys.path.insert(0, ROOT)
 
 # MI355X published dense peaks used for the roofline fractions
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
-# grouped-GEMM launch kinds -> kernel that serves them (bf16 at full size: the persistent direct-to-LDS
-# kernel; small or fp32 problems: k_gemm_dma / k_grouped_gemm)
+# grouped-GEMM launch kinds -> kernels that serve them (bf16 with enough tiles: the persistent direct-to-LDS kernel
+# k_gemm_pers; bf16 with few tiles: k_gemm_dma; fp32 and shapes that need masking: k_grouped_gemm)
 KERNEL_OF_KIND = {
-    "fwd_first": "k_grouped_gemm<x rows, W0(p), EpiFwd> forward, first layer",
-    "fwd_hidden": "k_gemm_pers<SRC_KCONTIG, SRC_KCONTIG, EpiFwd> forward, W x W layers (rollout + update)",
-    "dx_hidden": "k_gemm_pers<SRC_KCONTIG, SRC_KSTRIDED, EpiDx> dX, W x W layers",
-    "dw_hidden": "k_gemm_pers<SRC_KSTRIDED, SRC_KSTRIDED, EpiDw> dW, W x W layers",
-    "dw_first": "k_grouped_gemm<SRC_KSTRIDED, SRC_X_KSTRIDED, EpiDw> dW, first layer",
+    "fwd_first": "grouped GEMM <x rows, W0(p), EpiFwd> forward, first layer",
+    "fwd_hidden": "grouped GEMM <SRC_KCONTIG, SRC_KCONTIG, EpiFwd> forward, W x W layers (rollout + update)",
+    "dx_hidden": "grouped GEMM <SRC_KCONTIG, SRC_KSTRIDED, EpiDx> dX, W x W layers",
+    "dw_hidden": "grouped GEMM <SRC_KSTRIDED, SRC_KSTRIDED, EpiDw> dW, W x W layers (with the merge of a split contraction)",
+    "dw_first": "dW, first layer: grouped GEMM, or k_gather_x_pad + k_first_bwd_dw + k_first_dw_final for narrow observations",
     "fwd_fused": "k_mlp_fused_fwd: first layer and all W x W layers of a 128-row tile in one launch (rollout + update)",
 }
 

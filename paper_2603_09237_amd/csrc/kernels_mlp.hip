@@ -1570,6 +1570,12 @@ static GemmProf::Rec* prof_take(const morlax_ctx* c, int kind, double flops) {
     return r;
 }
 
+// the launches since the last record's end belong to it too (a merge after a split GEMM)
+static void prof_extend(const morlax_ctx* c, hipStream_t s) {
+    GemmProf* pr = c->prof;
+    if (pr && pr->on && pr->used > 0) (void)hipEventRecord(pr->recs[pr->used - 1].b, s);
+}
+
 // The direct-to-LDS kernel serves bf16 GEMMs of compact operands whose contraction length is a multiple
 // of 32 and whose addresses are 16-byte aligned; everything else runs k_grouped_gemm.
 template <int KIND>
@@ -1917,6 +1923,27 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ d
     }
 }
 
+// ---- dW of a W x W layer with few preferences: contraction split into ranges ---------------------------------
+// dW_l(p) has (W/128)^2 tiles per preference and the whole selection as its contraction; with few preferences that
+// is a few dozen workgroups walking thousands of rows each.  The selection is cut into S equal ranges that run as
+// P S groups of the same grouped GEMM into partial matrices, and the ranges are added in order.
+#ifndef DW_SPLIT_TARGET
+#define DW_SPLIT_TARGET 512
+#endif
+__global__ __launch_bounds__(256) void k_dw_split_final(const float* __restrict__ pw, int S, int64_t WW,
+                                                       float* __restrict__ dtheta_mat, int64_t mat_len, int64_t mat_off) {
+    const int p = blockIdx.y;
+    const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i4 >= WW) return;
+    float4 v = *reinterpret_cast<const float4*>(pw + (int64_t)p * S * WW + i4);
+    for (int c = 1; c < S; ++c) {
+        const float4 u = *reinterpret_cast<const float4*>(pw + ((int64_t)p * S + c) * WW + i4);
+        v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    // W is a multiple of 16, so every matrix starts on a 16-byte boundary of the row
+    *reinterpret_cast<float4*>(dtheta_mat + (int64_t)p * mat_len + mat_off + i4) = v;
+}
+
 // ---- first layer with a narrow observation (O <= 32) and few preferences ----------------------------------
 // dW_0(p)[o, i] = sum_m dZ_0[m, o] x[m, i] has W x O outputs and the whole selection as its contraction: as a tiled
 // GEMM it is two or three tiles per preference walking thousands of rows each (workload 2: 32 workgroups on 256 CUs).
@@ -2118,8 +2145,24 @@ static int64_t first_skinny_elems(const morlax_ctx* c, const RowSel& rs) {  // p
     const int OP = c->d.obs_dim <= 16 ? 16 : 32;
     return align_up((int64_t)c->d.P * rs.M * OP, 64) + align_up((int64_t)c->d.P * first_split(c, rs) * OP * c->d.width, 64);
 }
+// ranges the contraction of a hidden layer's dW is cut into (1 = the plain grouped GEMM)
+static int dw_split(const morlax_ctx* c, const RowSel& rs) {
+    const int t = (c->d.width + 127) / 128, tiles = t * t * c->d.P;
+    int S = 1;
+    while (S < 16 && tiles * S < DW_SPLIT_TARGET && rs.M % (2 * S * 64) == 0 && rs.M / (2 * S) >= 256) S *= 2;
+    return S;
+}
+// room for the partial matrices: sized by the most ranges any selection of at most this many rows can be cut
+// into, so that the workspace of a selection also serves every smaller one
+static int64_t dw_split_elems(const morlax_ctx* c, const RowSel& rs) {
+    const int t = (c->d.width + 127) / 128, tiles = t * t * c->d.P;
+    int S = 1;
+    while (S < 16 && tiles * S < DW_SPLIT_TARGET && rs.M / (2 * S) >= 256) S *= 2;
+    return S > 1 ? align_up((int64_t)c->d.P * S * c->d.width * c->d.width, 64) : 0;
+}
 static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
-    return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64) + first_skinny_elems(c, rs);
+    return head_lo_elems(c, rs) + align_up((int64_t)c->d.P * rs.M * MORLAX_MAX_OUT, 64) + first_skinny_elems(c, rs) +
+           dw_split_elems(c, rs);
 }
 static bool fused_fwd_dims_ok(const morlax_ctx* c) {
     return c->d.wdtype == 1 && c->d.width == FF_W && c->d.obs_dim % 64 == 0 && c->d.obs_dim <= FF_W &&
@@ -2341,7 +2384,21 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
             g.b.base = Hbuf(l - 1); g.b.ld = W; g.b.rows = W; g.b.kdim = M; g.b.rm = rm;
             g.a_pstride = (int64_t)M * W; g.b_pstride = (int64_t)M * W;
             g.epi = ew; g.e0_pstride = nd.mat_len; g.e1_pstride = 0; g.e2_pstride = 0;
-            run_gemm(c, 3, g, P, s);
+            const int S = dw_split(c, rs);
+            if (S > 1) {
+                float* pws = part + head_lo_elems(c, rs) + align_up((int64_t)P * M * MORLAX_MAX_OUT, 64) +
+                             first_skinny_elems(c, rs);
+                const int64_t WW = (int64_t)W * W;
+                g.a.kdim = g.b.kdim = M / S;
+                g.a_pstride = g.b_pstride = (int64_t)(M / S) * W;
+                g.epi.dW = pws; g.epi.ld = W; g.e0_pstride = WW;
+                run_gemm(c, 3, g, P * S, s);
+                k_dw_split_final<<<dim3((unsigned)((WW / 4 + 255) / 256), P), 256, 0, s>>>(pws, S, WW, dtheta_mat, nd.mat_len,
+                                                                                        Ld.mat_off);
+                prof_extend(c, s);
+            } else {
+                run_gemm(c, 3, g, P, s);
+            }
             GemmArgs<T, SRC_KCONTIG, SRC_KSTRIDED, EpiDx<T>, true, GEMM_NCH> h;
             h.a.base = dZbuf(l); h.a.ld = W; h.a.rows = M; h.a.kdim = W; h.a.rm = rm;
             h.b.base = theta_mat + Ld.mat_off; h.b.ld = W; h.b.rows = W; h.b.kdim = W; h.b.rm = rm;

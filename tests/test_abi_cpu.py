@@ -46,6 +46,23 @@ def test_layout_queries_match_oracle_and_generator(lib):
         ctx.close()
 
 
+def test_workspace_of_a_selection_covers_every_smaller_one(lib):
+    """A caller sizes one buffer for the whole tensor and reuses it for time ranges and minibatches, so the
+    size must not shrink when rows are added (the split and padded scratch regions depend on the row count)."""
+    for i in (1, 2, 3, 4):
+        cfg = configs.CONFIGS[i]
+        ctx = binding.Context.from_config(cfg)
+        whole = ctx.workspace_bytes()
+        prev = 0
+        for t_cnt in (1, 2, cfg.T // 2, cfg.T - 1, cfg.T, cfg.T + 1):
+            for j_cnt in (1, max(cfg.n_g // 4, 1), max(cfg.n_g // 2, 1), cfg.n_g):
+                b = ctx.workspace_bytes((0, t_cnt, 0, j_cnt))
+                assert 0 < b <= whole, (cfg.name, t_cnt, j_cnt, b, whole)
+            assert b >= prev, (cfg.name, t_cnt)  # full groups, growing time range
+            prev = b
+        ctx.close()
+
+
 @pytest.mark.parametrize("over,code", [
     (dict(P=1), binding.ERR_SHAPE), (dict(P=3), binding.ERR_SHAPE), (dict(K=0), binding.ERR_SHAPE),
     (dict(T=0), binding.ERR_SHAPE), (dict(rank=-2), binding.ERR_SHAPE), (dict(K=17), binding.ERR_UNSUPPORTED),
