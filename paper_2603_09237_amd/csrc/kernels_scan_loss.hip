@@ -30,7 +30,9 @@ void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s) {
 // The recursion over t, A_t = cut_t ? a_t : a_t + gl A_{t+1} (a_t = r_t - V_t at an episode end, else the
 // TD error; cut_t = episode end or time limit), is a chain of affine maps, so the time axis is split as
 // well: the LW = ceil(F / 64) waves that cover a row exist NC times, copy c taking chunk c of up to GAE_CH
-// steps.  A wave requests all loads of its chunk at once, runs the recursion from zero (A'_t), and posts
+// steps.  A wave requests all loads of its chunk at once -- unconditionally, with clamped addresses, so that they
+// leave back to back, and one group of chunks ahead: the next group's values arrive while this one is finished,
+// scalarised and written --, runs the recursion from zero (A'_t), and posts
 // the value at its first step and whether its chunk holds a cut.  After a barrier it folds the posts of
 // the later chunks into the advantage that enters its own chunk, x, and finishes
 // A_t = (a cut between t and the chunk's end) ? A'_t : A'_t + gl^(steps to the chunk's end) x.
@@ -39,8 +41,12 @@ void launch_env_pref_index(const morlax_ctx* c, int32_t* out, hipStream_t s) {
 // The scalarisation sum_k w_k A_k goes through LDS: every lane leaves w_k A_t there, and after a second
 // barrier the workgroup adds the K terms of a cell in ascending k and writes adv_s as 128-byte runs.
 #define GAE_E 32
-template <int GAE_CH>
-__global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
+// results that this kernel does not read again leave with non-temporal stores (measured: +4 % bandwidth on the
+// T = 256, N = 65536 shape; the same mark on the loads of r and v gained nothing and cost 5 % at workload 5)
+__device__ inline void st_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
+
+template <int GAE_CH, bool TRUNC>
+__global__ __launch_bounds__(768, 6) void k_vec_gae(const float* __restrict__ r, const float* __restrict__ v,
                                                      const uint8_t* __restrict__ done,
                                                      const uint8_t* __restrict__ trunc, const float* __restrict__ w,
                                                      float gamma, float gl, float* __restrict__ adv_vec,
@@ -63,34 +69,69 @@ __global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r
     const int n0 = blk * GAE_E, n = n0 + e;
     const bool live = (f < F) && (n < N);
     const int64_t NK = (int64_t)N * K;
-    const int64_t idx = (int64_t)n0 * K + f;
     const float wk = live ? w[(n / n_g) * K + k] : 0.f;
     float gl_ch = 1.f;  // gl^ch: what a whole chunk without a cut multiplies the entering advantage by
     for (int m = 0; m < ch; ++m) gl_ch *= gl;
 
     const int n_chunks = (T + ch - 1) / ch, n_groups = (n_chunks + NC - 1) / NC;
+    // the loads of a group's chunk: requested while the group before it (later in time) is finished and written
+    float rt_n[GAE_CH], vt_n[GAE_CH], vnext_n;
+    uint32_t cutm_n, donem_n;
+    // addresses = a wave-uniform row start (scalar registers) + the lane's pair or environment
+    const int64_t pair0 = (int64_t)n0 * K;
+    // Every load is issued whatever the lane or the step: rows past the chunk repeat the horizon's last row and idle
+    // lanes read the block's first pair, so the requests of a chunk leave back to back with no branch between them;
+    // what they return is discarded below.
+    // (a scalar row start plus an unsigned 32-bit byte offset of the lane: one address register per lane)
+    const uint32_t fs = live ? 4u * f : 0u, es = live ? e : 0u;
+    auto at = [](const float* row, uint32_t byte_off) {
+        return reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + byte_off);
+    };
+    auto request = [&](int g) {
+        const int t0 = (NC * g + cw) * ch;
+        int len = T - t0;
+        len = len < 0 ? 0 : (len > ch ? ch : len);
+        uint32_t dn[GAE_CH], tr[GAE_CH];
+#pragma unroll
+        for (int u = 0; u < GAE_CH; ++u) {  // the bytes first: the masks below then wait for these loads only
+            const int t = t0 + u < T ? t0 + u : T - 1;
+            dn[u] = (done + (int64_t)t * N + n0)[es];
+            tr[u] = TRUNC ? (trunc + (int64_t)t * N + n0)[es] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < GAE_CH; ++u) {
+            const int t = t0 + u < T ? t0 + u : T - 1;
+            rt_n[u] = *at(r + ((int64_t)t * NK + pair0), fs);
+            vt_n[u] = *at(v + ((int64_t)t * NK + pair0), fs);
+        }
+        // V after the chunk's last step (exists up to t = T)
+        const int tl = t0 + len < T ? t0 + len : T;
+        vnext_n = *at(v + ((int64_t)tl * NK + pair0), fs);
+        cutm_n = 0;
+        donem_n = 0;
+#pragma unroll
+        for (int u = 0; u < GAE_CH; ++u) {
+            const bool ok = live && u < len;
+            donem_n |= ((ok && dn[u] && !tr[u]) ? 1u : 0u) << u;  // a time limit keeps the bootstrap whatever `done` says
+            cutm_n |= ((ok && (dn[u] | tr[u])) ? 1u : 0u) << u;
+        }
+    };
+    request(n_groups - 1);
     for (int g = n_groups - 1, it = 0; g >= 0; --g, ++it) {
         const int buf = it & 1;  // posts and carries alternate between two slots
         const int c = NC * g + cw;
         const int t0 = c * ch;
         int len = T - t0;
         len = len < 0 ? 0 : (len > ch ? ch : len);
-        // loads of the whole chunk
-        float rt[GAE_CH], vt[GAE_CH + 1];
-        uint32_t cutm = 0, donem = 0;
+        float rt[GAE_CH], vt[GAE_CH];
 #pragma unroll
         for (int u = 0; u < GAE_CH; ++u) {
             const bool ok = live && u < len;
-            const int64_t o = (int64_t)(t0 + u) * NK + idx;
-            rt[u] = ok ? r[o] : 0.f;
-            vt[u] = ok ? v[o] : 0.f;
-            const uint32_t dn = ok ? done[(int64_t)(t0 + u) * N + n] : 0u;
-            const uint32_t tr = (ok && trunc) ? trunc[(int64_t)(t0 + u) * N + n] : 0u;
-            donem |= ((dn && !tr) ? 1u : 0u) << u;  // a time limit keeps the bootstrap whatever `done` says
-            cutm |= ((dn | tr) ? 1u : 0u) << u;
+            rt[u] = ok ? rt_n[u] : 0.f;
+            vt[u] = ok ? vt_n[u] : 0.f;
         }
-        // V after the chunk's last step (exists up to t = T)
-        float vnext = (live && len > 0) ? v[(int64_t)(t0 + len) * NK + idx] : 0.f;
+        const float vnext = (live && len > 0) ? vnext_n : 0.f;
+        const uint32_t cutm = cutm_n, donem = donem_n;
         // chunk-local recursion from zero, last step first
         float ap[GAE_CH];
         float acc = 0.f;
@@ -110,6 +151,7 @@ __global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r
             post_cut[buf][cw * F + f] = (uint8_t)(cutm != 0);
         }
         __syncthreads();  // (also: every wave is done reading the previous group's scalarisation terms)
+        if (g > 0) request(g - 1);
         // advantage entering this chunk: later chunks of the group folded onto the group's carry-in
         float x = (it == 0 || f >= F) ? 0.f : carry[buf ^ 1][f];
         for (int j = NC - 1; j > cw; --j) {
@@ -140,9 +182,9 @@ __global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r
                 const float a = ap[u];
                 if (f < F) sc[(cw * GAE_CH + u) * F + f] = wk * a;
                 if (live) {
-                    const int64_t o = (int64_t)(t0 + u) * NK + idx;
-                    if (adv_vec) adv_vec[o] = a;
-                    vtarg[o] = a + vt[u];
+                    const int64_t o = (int64_t)(t0 + u) * NK + pair0;  // wave-uniform
+                    if (adv_vec) st_stream(adv_vec + o + f, a);
+                    st_stream(vtarg + o + f, a + vt[u]);
                 }
             }
         }
@@ -156,7 +198,7 @@ __global__ __launch_bounds__(1024, 8) void k_vec_gae(const float* __restrict__ r
                 const float* term = sc + cu * F + ee * K;
                 float tot = term[0];
                 for (int j = 1; j < K; ++j) tot += term[j];
-                adv_s[(int64_t)t * N + n0 + ee] = tot;
+                st_stream(adv_s + (int64_t)t * N + n0 + ee, tot);
             }
         }
     }
@@ -167,19 +209,24 @@ void launch_vec_gae(const morlax_ctx* c, const float* r, const float* v, const u
                     float* vtarg, float* adv_s, hipStream_t s) {
     const int K = c->d.K, N = c->d.N, T = c->d.T;
     const int blocks = (N + GAE_E - 1) / GAE_E;
-    // chunks of up to eight steps (registers: at most 64 per lane, eight waves per SIMD); the chunk copies of a
-    // workgroup: the largest power of two that keeps it within 16 waves, at most eight (K = 6: four copies of three
+    // chunks of up to eight steps; a workgroup of at most twelve waves (two or three of them share a CU at six waves
+    // and 80 registers per SIMD: the chunk being finished and the next one's loads are both held in registers); the
+    // chunk copies: the largest power of two that keeps it within that, at most eight (K = 6: four copies of three
     // waves; five measured slower at T = 64 and T = 256), then no more than evens out the groups of chunks
     constexpr int CH = 8;
     const int LW = (GAE_E * K + WAVE - 1) / WAVE;
     int NC = 8;
-    while (NC * LW > 16) NC >>= 1;
+    while (NC * LW > 12) NC >>= 1;
     int ch = (T + NC - 1) / NC;
     ch = ch > CH ? CH : ch;
     const int n_chunks = (T + ch - 1) / ch, n_groups = (n_chunks + NC - 1) / NC;
     NC = (n_chunks + n_groups - 1) / n_groups;
-    k_vec_gae<CH><<<blocks, WAVE * LW * NC, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg, adv_s,
-                                                   T, N, K, c->n_g, ch, LW, NC);
+    if (trunc)
+        k_vec_gae<CH, true><<<blocks, WAVE * LW * NC, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg,
+                                                             adv_s, T, N, K, c->n_g, ch, LW, NC);
+    else
+        k_vec_gae<CH, false><<<blocks, WAVE * LW * NC, 0, s>>>(r, v, done, trunc, w, gamma, gamma * lambda, adv_vec, vtarg,
+                                                              adv_s, T, N, K, c->n_g, ch, LW, NC);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -337,7 +384,8 @@ struct CellRuns {
 };
 
 // V4: every run starts on a 16-byte boundary and holds a multiple of four floats (the launcher checks the
-// selection), so a lane moves 16 bytes at a time
+// selection), so a lane moves 16 bytes at a time.  The loads are marked non-temporal (each byte is read once;
+// +6 % bandwidth measured on the T = 256, N = 65536 shape; the same mark on the stores gained nothing).
 template <bool V4, int NT>
 __device__ inline void runs_to_lds(const CellRuns& cr, const float* __restrict__ X, int C, uint32_t lds_addr) {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -350,13 +398,13 @@ __device__ inline void runs_to_lds(const CellRuns& cr, const float* __restrict__
             const int count = ncell * C / 4;
             for (int c0 = wave * 64; c0 < count; c0 += NT)
                 if (c0 + lane < count)
-                    dma16(src + 4 * c0, (uint32_t)lane * 16u,
+                    dma16_nt(src + 4 * c0, (uint32_t)lane * 16u,
                           __builtin_amdgcn_readfirstlane(lds_addr + (uint32_t)(cell0 * C + 4 * c0) * 4u));
         } else {
             const int count = ncell * C;
             for (int c0 = wave * 64; c0 < count; c0 += NT)
                 if (c0 + lane < count)
-                    dma4(src + c0, (uint32_t)lane * 4u,
+                    dma4_nt(src + c0, (uint32_t)lane * 4u,
                          __builtin_amdgcn_readfirstlane(lds_addr + (uint32_t)(cell0 * C + c0) * 4u));
         }
     }

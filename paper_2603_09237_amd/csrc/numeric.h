@@ -67,5 +67,16 @@ __device__ inline void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr)
                  "s"(uniform_addr(sbase))
                  : "memory");
 }
+// the same, marked non-temporal: for tensors a kernel reads once
+__device__ inline void dma16_nt(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_addr), "v"(voff),
+                 "s"(uniform_addr(sbase))
+                 : "memory");
+}
+__device__ inline void dma4_nt(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2 nt" ::"s"(lds_addr), "v"(voff),
+                 "s"(uniform_addr(sbase))
+                 : "memory");
+}
 template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
