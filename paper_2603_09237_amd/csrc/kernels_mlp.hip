@@ -1401,9 +1401,10 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
                 unsigned char* hrow = dlds + olr * 1024;
                 unsigned char* patch = dlds + FF_ACT_BYTES + wave * 4096;
                 gfix16_t* Gl = SAVE ? a.G + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
+                bf16_t* Hl = SAVE ? a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    uint4 gq[4];
+                    uint4 gq[4], hq[4];
 #pragma unroll
                     for (int o = 0; o < 4; ++o) {
                         const int j = o >> 1, h = o & 1;
@@ -1411,43 +1412,37 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
 #pragma unroll
                         for (int u = 0; u < 8; ++u) act_pair<ACT>(acc[i][j][8 * h + u], v[u], g[u]);
                         const int cc = 8 * wave + 4 * j + 2 * h + olg;
-                        *reinterpret_cast<uint4*>(hrow + i * 32768 + ((cc ^ ox) * 16)) = pack_chunk<bf16_t>(v);
+                        hq[o] = pack_chunk<bf16_t>(v);
+                        *reinterpret_cast<uint4*>(hrow + i * 32768 + ((cc ^ ox) * 16)) = hq[o];
                         if (SAVE) gq[o] = pack8(g, (const gfix16_t*)nullptr).lo;
                     }
-                    if (SAVE) {  // act'(z) leaves through the wave's patch as whole 128-byte row segments
+                    // act'(z) and h leave through the wave's patch as whole 128-byte row segments, row block by row
+                    // block between the epilogue's arithmetic (h read back from the tile after the closing barrier and
+                    // stored as whole rows cost 1 ms more per step of workload 5: those stores sat in front of the
+                    // next layer's first requests)
+                    if (SAVE) {
 #pragma unroll
-                        for (int o = 0; o < 4; ++o) {
-                            const int cch = 4 * (o >> 1) + 2 * (o & 1) + olg;
-                            *reinterpret_cast<uint4*>(patch + olr * 128 + ((cch ^ (olr & 7)) * 16)) = gq[o];
-                        }
-                        __builtin_amdgcn_wave_barrier();
+                        for (int arr = 0; arr < 2; ++arr) {
 #pragma unroll
-                        for (int it = 0; it < 4; ++it) {
-                            const int prow = it * 8 + (ol >> 3), pc = ol & 7;
-                            const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
-                            const int gr = 32 * i + prow;
-                            if (gr < rows) *reinterpret_cast<uint4*>(Gl + (int64_t)gr * FF_W + pc * 8) = u;
+                            for (int o = 0; o < 4; ++o) {
+                                const int cch = 4 * (o >> 1) + 2 * (o & 1) + olg;
+                                *reinterpret_cast<uint4*>(patch + olr * 128 + ((cch ^ (olr & 7)) * 16)) = arr ? hq[o] : gq[o];
+                            }
+                            __builtin_amdgcn_wave_barrier();
+                            char* dst = arr ? reinterpret_cast<char*>(Hl) : reinterpret_cast<char*>(Gl);
+#pragma unroll
+                            for (int it = 0; it < 4; ++it) {
+                                const int prow = it * 8 + (ol >> 3), pc = ol & 7;
+                                const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
+                                const int gr = 32 * i + prow;
+                                if (gr < rows) *reinterpret_cast<uint4*>(dst + ((int64_t)gr * FF_W + pc * 8) * 2) = u;
+                            }
+                            __builtin_amdgcn_wave_barrier();
                         }
-                        __builtin_amdgcn_wave_barrier();
                     }
                 }
             }
             __syncthreads();  // the layer's output is complete in LDS
-            if (SAVE) {  // h to memory, one whole row per wave and store
-                const int ol = opaque(lane);
-                bf16_t* Hl = a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + 8 * ol;
-                uint4 hv[16];
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const int r = 8 * q + wave;
-                    hv[q] = *reinterpret_cast<const uint4*>(dlds + r * 1024 + ((ol ^ (r & 15)) * 16));
-                }
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const int r = 8 * q + wave;
-                    if (r < rows) *reinterpret_cast<uint4*>(Hl + (int64_t)r * FF_W) = hv[q];
-                }
-            }
             if (more) init_acc(bnext);
         }
 
