@@ -1840,11 +1840,20 @@ __global__ __launch_bounds__(256) void k_head_bwd_dz(const float* __restrict__ d
     }
 }
 
+// Transposing 8-byte LDS read: the 16 lanes of a group address the 64-bit words of a 4 x 16 block of 16-bit values
+// -- lane 4 e + c the word of contraction index e that holds columns 4 c .. 4 c + 3 -- and lane b of the group
+// receives the four contraction indices of column b: the B operand of a 16x16x16 MFMA read from a row-major tile.
+template <typename E>
+__device__ inline short4_t lds_tr4(const E* word) {
+    typedef __attribute__((address_space(3))) short4_t lds_s4;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(word));
+}
+
 // dW_L(p)[j, i] = sum_m dz_L[m, j] h_{L-1}[m, i] in two stages.  Stage 1: a block takes one of HB_SPLIT row
 // ranges of one preference and 128 columns, and walks its rows 128 at a time: the dz rows (rounded to the
 // GEMM input type) and the h tile sit in LDS, the next h tile is already on its way in registers; wave w
-// multiplies dz^T [16 x 128] by h [128 x columns 32 w .. 32 w + 31] with fp32 16x16x4 MFMAs (bf16 h is
-// widened on the way out of LDS, which is exact).  Partials go to pw[p][range][j][i]; stage 2
+// multiplies dz^T [16 x 128] by h [128 x columns 32 w .. 32 w + 31]: bf16 networks with 16x16x16 bf16 MFMAs (dz^T
+// staged with the contraction contiguous, h read through transposing LDS reads), fp32 ones with 16x16x4 MFMAs.  Partials go to pw[p][range][j][i]; stage 2
 // (k_head_bwd_dw_final) adds the ranges, and the bias partials of k_head_dzh, in order.
 #define HB_ROWS 128
 #define HB_SPLIT 4
@@ -1855,7 +1864,9 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ d
     constexpr int HP = 128 + VE;                           // h tile pitch in elements (16 bytes of padding)
     constexpr int CPR = 128 / VE;                          // 16-byte pieces per tile row
     constexpr int NPT = HB_ROWS * CPR / 256;               // pieces per thread
-    __shared__ float sdr[HB_ROWS][MORLAX_MAX_OUT];
+    constexpr bool kBf = std::is_same<T, bf16_t>::value;
+    __shared__ __align__(16) float sdr[kBf ? 1 : HB_ROWS][MORLAX_MAX_OUT];        // fp32: dz rows as they lie
+    __shared__ __align__(16) bf16_t sdT[kBf ? MORLAX_MAX_OUT : 1][HB_ROWS + 8];  // bf16: dz^T, contraction contiguous
     __shared__ __align__(16) T sh[HB_ROWS][HP];
     const int p = blockIdx.z, rs = blockIdx.y, i0 = blockIdx.x * 128;
     const int per = ((M + HB_SPLIT - 1) / HB_SPLIT + HB_ROWS - 1) / HB_ROWS * HB_ROWS;  // rows per range
@@ -1890,19 +1901,36 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw(const float* __restrict__ d
             const int mm = idx / (MORLAX_MAX_OUT / 4), q = idx % (MORLAX_MAX_OUT / 4);
             float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
             if (m0 + mm < m_hi) d = *reinterpret_cast<const float4*>(dzh + ((int64_t)p * M + m0 + mm) * MORLAX_MAX_OUT + 4 * q);
-            sdr[mm][4 * q] = to_f(cvt<T>(d.x)); sdr[mm][4 * q + 1] = to_f(cvt<T>(d.y));
-            sdr[mm][4 * q + 2] = to_f(cvt<T>(d.z)); sdr[mm][4 * q + 3] = to_f(cvt<T>(d.w));
+            if constexpr (kBf) {
+                sdT[4 * q][mm] = cvt<T>(d.x); sdT[4 * q + 1][mm] = cvt<T>(d.y);
+                sdT[4 * q + 2][mm] = cvt<T>(d.z); sdT[4 * q + 3][mm] = cvt<T>(d.w);
+            } else {
+                sdr[mm][4 * q] = to_f(cvt<T>(d.x)); sdr[mm][4 * q + 1] = to_f(cvt<T>(d.y));
+                sdr[mm][4 * q + 2] = to_f(cvt<T>(d.z)); sdr[mm][4 * q + 3] = to_f(cvt<T>(d.w));
+            }
         }
         if (m0 + HB_ROWS < m_hi) fetch(m0 + HB_ROWS);
         __syncthreads();
+        if constexpr (kBf) {
+            // both operands are bf16 values: 16x16x16 bf16 MFMAs, eight times the fp32 rate for the same sums
 #pragma unroll
-        for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
-            const int m = 4 * kk + kg;
-            const float a = sdr[m][ln];                              // dz^T[j = ln][m]
+            for (int ks = 0; ks < HB_ROWS / 16; ++ks) {
+                const short4_t a = *reinterpret_cast<const short4_t*>(&sdT[ln][16 * ks + 4 * kg]);  // dz^T[j = ln][4 m]
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const float b = to_f(sh[m][32 * wave + 16 * c + ln]);  // h[m][column]
-                acc[c][kk & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[c][kk & 1], 0, 0, 0);
+                for (int c = 0; c < 2; ++c)
+                    acc[c][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                        a, lds_tr4(&sh[16 * ks + 4 * kg + (ln >> 2)][32 * wave + 16 * c + 4 * (ln & 3)]), acc[c][ks & 1], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
+                const int m = 4 * kk + kg;
+                const float a = sdr[m][ln];                              // dz^T[j = ln][m]
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const float b = to_f(sh[m][32 * wave + 16 * c + ln]);  // h[m][column]
+                    acc[c][kk & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[c][kk & 1], 0, 0, 0);
+                }
             }
         }
     }
@@ -1963,7 +1991,9 @@ __global__ __launch_bounds__(256) void k_first_bwd_dw(const float* __restrict__ 
     constexpr int CPR = 128 / VE;
     constexpr int NPT = HB_ROWS * CPR / 256;
     constexpr int OP = 16 * JB;
-    __shared__ float sdr[HB_ROWS][OP];
+    constexpr bool kBf = std::is_same<T, bf16_t>::value;
+    __shared__ __align__(16) float sdr[kBf ? 1 : HB_ROWS][OP];        // fp32: observation rows as they lie
+    __shared__ __align__(16) bf16_t sdT[kBf ? OP : 1][HB_ROWS + 8];  // bf16: x^T, contraction contiguous
     __shared__ __align__(16) T sh[HB_ROWS][HP];
     const int p = blockIdx.z, rs = blockIdx.y, i0 = blockIdx.x * 128;
     const int per = ((M + n_split - 1) / n_split + HB_ROWS - 1) / HB_ROWS * HB_ROWS;  // rows per range
@@ -2000,20 +2030,39 @@ __global__ __launch_bounds__(256) void k_first_bwd_dw(const float* __restrict__ 
             const int mm = idx / (OP / 4), q = idx % (OP / 4);
             float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
             if (m0 + mm < m_hi) d = *reinterpret_cast<const float4*>(xz + ((int64_t)p * M + m0 + mm) * OP + 4 * q);
-            sdr[mm][4 * q] = to_f(cvt<T>(d.x)); sdr[mm][4 * q + 1] = to_f(cvt<T>(d.y));  // GEMM input rounding
-            sdr[mm][4 * q + 2] = to_f(cvt<T>(d.z)); sdr[mm][4 * q + 3] = to_f(cvt<T>(d.w));
+            if constexpr (kBf) {  // GEMM input rounding
+                sdT[4 * q][mm] = cvt<T>(d.x); sdT[4 * q + 1][mm] = cvt<T>(d.y);
+                sdT[4 * q + 2][mm] = cvt<T>(d.z); sdT[4 * q + 3][mm] = cvt<T>(d.w);
+            } else {
+                sdr[mm][4 * q] = to_f(cvt<T>(d.x)); sdr[mm][4 * q + 1] = to_f(cvt<T>(d.y));
+                sdr[mm][4 * q + 2] = to_f(cvt<T>(d.z)); sdr[mm][4 * q + 3] = to_f(cvt<T>(d.w));
+            }
         }
         if (m0 + HB_ROWS < m_hi) fetch(m0 + HB_ROWS);
         __syncthreads();
+        if constexpr (kBf) {
 #pragma unroll
-        for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
-            const int m = 4 * kk + kg;
+            for (int ks = 0; ks < HB_ROWS / 16; ++ks) {
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const float b = to_f(sh[m][32 * wave + 16 * c + ln]);  // dZ_0[m][column]
+                for (int c = 0; c < 2; ++c) {
+                    const short4_t b = lds_tr4(&sh[16 * ks + 4 * kg + (ln >> 2)][32 * wave + 16 * c + 4 * (ln & 3)]);
 #pragma unroll
-                for (int jb = 0; jb < JB; ++jb)
-                    acc[jb][c][kk & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(sdr[m][16 * jb + ln], b, acc[jb][c][kk & 1], 0, 0, 0);
+                    for (int jb = 0; jb < JB; ++jb)
+                        acc[jb][c][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                            *reinterpret_cast<const short4_t*>(&sdT[16 * jb + ln][16 * ks + 4 * kg]), b, acc[jb][c][ks & 1], 0, 0, 0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < HB_ROWS / 4; ++kk) {
+                const int m = 4 * kk + kg;
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const float b = to_f(sh[m][32 * wave + 16 * c + ln]);  // dZ_0[m][column]
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb)
+                        acc[jb][c][kk & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(sdr[m][16 * jb + ln], b, acc[jb][c][kk & 1], 0, 0, 0);
+                }
             }
         }
     }
