@@ -1967,6 +1967,88 @@ __global__ __launch_bounds__(256) void k_dw_split_final(const float* __restrict_
     *reinterpret_cast<float4*>(dtheta_mat + (int64_t)p * mat_len + mat_off + i4) = v;
 }
 
+// ---- forward of the first layer with a narrow observation (O <= 32) ---------------------------------------
+// h = act(x W0(p)^T + b0(p)) is, per output, an inner product of O terms: too short to fill GEMM tiles (the tiled
+// kernel pads the contraction to 32 and loads the odd-width rows element by element) and bound by the stores of h
+// and act'(z).  A block of 256 threads takes FN_ROWS rows of one preference with W0(p) in LDS, transposed to
+// [i][o] in fp32 (exact for bf16 weights), and the rows' observations rounded to the network's type as the GEMM
+// rounds them; a thread owns eight consecutive outputs of FN_ROWS / RPT rows, walks the contraction once with its
+// eight weights of the step in registers, and stores 16- or 32-byte pieces that the threads of a row join to whole
+// rows.  Sums run in ascending i in fp32, as one accumulator per output.
+#define FN_ROWS 64
+template <typename T, int ACT, bool SAVE>
+__global__ __launch_bounds__(256) void k_first_fwd_narrow(const float* __restrict__ x, const T* __restrict__ theta_mat,
+                                                         const float* __restrict__ theta_vec, int64_t mat_len,
+                                                         int64_t vec_len, int64_t mat_off, int64_t vec_off, int O, int W,
+                                                         int M, RowMap rm, T* __restrict__ H,
+                                                         typename GradT<T>::type* __restrict__ G) {
+    extern __shared__ __align__(16) float fn_lds[];
+    const int WP = W + 4;  // pitch of a row of W0^T: keeps 16-byte alignment, shifts the banks from row to row
+    float* sw = fn_lds;               // [O][WP]
+    float* sb = sw + O * WP;          // [W]
+    float* sx = sb + W;               // [FN_ROWS][O]
+    const int p = blockIdx.y, m0 = blockIdx.x * FN_ROWS;
+    const T* w0 = theta_mat + (int64_t)p * mat_len + mat_off;
+    for (int idx = threadIdx.x; idx < W * O; idx += 256) {
+        const int o = idx / O, i = idx - o * O;
+        sw[i * WP + o] = to_f(w0[idx]);
+    }
+    for (int o = threadIdx.x; o < W; o += 256) sb[o] = theta_vec[(int64_t)p * vec_len + vec_off + o];
+    for (int idx = threadIdx.x; idx < FN_ROWS * O; idx += 256) {
+        const int r = idx / O, i = idx - r * O;
+        const int m = m0 + r < M ? m0 + r : M - 1;
+        sx[idx] = to_f(cvt<T>(x[rm.row(p, m) * O + i]));
+    }
+    __syncthreads();
+    const int CH = W >> 3;        // pieces of eight outputs per row (at most 256)
+    const int RPT = 256 / CH;     // rows in work at a time
+    const int chunk = threadIdx.x % CH, slot = threadIdx.x / CH;
+    if (slot >= RPT) return;
+    constexpr int TURNS = 8;      // rows per thread and pass
+    for (int r0 = 0; r0 < FN_ROWS; r0 += RPT * TURNS) {
+        float acc[TURNS][8];
+        const float4 b0 = *reinterpret_cast<const float4*>(sb + 8 * chunk), b1 = *reinterpret_cast<const float4*>(sb + 8 * chunk + 4);
+        const float* xr[TURNS];
+#pragma unroll
+        for (int t = 0; t < TURNS; ++t) {
+            acc[t][0] = b0.x; acc[t][1] = b0.y; acc[t][2] = b0.z; acc[t][3] = b0.w;
+            acc[t][4] = b1.x; acc[t][5] = b1.y; acc[t][6] = b1.z; acc[t][7] = b1.w;
+            const int r = r0 + slot + t * RPT;
+            xr[t] = sx + (r < FN_ROWS ? r : FN_ROWS - 1) * O;
+        }
+        for (int i = 0; i < O; ++i) {  // (the observation values read four steps at a time measured no faster)
+            const float4 wa = *reinterpret_cast<const float4*>(sw + i * WP + 8 * chunk);
+            const float4 wb = *reinterpret_cast<const float4*>(sw + i * WP + 8 * chunk + 4);
+#pragma unroll
+            for (int t = 0; t < TURNS; ++t) {
+                const float xv = xr[t][i];
+                acc[t][0] += xv * wa.x; acc[t][1] += xv * wa.y; acc[t][2] += xv * wa.z; acc[t][3] += xv * wa.w;
+                acc[t][4] += xv * wb.x; acc[t][5] += xv * wb.y; acc[t][6] += xv * wb.z; acc[t][7] += xv * wb.w;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TURNS; ++t) {
+            const int r = r0 + slot + t * RPT, m = m0 + r;
+            if (r < FN_ROWS && m < M) {
+                float g[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) act_pair<ACT>(acc[t][u], acc[t][u], g[u]);
+                const int64_t at = ((int64_t)p * M + m) * W + 8 * chunk;
+                put8(H + at, pack8(acc[t], (const T*)nullptr));
+                if (SAVE) put8(G + at, pack8(g, (const typename GradT<T>::type*)nullptr));
+            }
+        }
+    }
+}
+static int64_t first_fwd_narrow_lds(const morlax_ctx* c) {
+    return ((int64_t)(c->d.width + 4) * c->d.obs_dim + c->d.width + (int64_t)FN_ROWS * c->d.obs_dim) * 4;
+}
+static bool first_fwd_narrow_ok(const morlax_ctx* c) {
+    // bf16 networks only: with fp32 outputs (twice the bytes per store) the tiled kernel measured faster
+    return c->d.wdtype == 1 && c->d.obs_dim <= 32 && c->d.width % 8 == 0 && c->d.width <= 2048 &&
+           first_fwd_narrow_lds(c) <= 64 * 1024;
+}
+
 // ---- first layer with a narrow observation (O <= 32) and few preferences ----------------------------------
 // dW_0(p)[o, i] = sum_m dZ_0[m, o] x[m, i] has W x O outputs and the whole selection as its contraction: as a tiled
 // GEMM it is two or three tiles per preference walking thousands of rows each (workload 2: 32 workgroups on 256 CUs).
@@ -2111,15 +2193,26 @@ __global__ __launch_bounds__(256) void k_head_bwd_dw_final(const float* __restri
     }
 }
 
-// db_l(p)[o] = sum over the row blocks of the partial column sums of dZ_l, in block order.
+// db_l(p)[o] = sum over the row blocks of the partial column sums of dZ_l.  A block takes 32 columns of one
+// preference; its eight groups of 32 threads each add a contiguous eighth of the row blocks in order, and the eight
+// sums are added in group order (a fixed association: results repeat bit for bit).
 __global__ __launch_bounds__(256) void k_colsum_final(const float* __restrict__ part, int n_part,
                                                      float* __restrict__ dtheta_vec, int64_t vec_len,
                                                      int64_t vec_off, int W) {
-    const int p = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= W) return;
+    __shared__ float sg[8][32];
+    const int p = blockIdx.y, c = threadIdx.x & 31, g = threadIdx.x >> 5, i = blockIdx.x * 32 + c;
+    const int per = (n_part + 7) / 8, q_lo = g * per, q_hi = (q_lo + per < n_part) ? q_lo + per : n_part;
     float a = 0.f;
-    for (int q = 0; q < n_part; ++q) a += part[((int64_t)p * n_part + q) * W + i];
-    dtheta_vec[(int64_t)p * vec_len + vec_off + i] = a;
+    if (i < W)
+        for (int q = q_lo; q < q_hi; ++q) a += part[((int64_t)p * n_part + q) * W + i];
+    sg[g][c] = a;
+    __syncthreads();
+    if (g == 0 && i < W) {
+        float t = sg[0][c];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) t += sg[k][c];
+        dtheta_vec[(int64_t)p * vec_len + vec_off + i] = t;
+    }
 }
 
 __global__ void k_copy_dlogsig(const float* __restrict__ dlogsig, float* __restrict__ dtheta_vec, int64_t vec_len,
@@ -2295,6 +2388,19 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
                 g.epi = ep; g.e0_pstride = nd.vec_len; g.e1_pstride = (int64_t)M * W; g.e2_pstride = 0;
                 run_gemm(c, 0, g, P, s);
             }
+        } else if (l == 0 && first_fwd_narrow_ok(c)) {
+            const int lds = (int)first_fwd_narrow_lds(c);
+            static bool attr_set = false;
+            if (!attr_set) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_first_fwd_narrow<T, ACT, SAVE>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                attr_set = true;
+            }
+            GemmProf::Rec* r = prof_take(c, 0, 2.0 * M * (double)W * O * P);
+            if (r) (void)hipEventRecord(r->a, s);
+            k_first_fwd_narrow<T, ACT, SAVE><<<dim3((M + FN_ROWS - 1) / FN_ROWS, P), 256, lds, s>>>(
+                x, theta_mat, theta_vec, nd.mat_len, nd.vec_len, Ld.mat_off, Ld.vec_off, O, W, M, rm, Hbuf(0), Gbuf(0));
+            if (r) (void)hipEventRecord(r->b, s);
         } else if (l == 0) {
             auto launch = [&](auto fast) {
                 constexpr bool F = decltype(fast)::value;
@@ -2418,7 +2524,7 @@ static void policy_bwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
     }
     for (int l = L - 1; l >= 0; --l) {
         const LayerDev& Ld = nd.layer[l];
-        k_colsum_final<<<dim3((W + 255) / 256, P), 256, 0, s>>>(part, n_part, dtheta_vec, nd.vec_len, Ld.vec_off, W);
+        k_colsum_final<<<dim3((W + 31) / 32, P), 256, 0, s>>>(part, n_part, dtheta_vec, nd.vec_len, Ld.vec_off, W);
         EpiDw ew;
         ew.dW = dtheta_mat + Ld.mat_off;
         ew.ld = Ld.d_in;
