@@ -1227,6 +1227,8 @@ struct FusedFwdArgs {
     const float* theta_vec;   // [P][vec_len]
     int64_t mat_len, vec_len;
     int64_t mat_off[MORLAX_MAX_LAYERS], vec_off[MORLAX_MAX_LAYERS];
+    int64_t frag_len, frag_off[MORLAX_MAX_LAYERS];  // the fragment-order copy: elements per preference, layer starts
+    int32_t Opad;  // O rounded up to a multiple of 64: the first layer's contraction, zero-filled beyond O
     bf16_t* H;    // saving: h of layer l at H + l * lstride; else the last layer's h only
     gfix16_t* G;  // saving: act'(z) of layer l at G + l * lstride
     int64_t lstride;
@@ -1254,10 +1256,11 @@ __device__ inline int swap_bits23(int i) { return (i & 0x13) | ((i & 4) << 1) | 
 // One workgroup moves a super-step pair of units of one j: 32 rows x 128 bytes, whole lines in and out.
 struct FragOrderArgs {
     const bf16_t* src;  // [P][mat_len] row-major matrices
-    bf16_t* dst;        // [P][mat_len]
-    int64_t mat_len;
-    int64_t mat_off[MORLAX_MAX_LAYERS];
-    int32_t K[MORLAX_MAX_LAYERS];
+    bf16_t* dst;        // [P][frag_len]
+    int64_t mat_len, frag_len;
+    int64_t mat_off[MORLAX_MAX_LAYERS], frag_off[MORLAX_MAX_LAYERS];
+    int32_t K[MORLAX_MAX_LAYERS];     // contraction length in the copy (a multiple of 64)
+    int32_t Ksrc[MORLAX_MAX_LAYERS];  // columns of the row-major matrix; the copy is zero beyond them
     int32_t g0[MORLAX_MAX_LAYERS + 1];  // first workgroup of layer l; g0[L] = workgroups per preference
     int32_t L;
 };
@@ -1271,10 +1274,23 @@ __global__ __launch_bounds__(256) void k_theta_fragment_order(FragOrderArgs a) {
     const int v = g / per_wave, r = g % per_wave, sstep = r >> 1, j = r & 1;
     const int wq = threadIdx.x >> 6, ln = threadIdx.x & 63, ub = wq >> 1, e = wq & 1, lg = ln >> 5, lr = ln & 31;
     const int u = 2 * sstep + ub;
-    const char* W = reinterpret_cast<const char*>(a.src + (int64_t)p * a.mat_len + a.mat_off[l]);
-    char* D = reinterpret_cast<char*>(a.dst + (int64_t)p * a.mat_len + a.mat_off[l]);
+    const bf16_t* Wsrc = a.src + (int64_t)p * a.mat_len + a.mat_off[l];
+    char* D = reinterpret_cast<char*>(a.dst + (int64_t)p * a.frag_len + a.frag_off[l]);
     const int f = 64 * v + 32 * j + swap_bits23(lr);
-    const uint4 q = *reinterpret_cast<const uint4*>(W + (int64_t)f * K * 2 + sstep * 128 + ub * 32 + lg * 64 + e * 16);
+    const int k0 = (sstep * 128 + ub * 32 + lg * 64 + e * 16) >> 1, Ks = a.Ksrc[l];
+    uint4 q;
+    if (Ks == K) {
+        q = *reinterpret_cast<const uint4*>(Wsrc + (int64_t)f * K + k0);
+    } else {  // an observation width that is no multiple of 64: element by element, zeros beyond it
+        const unsigned short* row = reinterpret_cast<const unsigned short*>(Wsrc) + (int64_t)f * Ks;
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = (k0 + 2 * i < Ks) ? row[k0 + 2 * i] : 0u, hi = (k0 + 2 * i + 1 < Ks) ? row[k0 + 2 * i + 1] : 0u;
+            w[i] = lo | (hi << 16);
+        }
+        q = make_uint4(w[0], w[1], w[2], w[3]);
+    }
     *reinterpret_cast<uint4*>(D + (int64_t)v * (K >> 5) * 4096 + u * 4096 + j * 2048 + e * 1024 + ln * 16) = q;
 }
 
@@ -1299,13 +1315,13 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
         const int rows = a.M - m0 < FF_ROWS ? a.M - m0 : FF_ROWS;
         const int wn = wave * 64;
 
-        const bf16_t* Wp = a.theta_frag + (int64_t)p * a.mat_len;
+        const bf16_t* Wp = a.theta_frag + (int64_t)p * a.frag_len;
         const float* bp = a.theta_vec + (int64_t)p * a.vec_len;
         auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's place in the wave's stream of W_l(p), per feature half
-            const int K = l == 0 ? a.O : FF_W;
+            const int K = l == 0 ? a.Opad : FF_W;
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                w[j] = reinterpret_cast<const char*>(Wp + a.mat_off[l]) + (int64_t)wave * (K >> 5) * 4096 + j * 2048 +
+                w[j] = reinterpret_cast<const char*>(Wp + a.frag_off[l]) + (int64_t)wave * (K >> 5) * 4096 + j * 2048 +
                        lane * 16;
         };
         // unit u of a layer = 32 contraction indices per lane group, 4 KB of the wave's stream (fragment order)
@@ -1327,14 +1343,22 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
         {  // the tile's observations, gathered from the time-major tensor and rounded to bf16; rows past the end
            // repeat the last row (their results are never stored).  The saving variant keeps the compact copy
            // that the first layer's dW product reads.
-            const int cpr = a.O >> 3;
+            const int cpr = a.Opad >> 3;
+            const bool whole = (a.O & 7) == 0;  // rows of whole 8-value pieces (16-byte aligned: the launcher checks x)
             for (int id = threadIdx.x; id < FF_ROWS * cpr; id += 512) {
                 const int r = id / cpr, c = id % cpr, rc = r < rows ? r : rows - 1;
+                const float* xr = a.x + a.rm.row(p, m0 + rc) * a.O;
                 float v[8];
-                get8(a.x + a.rm.row(p, m0 + rc) * a.O + 8 * c, v);
+                if (whole && 8 * c < a.O) {
+                    get8(xr + 8 * c, v);
+                } else {  // a width that is no multiple of 8, or the zero fill up to Opad
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = (8 * c + e < a.O) ? xr[8 * c + e] : 0.f;
+                }
                 const uint4 q = pack_chunk<bf16_t>(v);
                 *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) = q;
-                if (SAVE && r < rows) *reinterpret_cast<uint4*>(a.x0 + ((int64_t)p * a.M + m0 + r) * a.O + 8 * c) = q;
+                if (SAVE && a.x0 && r < rows && 8 * c < a.O)
+                    *reinterpret_cast<uint4*>(a.x0 + ((int64_t)p * a.M + m0 + r) * a.O + 8 * c) = q;
             }
         }
         // fragment addresses: row 32 i + lr, chunk (8 s + 4 lg + jj) ^ (lr & 15)
@@ -1382,7 +1406,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
             // layer: a harmless, valid load), so that every pass through the loop has the same loads in flight
             const char* wq[2];
             w_rows(more ? l + 1 : l, wq);
-            const int nU = l == 0 ? a.O >> 5 : FF_W / 32;
+            const int nU = l == 0 ? a.Opad >> 5 : FF_W / 32;
             for (int u = 0; u < nU; u += 2) {
                 load_w(wfb, wp[0], wp[1], u + 1);
                 __builtin_amdgcn_sched_barrier(0);  // the requests stay ahead of the products they overlap with
@@ -2302,15 +2326,19 @@ static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
            dw_split_elems(c, rs);
 }
 static bool fused_fwd_dims_ok(const morlax_ctx* c) {
-    return c->d.wdtype == 1 && c->d.width == FF_W && c->d.obs_dim % 64 == 0 && c->d.obs_dim <= FF_W &&
-           c->d.n_hidden >= 1;
+    return c->d.wdtype == 1 && c->d.width == FF_W && c->d.obs_dim <= FF_W && c->d.n_hidden >= 1;
+}
+// elements per preference of the fused forward's copy of the matrices: the first layer's rows padded to a multiple of 64
+static int64_t fused_frag_len(const morlax_ctx* c, int net) {
+    const int Opad = (c->d.obs_dim + 63) & ~63;
+    return c->net[net].mat_len + (int64_t)FF_W * (Opad - c->d.obs_dim);
 }
 
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
     int64_t b = 2 * act_elems(c, rs) * esize(c) + part_elems(c, rs) * 4 + (use_x0(c) ? x0_elems(c, rs) * esize(c) : 0);
     if (fused_fwd_dims_ok(c)) {  // the fused forward's copy of the matrices in fragment order
         for (int net = 0; net < 2; ++net) {
-            const int64_t f = align_up((int64_t)c->d.P * c->net[net].mat_len * 2, 256);
+            const int64_t f = align_up((int64_t)c->d.P * fused_frag_len(c, net) * 2, 256);
             if (f > b) b = f;
         }
     }
@@ -2323,7 +2351,7 @@ static RowMap make_rowmap(const morlax_ctx* c, const RowSel& rs) {
     return rm;
 }
 
-// The fused forward serves bf16 networks of width 512 whose observation width is a multiple of 64.
+// The fused forward serves bf16 networks of width 512 (the observation is zero-filled to a multiple of 64 in LDS).
 static bool fused_fwd_ok(const morlax_ctx* c, const NetDev& nd, const void* theta_mat) {
     if (!fused_fwd_dims_ok(c)) return false;
     if ((reinterpret_cast<uintptr_t>(theta_mat) & 15) || (nd.mat_len & 7)) return false;
@@ -2426,19 +2454,24 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
         if (fused_fwd_ok(c, nd, theta_mat)) {
             FusedFwdArgs a;
             a.x = x;
-            a.x0 = sv ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
-                                             align_up((int64_t)P * M * OUT_PITCH * 4, 256))
-                      : nullptr;
+            a.x0 = (sv && use_x0(c)) ? reinterpret_cast<T*>(reinterpret_cast<char*>(sv) + (int64_t)2 * L * ae * sizeof(T) +
+                                                            align_up((int64_t)P * M * OUT_PITCH * 4, 256))
+                                     : nullptr;
             a.theta_mat = theta_mat; a.theta_vec = theta_vec;
+            a.Opad = (O + 63) & ~63;
+            a.frag_len = fused_frag_len(c, net);
             a.mat_len = nd.mat_len; a.vec_len = nd.vec_len;
             for (int l = 0; l < L; ++l) { a.mat_off[l] = nd.layer[l].mat_off; a.vec_off[l] = nd.layer[l].vec_off; }
             {  // the matrices the kernel streams, once more in the order of its requests
                 FragOrderArgs fo;
                 fo.src = theta_mat; fo.dst = reinterpret_cast<bf16_t*>(ws); fo.mat_len = nd.mat_len; fo.L = L;
+                fo.frag_len = a.frag_len;
                 int g = 0;
                 for (int l = 0; l < L; ++l) {
                     fo.mat_off[l] = nd.layer[l].mat_off;
-                    fo.K[l] = l == 0 ? O : FF_W;
+                    fo.frag_off[l] = a.frag_off[l] = nd.layer[l].mat_off + (l > 0 ? (int64_t)FF_W * (a.Opad - O) : 0);
+                    fo.K[l] = l == 0 ? a.Opad : FF_W;
+                    fo.Ksrc[l] = l == 0 ? O : FF_W;
                     fo.g0[l] = g;
                     g += 8 * 2 * (fo.K[l] >> 6);
                 }
