@@ -1191,10 +1191,11 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
     }
 }
 
-// ---- fused forward: observations -> every hidden layer -> output layer (bf16, width 512) --------------
+// ---- fused forward: observations -> every hidden layer -> output layer (bf16, width 512 or 256) -------
 // (paper Sec. III-C: the target network of a preference applied to that preference's environments, in the
-// rollout and in the update.)  One workgroup of eight waves carries 128 rows of one preference through the
-// whole network, tile after tile (one workgroup per CU).  The activations of the tile live in LDS (128 rows x 1 KB, 16-byte chunks XOR-swizzled by
+// rollout and in the update.)  One workgroup of W / 64 waves carries 128 rows of one preference through the
+// whole network, tile after tile (width 512: eight waves, one workgroup per CU; width 256: four waves and half the
+// tile, two per CU).  The activations of the tile live in LDS (128 rows x 2 W bytes, 16-byte chunks XOR-swizzled by
 // the row) and are rewritten in place layer after layer; HBM sees the observations once, the outputs once
 // and, in the saving variant, the stores of h and act'(z) that the backward pass reads -- never a load of
 // an activation.
@@ -1216,8 +1217,6 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
 // requests, the products, the epilogue arithmetic and a fixed part per tile (observation gather, first
 // requests, barriers).
 #define FF_ROWS 128
-#define FF_W 512
-#define FF_ACT_BYTES (FF_ROWS * FF_W * 2)
 
 struct FusedFwdArgs {
     const float* x;           // observations, time-major rows of O values
@@ -1247,7 +1246,7 @@ struct FusedFwdArgs {
 
 __device__ inline int swap_bits23(int i) { return (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
-// Fragment order of a [512][K] bf16 matrix W (K a multiple of 64): the 16-byte pieces of W in the order in
+// Fragment order of a [W][K] bf16 matrix (K a multiple of 64): the 16-byte pieces of W in the order in
 // which the fused forward requests them, so that each of its load instructions reads 1 KB of consecutive
 // addresses (eight whole cache lines) instead of 32 bytes from each of 32 rows.  Wave v of the forward owns
 // output features [64 v, 64 v + 64); its stream is K / 32 units of 4 KB; unit u holds four 1 KB blocks
@@ -1301,8 +1300,11 @@ __device__ inline int opaque(int v) {
     return v;
 }
 
-template <int ACT, bool SAVE>
-__global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
+template <int ACT, bool SAVE, int WD>
+__global__ __launch_bounds__(WD, 2) void k_mlp_fused_fwd(FusedFwdArgs a) {
+    constexpr int RB = 2 * WD;           // bytes of a tile row
+    constexpr int NW = WD / 64;          // waves: 64 output features each
+    constexpr int TILE_BYTES = FF_ROWS * RB;
     extern __shared__ __align__(16) unsigned char dlds[];
     // One workgroup per CU walks the tiles (no launch gap, no register spill in the saving variant).  Everything
     // derived from the lane is formed again for every tile behind opaque(): kept across tiles it would occupy
@@ -1318,7 +1320,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
         const bf16_t* Wp = a.theta_frag + (int64_t)p * a.frag_len;
         const float* bp = a.theta_vec + (int64_t)p * a.vec_len;
         auto w_rows = [&](int l, const char* (&w)[2]) {  // the lane's place in the wave's stream of W_l(p), per feature half
-            const int K = l == 0 ? a.Opad : FF_W;
+            const int K = l == 0 ? a.Opad : WD;
 #pragma unroll
             for (int j = 0; j < 2; ++j)
                 w[j] = reinterpret_cast<const char*>(Wp + a.frag_off[l]) + (int64_t)wave * (K >> 5) * 4096 + j * 2048 +
@@ -1345,7 +1347,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
            // that the first layer's dW product reads.
             const int cpr = a.Opad >> 3;
             const bool whole = (a.O & 7) == 0;  // rows of whole 8-value pieces (16-byte aligned: the launcher checks x)
-            for (int id = threadIdx.x; id < FF_ROWS * cpr; id += 512) {
+            for (int id = threadIdx.x; id < FF_ROWS * cpr; id += WD) {
                 const int r = id / cpr, c = id % cpr, rc = r < rows ? r : rows - 1;
                 const float* xr = a.x + a.rm.row(p, m0 + rc) * a.O;
                 float v[8];
@@ -1356,14 +1358,14 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
                     for (int e = 0; e < 8; ++e) v[e] = (8 * c + e < a.O) ? xr[8 * c + e] : 0.f;
                 }
                 const uint4 q = pack_chunk<bf16_t>(v);
-                *reinterpret_cast<uint4*>(dlds + r * 1024 + ((c ^ (r & 15)) * 16)) = q;
+                *reinterpret_cast<uint4*>(dlds + r * RB + ((c ^ (r & 15)) * 16)) = q;
                 if (SAVE && a.x0 && r < rows && 8 * c < a.O)
                     *reinterpret_cast<uint4*>(a.x0 + ((int64_t)p * a.M + m0 + r) * a.O + 8 * c) = q;
             }
         }
         // fragment addresses: row 32 i + lr, chunk (8 s + 4 lg + jj) ^ (lr & 15)
         const int x = lr & 15;
-        const unsigned char* arow = dlds + lr * 1024;
+        const unsigned char* arow = dlds + lr * RB;
         uint32_t aoff[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) aoff[jj] = (uint32_t)(((4 * lg + jj) ^ (x & 7)) * 16);
@@ -1377,7 +1379,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) fa[jj][i] = *reinterpret_cast<const uint4*>(as + i * 32768 + aoff[2 * HALF + jj]);
+                for (int i = 0; i < 4; ++i) fa[jj][i] = *reinterpret_cast<const uint4*>(as + i * (32 * RB) + aoff[2 * HALF + jj]);
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
@@ -1406,7 +1408,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
             // layer: a harmless, valid load), so that every pass through the loop has the same loads in flight
             const char* wq[2];
             w_rows(more ? l + 1 : l, wq);
-            const int nU = l == 0 ? a.Opad >> 5 : FF_W / 32;
+            const int nU = l == 0 ? a.Opad >> 5 : WD / 32;
             for (int u = 0; u < nU; u += 2) {
                 load_w(wfb, wp[0], wp[1], u + 1);
                 __builtin_amdgcn_sched_barrier(0);  // the requests stay ahead of the products they overlap with
@@ -1422,10 +1424,10 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
             const float bnext = load_bias(more ? l + 1 : l);
             {
                 const int ol = opaque(lane), olr = ol & 31, olg = ol >> 5, ox = ol & 15;
-                unsigned char* hrow = dlds + olr * 1024;
-                unsigned char* patch = dlds + FF_ACT_BYTES + wave * 4096;
-                gfix16_t* Gl = SAVE ? a.G + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
-                bf16_t* Hl = SAVE ? a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * FF_W + wn : nullptr;
+                unsigned char* hrow = dlds + olr * RB;
+                unsigned char* patch = dlds + TILE_BYTES + wave * 4096;
+                gfix16_t* Gl = SAVE ? a.G + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * WD + wn : nullptr;
+                bf16_t* Hl = SAVE ? a.H + (int64_t)l * a.lstride + ((int64_t)p * a.M + m0) * WD + wn : nullptr;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     uint4 gq[4], hq[4];
@@ -1437,7 +1439,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
                         for (int u = 0; u < 8; ++u) act_pair<ACT>(acc[i][j][8 * h + u], v[u], g[u]);
                         const int cc = 8 * wave + 4 * j + 2 * h + olg;
                         hq[o] = pack_chunk<bf16_t>(v);
-                        *reinterpret_cast<uint4*>(hrow + i * 32768 + ((cc ^ ox) * 16)) = hq[o];
+                        *reinterpret_cast<uint4*>(hrow + i * (32 * RB) + ((cc ^ ox) * 16)) = hq[o];
                         if (SAVE) gq[o] = pack8(g, (const gfix16_t*)nullptr).lo;
                     }
                     // act'(z) and h leave through the wave's patch as whole 128-byte row segments, row block by row
@@ -1459,7 +1461,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
                                 const int prow = it * 8 + (ol >> 3), pc = ol & 7;
                                 const uint4 u = *reinterpret_cast<const uint4*>(patch + prow * 128 + ((pc ^ (prow & 7)) * 16));
                                 const int gr = 32 * i + prow;
-                                if (gr < rows) *reinterpret_cast<uint4*>(dst + ((int64_t)gr * FF_W + pc * 8) * 2) = u;
+                                if (gr < rows) *reinterpret_cast<uint4*>(dst + ((int64_t)gr * WD + pc * 8) * 2) = u;
                             }
                             __builtin_amdgcn_wave_barrier();
                         }
@@ -1472,15 +1474,18 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
 
         // output layer: wave w takes rows 16 w .. 16 w + 15 of the tile with 16x16x32 products; lane (hl, hg)
         // supplies row hl / output hl at contraction chunk 4 u + hg and receives output hl of rows 4 hg + e
-        {
+        // (width 256: four waves, two passes of 64 rows)
+#pragma unroll
+        for (int pass = 0; pass < 8 / NW; ++pass) {
             const int hl = lane & 15, hg = lane >> 4;
-            const int r = 16 * wave + hl;
-            const unsigned char* hrow = dlds + r * 1024;
-            const bf16_t* wrow = a.theta_mat + (int64_t)p * a.mat_len + a.head_mat_off + (int64_t)hl * FF_W;
+            const int wv = wave + NW * pass;
+            const int r = 16 * wv + hl;
+            const unsigned char* hrow = dlds + r * RB;
+            const bf16_t* wrow = a.theta_mat + (int64_t)p * a.mat_len + a.head_mat_off + (int64_t)hl * WD;
             const bool b_ok = hl < a.out_dim;
             float4_t c = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
+            for (int half = 0; half < WD / 256; ++half) {
                 uint4 fa[8], fb[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
@@ -1503,7 +1508,7 @@ __global__ __launch_bounds__(512) void k_mlp_fused_fwd(FusedFwdArgs a) {
             if (a.eps && a_ok && !a.sig_state) ls_p = bp[a.logsig_off + hl];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int tr = 16 * wave + 4 * hg + e, m = m0 + tr;
+                const int tr = 16 * wv + 4 * hg + e, m = m0 + tr;
                 const bool ok = (tr < rows) && b_ok;
                 const float z = c[e] + bias;
                 const float o = (hl < a.tanh_cols) ? tanhf(z) : z;
@@ -2326,12 +2331,13 @@ static int64_t part_elems(const morlax_ctx* c, const RowSel& rs) {
            dw_split_elems(c, rs);
 }
 static bool fused_fwd_dims_ok(const morlax_ctx* c) {
-    return c->d.wdtype == 1 && c->d.width == FF_W && c->d.obs_dim <= FF_W && c->d.n_hidden >= 1;
+    return c->d.wdtype == 1 && (c->d.width == 512 || c->d.width == 256) && c->d.obs_dim <= c->d.width &&
+           c->d.n_hidden >= 1;
 }
 // elements per preference of the fused forward's copy of the matrices: the first layer's rows padded to a multiple of 64
 static int64_t fused_frag_len(const morlax_ctx* c, int net) {
     const int Opad = (c->d.obs_dim + 63) & ~63;
-    return c->net[net].mat_len + (int64_t)FF_W * (Opad - c->d.obs_dim);
+    return c->net[net].mat_len + (int64_t)c->d.width * (Opad - c->d.obs_dim);
 }
 
 int64_t mlp_ws_bytes(const morlax_ctx* c, const RowSel& rs) {
@@ -2351,7 +2357,7 @@ static RowMap make_rowmap(const morlax_ctx* c, const RowSel& rs) {
     return rm;
 }
 
-// The fused forward serves bf16 networks of width 512 (the observation is zero-filled to a multiple of 64 in LDS).
+// The fused forward serves bf16 networks of width 512 or 256 (the observation is zero-filled to a multiple of 64 in LDS).
 static bool fused_fwd_ok(const morlax_ctx* c, const NetDev& nd, const void* theta_mat) {
     if (!fused_fwd_dims_ok(c)) return false;
     if ((reinterpret_cast<uintptr_t>(theta_mat) & 15) || (nd.mat_len & 7)) return false;
@@ -2360,21 +2366,27 @@ static bool fused_fwd_ok(const morlax_ctx* c, const NetDev& nd, const void* thet
     return true;
 }
 
-template <int ACT, bool SAVE>
-static void launch_fused_fwd(const morlax_ctx* c, const FusedFwdArgs& a, hipStream_t s) {
-    constexpr int lds = FF_ACT_BYTES + (SAVE ? 8 * 4096 : 0);
+template <int ACT, bool SAVE, int WD>
+static void launch_fused_fwd_w(const morlax_ctx* c, const FusedFwdArgs& a, hipStream_t s) {
+    constexpr int lds = FF_ROWS * WD * 2 + (SAVE ? (WD / 64) * 4096 : 0);
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mlp_fused_fwd<ACT, SAVE>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mlp_fused_fwd<ACT, SAVE, WD>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
-    const double per_row = 2.0 * FF_W * ((double)a.O + (double)(a.L - 1) * FF_W);
+    const double per_row = 2.0 * WD * ((double)a.O + (double)(a.L - 1) * WD);
     GemmProf::Rec* r = prof_take(c, 5, per_row * a.M * c->d.P);
     if (r) (void)hipEventRecord(r->a, s);
-    const int cus = resident_slots() / 2;  // one workgroup per CU (the tile fills its LDS)
-    k_mlp_fused_fwd<ACT, SAVE><<<a.n_tiles < cus ? a.n_tiles : cus, 512, lds, s>>>(a);
+    // width 512: one workgroup per CU (the tile fills its LDS); width 256: half the tile and half the waves, two per CU
+    const int slots = resident_slots() / 2 * (512 / WD);
+    k_mlp_fused_fwd<ACT, SAVE, WD><<<a.n_tiles < slots ? a.n_tiles : slots, WD, lds, s>>>(a);
     if (r) (void)hipEventRecord(r->b, s);
+}
+template <int ACT, bool SAVE>
+static void launch_fused_fwd(const morlax_ctx* c, const FusedFwdArgs& a, hipStream_t s) {
+    if (c->d.width == 256) launch_fused_fwd_w<ACT, SAVE, 256>(c, a, s);
+    else launch_fused_fwd_w<ACT, SAVE, 512>(c, a, s);
 }
 
 template <typename T>
@@ -2469,11 +2481,11 @@ static void policy_fwd_t(const morlax_ctx* c, int net, const T* theta_mat, const
                 int g = 0;
                 for (int l = 0; l < L; ++l) {
                     fo.mat_off[l] = nd.layer[l].mat_off;
-                    fo.frag_off[l] = a.frag_off[l] = nd.layer[l].mat_off + (l > 0 ? (int64_t)FF_W * (a.Opad - O) : 0);
-                    fo.K[l] = l == 0 ? a.Opad : FF_W;
-                    fo.Ksrc[l] = l == 0 ? O : FF_W;
+                    fo.frag_off[l] = a.frag_off[l] = nd.layer[l].mat_off + (l > 0 ? (int64_t)W * (a.Opad - O) : 0);
+                    fo.K[l] = l == 0 ? a.Opad : W;
+                    fo.Ksrc[l] = l == 0 ? O : W;
                     fo.g0[l] = g;
-                    g += 8 * 2 * (fo.K[l] >> 6);
+                    g += (W / 64) * 2 * (fo.K[l] >> 6);
                 }
                 fo.g0[L] = g;
                 k_theta_fragment_order<<<dim3(g, P), 256, 0, s>>>(fo);

@@ -67,6 +67,13 @@ RAGGED_FUSED_WIDE = scaled(RAGGED_FUSED, name="ragged-fused-bf16-obs512", obs_di
 # next multiple (27 and 45: element-wise gather, narrow and general first-layer dW; 100: a multiple of 4 only;
 # 72: whole 8-value pieces without the gathered copy; 96: with the gathered copy that the first layer's dW reads)
 FUSED_ODD_OBS = [scaled(RAGGED_FUSED, name=f"ragged-fused-bf16-obs{o}", obs_dim=o) for o in (27, 45, 72, 96, 100)]
+# the fused forward at width 256 (four waves, two output-layer passes per tile): the widest observation it takes,
+# a multiple of 64, a narrow odd one, tanh, and the state-dependent sigma
+FUSED_W256 = [scaled(RAGGED_FUSED, name="ragged-fused-w256-obs256", width=256, obs_dim=256),
+              scaled(RAGGED_FUSED, name="ragged-fused-w256-obs64", width=256, obs_dim=64, n_hidden=4),
+              scaled(RAGGED_FUSED, name="ragged-fused-w256-obs11", width=256, obs_dim=11),
+              scaled(RAGGED_FUSED_TANH, name="ragged-fused-w256-tanh", width=256, obs_dim=128, n_hidden=2),
+              scaled(RAGGED_FUSED, name="ragged-fused-w256-sigma", width=256, obs_dim=40, sigma_state=1)]
 # state-dependent standard deviation (the actor's output layer is 2A wide): fp32, the widest allowed (2A = 16),
 # a ragged fp32 case, and the fused bf16 forward
 SIGMA_CASES = [scaled(CONFIGS[1], name="cfg1-sigma", sigma_state=1), scaled(CONFIGS[2], name="cfg2-sigma", sigma_state=1),
@@ -434,7 +441,8 @@ FWD_CASES = [(CONFIGS[1], None), (CONFIGS[1], (3, 9, 5, 7)), (RAGGED, None), (RA
              (CONFIGS[4], None), (CONFIGS[5], None), (CONFIGS[5], "mb"), (RAGGED_FUSED, None),
              (RAGGED_FUSED, (2, 5, 3, 30)), (RAGGED_FUSED_TANH, None)] + [(c, None) for c in SIGMA_CASES] + \
             [(SIGMA_CASES[2], (1, 5, 2, 19)), (RAGGED_FUSED, (3, 1, 5, 1)), (RAGGED_FUSED_WIDE, None), (LIMITS_BF16, None)] + \
-            RANDOM_FUSED + [(c, None) for c in FUSED_ODD_OBS] + [(FUSED_ODD_OBS[0], (2, 5, 3, 30))]
+            RANDOM_FUSED + [(c, None) for c in FUSED_ODD_OBS] + [(FUSED_ODD_OBS[0], (2, 5, 3, 30))] + \
+            [(c, None) for c in FUSED_W256] + [(FUSED_W256[2], (2, 5, 3, 30)), (FUSED_W256[0], (3, 1, 5, 1))]
 
 
 @pytest.mark.parametrize("cfg,rows", FWD_CASES, ids=lambda x: getattr(x, "name", str(x)))
@@ -503,7 +511,8 @@ BWD_CASES = [(CONFIGS[1], None), (RAGGED, None), (RAGGED, (1, 5, 2, 19)), (RAGGE
              (CONFIGS[5], "mb"), (RAGGED_FUSED, None), (RAGGED_FUSED_TANH, (1, 6, 0, 37))] + \
             [(c, None) for c in SIGMA_CASES] + \
             [(RAGGED_FUSED, (3, 1, 5, 1)), (scaled(RAGGED_FUSED_WIDE, name="ragged-fused-bf16-obs512-3layers", n_hidden=3), None)] + \
-            RANDOM_FUSED + [(LIMITS_BF16, None)] + [(c, None) for c in FUSED_ODD_OBS] + [(FUSED_ODD_OBS[1], (2, 5, 3, 30))]
+            RANDOM_FUSED + [(LIMITS_BF16, None)] + [(c, None) for c in FUSED_ODD_OBS] + [(FUSED_ODD_OBS[1], (2, 5, 3, 30))] + \
+            [(c, None) for c in FUSED_W256] + [(FUSED_W256[1], (2, 5, 3, 30))]
 # (the eight-layer network has a test of its own below, test_policy_bwd_eight_hidden_layers_bf16)
 
 
@@ -823,6 +832,7 @@ def test_update_step_fp32_matches_oracle(cfg, torch, binding):
 @pytest.mark.parametrize("cfg", [scaled(RAGGED_BF16, name="ragged-bf16-step", minibatches=2), RAGGED_PERS, CONFIGS[3],
                                  scaled(RAGGED_FUSED, name="ragged-fused-step", minibatches=1, epochs=1),
                                  scaled(FUSED_ODD_OBS[0], name="ragged-fused-obs27-step", minibatches=1, epochs=1),
+                                 scaled(FUSED_W256[2], name="ragged-fused-w256-obs11-step", minibatches=1, epochs=1),
                                  scaled(RAGGED_FUSED, name="ragged-fused-sigma-step", minibatches=1, epochs=1,
                                         sigma_state=1)],
                          ids=lambda c: c.name)
