@@ -1130,12 +1130,28 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        uint4 first[4] = {};
         for (int kt = 0; kt < nk; ++kt) {
             // a wave has kLoads loads per stage in flight.  At the first step of a tile the stores of the
             // previous epilogue may still be counted as well, so everything is waited for.
             if (kt == 0 || kt == nk - 1) wait_vm<0>();
             else wait_vm<S::kLoads>();
             __syncthreads();  // stage kt is complete, and stage kt - 1 (or the last epilogue's patch) is free
+            if constexpr (Epi::kPrefetch) {
+                // the epilogue's first block of act'(z): requested behind the tile's last operand stage, during the
+                // last contraction step (after the products it cost 0.2 ms more per step of workload 5; two or four
+                // steps earlier measured no better)
+                if (kt == nk - 1) {
+                    Epi epi0 = g.epi;
+                    shift_epi(epi0, p, g.e0_pstride, g.e1_pstride, g.e2_pstride);
+                    const int r = tm * PG_TM + wm + (threadIdx.x & 31), rc = r < g.a.rows ? r : g.a.rows - 1;
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        const int c = tn * TN + wn + 16 * o + 8 * ((threadIdx.x & 63) >> 5);
+                        first[o] = epi0.fetch(rc, c < g.b.rows ? c : 0);
+                    }
+                }
+            }
             if (kt + PG_NST - 1 < nk) {
                 const uint32_t tile = lbase + (uint32_t)((kt + PG_NST - 1) % PG_NST) * S::kStage;
                 A.issue(kt + PG_NST - 1, tile);
@@ -1168,16 +1184,6 @@ __global__ __launch_bounds__(2 * TN, 2) void k_gemm_pers(GemmArgs<bf16_t, KA, KB
         const float* lds_bias = reinterpret_cast<const float*>(dlds + S::kLds + bslot * (4 * TN));
         Epi epi = g.epi;
         shift_epi(epi, pc, g.e0_pstride, g.e1_pstride, g.e2_pstride);
-        uint4 first[4] = {};
-        if constexpr (Epi::kPrefetch) {
-            // ahead of the next tile's operand loads, which would otherwise be returned first
-            const int r = tmc * PG_TM + wm + (threadIdx.x & 31), rc = r < g.a.rows ? r : g.a.rows - 1;
-#pragma unroll
-            for (int o = 0; o < 4; ++o) {
-                const int c = tnc * TN + wn + 16 * o + 8 * ((threadIdx.x & 63) >> 5);
-                first[o] = epi.fetch(rc, c < g.b.rows ? c : 0);
-            }
-        }
         vid += gridDim.x;
         const bool more = vid < n_tiles;
         if (more) {
