@@ -542,9 +542,15 @@ def test_policy_bwd_matches_oracle(cfg, rows, torch, binding):
         ctx.policy_fwd(net, d_tm, d_tv, d_x, rows, out, saved=saved, ws=ws)
         dtm = torch.full((cfg.P, ctx.theta_mat_len(net)), 5.0, device="cuda")
         dtv = torch.full((cfg.P, ctx.theta_vec_len(net)), 5.0, device="cuda")
-        ctx.policy_bwd(net, d_tm, d_tv, d_x, rows, saved, dev(dout), dev(dls) if dls is not None else None, dtm,
-                       dtv, ws)
+        d_dout, d_dls = dev(dout), (dev(dls) if dls is not None else None)
+        ctx.policy_bwd(net, d_tm, d_tv, d_x, rows, saved, d_dout, d_dls, dtm, dtv, ws)
+        # every sum of the backward pass has a fixed order (split contractions and partial sums included): a second
+        # call on the same saved activations returns the same bits
+        dtm2, dtv2 = torch.full_like(dtm, -3.0), torch.full_like(dtv, -3.0)
+        ctx.policy_bwd(net, d_tm, d_tv, d_x, rows, saved, d_dout, d_dls, dtm2, dtv2, ws)
         torch.cuda.synchronize()
+        assert torch.equal(dtm, dtm2) and torch.equal(dtv, dtv2)
+        del dtm2, dtv2
         emu = cfg.wdtype == 1
         o_dtm, o_dtv = orc.policy_bwd(cfg, net, tm, tv.astype(np.float32), x, rows, dout, dls, emulate_bf16=emu,
                                       prefs=prefs)
