@@ -1654,8 +1654,10 @@ static bool launch_dma(GemmArgs<T, KA, KB, Epi, FAST, NCH>& g, int P, int nb, hi
         };
         if (g.a.rows >= 64) {
             const int slots = resident_slots();
-            // (with fewer than four wide tiles per workgroup the narrow shape measured faster: dW at W = 512)
-            if (g.b.rows >= 256 && ptm * ((g.b.rows + 255) / 256) * P >= 4 * (slots / 2)) {
+            // (the wide shape as soon as there is a tile per CU: a third fewer operand bytes per product through the
+            // vector cache, whose requests in flight are what the products wait for; dW at W = 512 with two tiles per
+            // workgroup: 8.3 -> 7.9 ms per step of workload 5, with one tile per workgroup at workload 4: 0.945 -> 0.915)
+            if (g.b.rows >= 256 && ptm * ((g.b.rows + 255) / 256) * P >= slots / 2) {
                 launch_pers(std::integral_constant<int, 256>{}, slots / 2);
                 return true;
             }
